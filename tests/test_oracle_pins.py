@@ -1,0 +1,350 @@
+"""Pins for the CPU oracle: each test checks oracle/ against something other than itself --
+closed forms, invariants, finite differences, brute force, hand-worked fixtures, or a library
+routine -- so that a dropped term, wrong sign, wrong index or transposed operand fails one."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2312_17482_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _case(seed, lengths, L, H, D, std=1.0):
+    c = wl.random_attention_case(seed, lengths, L, H, D, std)
+    rng = np.random.default_rng(seed + 7)
+    c["slopes"] = rng.uniform(0.01, 0.7, size=H)
+    return c
+
+
+# ---------------------------------------------------------------- P1: softmax rows, LSE
+def test_rows_sum_to_one_and_lse_consistent():
+    c = _case(1, [5, 17, 32, 9, 1], 32, 3, 8)
+    O, LSE, P = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"], return_probs=True)
+    pos = np.arange(32)
+    for b, n in enumerate(c["lengths"]):
+        assert np.allclose(P[b, :, :n, :].sum(-1), 1.0, atol=1e-14)
+        assert np.all(P[b, :, :, n:] == 0) and np.all(P[b, :, n:, :] == 0)
+        for h in range(3):
+            q, k = c["q"][b, :n, h].astype(np.float64), c["k"][b, :n, h].astype(np.float64)
+            S = c["scale"] * np.einsum("id,jd->ij", q, k) - c["slopes"][h] * np.abs(pos[:n, None] - pos[None, :n])
+            assert np.allclose(np.exp(S - LSE[b, h, :n, None]), P[b, h, :n, :n], atol=1e-13)
+
+
+# ---------------------------------------------------------------- P2: length-1 sequence
+def test_length_one_sequence():
+    c = _case(2, [1, 1], 8, 2, 4)
+    O, LSE = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    dQ, dK, dV = orc.attention_bwd(c["do"], c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    for b in range(2):
+        assert np.allclose(O[b, 0], c["v"][b, 0], atol=1e-15)
+        assert np.allclose(LSE[b, :, 0], c["scale"] * np.sum(c["q"][b, 0].astype(np.float64) * c["k"][b, 0], axis=-1))
+        assert np.allclose(dV[b, 0], c["do"][b, 0])
+        assert np.all(dQ[b] == 0) and np.all(dK[b] == 0)
+        assert np.all(O[b, 1:] == 0) and np.all(dV[b, 1:] == 0)
+
+
+# ---------------------------------------------------------------- P3: zero slopes, identical keys
+def test_zero_slope_identical_keys_gives_mean_of_v():
+    c = _case(3, [7, 12], 12, 2, 4)
+    c["k"][:] = c["k"][:, :1]            # every key equals the first key of its sequence
+    O, _ = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], np.zeros(2), c["scale"])
+    for b, n in enumerate(c["lengths"]):
+        mean_v = c["v"][b, :n].astype(np.float64).mean(axis=0)
+        assert np.allclose(O[b, :n], mean_v[None], atol=1e-14)
+
+
+# ---------------------------------------------------------------- P4: padding is inert
+def test_padding_content_and_width_do_not_matter():
+    lengths = [5, 17, 32, 9]
+    c = _case(4, lengths, 32, 2, 8)
+    args = (c["mask"], c["slopes"], c["scale"])
+    O, LSE = orc.attention_fwd(c["q"], c["k"], c["v"], *args)
+    grads = orc.attention_bwd(c["do"], c["q"], c["k"], c["v"], *args)
+    # (a) poison pads with NaN, (b) widen L to 40
+    big = {}
+    for key in ("q", "k", "v", "do"):
+        t = np.full((4, 40, 2, 8), np.nan, dtype=np.float64)
+        for b, n in enumerate(lengths):
+            t[b, :n] = c[key][b, :n]
+        big[key] = t
+    mask40 = wl.suffix_mask(np.array(lengths), 40)
+    O2, LSE2 = orc.attention_fwd(big["q"], big["k"], big["v"], mask40, c["slopes"], c["scale"])
+    grads2 = orc.attention_bwd(big["do"], big["q"], big["k"], big["v"], mask40, c["slopes"], c["scale"])
+    for b, n in enumerate(lengths):
+        assert np.array_equal(O2[b, :n], O[b, :n]) and np.all(O2[b, n:] == 0)
+        assert np.array_equal(LSE2[b, :, :n], LSE[b, :, :n])
+        for g2, g in zip(grads2, grads):
+            assert np.allclose(g2[b, :n], g[b, :n], atol=1e-14) and np.all(g2[b, n:] == 0)
+    # (c) each sequence alone, unpadded, dense: same numbers
+    for b, n in enumerate(lengths):
+        one = {k_: c[k_][b:b + 1, :n] for k_ in ("q", "k", "v", "do")}
+        m1 = np.ones((1, n), dtype=np.int32)
+        O1, LSE1 = orc.attention_fwd(one["q"], one["k"], one["v"], m1, c["slopes"], c["scale"])
+        g1 = orc.attention_bwd(one["do"], one["q"], one["k"], one["v"], m1, c["slopes"], c["scale"])
+        assert np.allclose(O1[0], O[b, :n], atol=1e-14)
+        assert np.allclose(LSE1[0], LSE[b, :, :n], atol=1e-14)
+        for x1, x in zip(g1, grads):
+            assert np.allclose(x1[0], x[b, :n], atol=1e-13)
+
+
+# ---------------------------------------------------------------- P5: closed form for the ALiBi bias
+@pytest.mark.parametrize("n,m", [(1, 0.3), (6, 0.25), (19, 2.0 ** -4), (32, 0.9)])
+def test_alibi_closed_form_identical_keys(n, m):
+    """All keys equal => scores are c - m|i-j|; with r = exp(-m) and 1-based i,
+    Z_i = (1 + r - r^i - r^(n+1-i)) / (1 - r), P_ij = r^|i-j| / Z_i, LSE_i = c + ln Z_i."""
+    rng = np.random.default_rng(5)
+    D, L = 4, n + 3
+    q = rng.standard_normal((1, L, 1, D))
+    k = np.broadcast_to(rng.standard_normal((1, 1, 1, D)), (1, L, 1, D)).copy()
+    v = rng.standard_normal((1, L, 1, D))
+    mask = wl.suffix_mask(np.array([n]), L)
+    scale = 0.37
+    O, LSE, P = orc.attention_fwd(q, k, v, mask, np.array([m]), scale, return_probs=True)
+    r = np.exp(-m)
+    i = np.arange(1, n + 1, dtype=np.float64)
+    Z = (1 + r - r ** i - r ** (n + 1 - i)) / (1 - r)
+    dist = np.abs(i[:, None] - i[None, :])
+    P_ref = r ** dist / Z[:, None]
+    c = scale * np.einsum("id,d->i", q[0, :n, 0], k[0, 0, 0])
+    assert np.allclose(P[0, 0, :n, :n], P_ref, atol=1e-14)
+    assert np.allclose(LSE[0, 0, :n], c + np.log(Z), atol=1e-13)
+    assert np.allclose(O[0, :n, 0], P_ref @ v[0, :n, 0], atol=1e-14)
+    # the bias must favour near tokens: weights decay monotonically away from the diagonal
+    if n >= 3:
+        assert P[0, 0, 0, 0] > P[0, 0, 0, 1] > P[0, 0, 0, 2]
+        assert P[0, 0, n - 1, n - 1] > P[0, 0, n - 1, n - 2] > P[0, 0, n - 1, n - 3]
+
+
+# ---------------------------------------------------------------- P6: slopes
+def test_slopes_match_fixture():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "alibi_slopes.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) > 20
+    for n, h, p, q in rows:
+        n, h, p, q = int(n), int(h), int(p), int(q)
+        got = orc.alibi_slopes(n)
+        assert got.shape == (n,)
+        expect = 2.0 ** (-(p / q))
+        assert abs(got[h - 1] - expect) <= 1e-15 * expect
+        if q == 1:
+            assert got[h - 1] == 2.0 ** (-p)             # exact power of two
+    s = orc.alibi_slopes(12)
+    assert np.allclose(s[1:] / s[:-1], 2.0 ** (-8 / 12), rtol=1e-14)   # the stated ratio
+    assert s[0] == s[1] / s[0] or abs(s[0] - s[1] / s[0]) < 1e-15       # first term = ratio
+
+
+# ---------------------------------------------------------------- P7: symmetry
+def test_reversal_symmetry_and_permutation_invariance():
+    lengths = [11, 6]
+    c = _case(7, lengths, 11, 2, 4)
+    O, LSE = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    rev = {}
+    for key in ("q", "k", "v"):
+        t = c[key].copy()
+        for b, n in enumerate(lengths):
+            t[b, :n] = c[key][b, :n][::-1]
+        rev[key] = t
+    Or, LSEr = orc.attention_fwd(rev["q"], rev["k"], rev["v"], c["mask"], c["slopes"], c["scale"])
+    for b, n in enumerate(lengths):
+        assert np.allclose(Or[b, :n], O[b, :n][::-1], atol=1e-14)
+        assert np.allclose(LSEr[b, :, :n], LSE[b, :, :n][:, ::-1], atol=1e-14)
+    # zero slopes: jointly permuting keys and values changes nothing
+    zero = np.zeros(2)
+    O0, _ = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], zero, c["scale"])
+    perm = np.random.default_rng(0).permutation(6)
+    k2, v2 = c["k"].copy(), c["v"].copy()
+    k2[1, :6] = c["k"][1, :6][perm]
+    v2[1, :6] = c["v"][1, :6][perm]
+    O1, _ = orc.attention_fwd(c["q"], k2, v2, c["mask"], zero, c["scale"])
+    assert np.allclose(O1, O0, atol=1e-14)
+    # ... but with a nonzero slope it must change (the bias sees positions)
+    O2, _ = orc.attention_fwd(c["q"], k2, v2, c["mask"], c["slopes"], c["scale"])
+    assert np.abs(O2[1, :6] - O[1, :6]).max() > 1e-3
+
+
+# ---------------------------------------------------------------- P8: finite differences
+def _loss(q, k, v, do, mask, slopes, scale):
+    O, _ = orc.attention_fwd(q, k, v, mask, slopes, scale)
+    return float(np.sum(O * np.where(mask[:, :, None, None] != 0, do, 0.0)))
+
+
+@pytest.mark.parametrize("which", ["tiny", "random"])
+def test_backward_matches_central_differences(which):
+    if which == "tiny":
+        b = wl.make_batch("tiny")
+        slopes = orc.alibi_slopes(2)
+        q, k, v, do = (b[x].astype(np.float64) for x in ("q", "k", "v", "do"))
+        mask, scale = b["mask"], b["scale"]
+    else:
+        c = _case(8, [3, 9, 1, 6], 9, 3, 5)
+        slopes = c["slopes"]
+        q, k, v, do = (c[x].astype(np.float64) for x in ("q", "k", "v", "do"))
+        mask, scale = c["mask"], 0.61
+    dQ, dK, dV = orc.attention_bwd(do, q, k, v, mask, slopes, scale)
+    rng = np.random.default_rng(11)
+    eps = 1e-5
+    for name, X, G in (("q", q, dQ), ("k", k, dK), ("v", v, dV)):
+        # directional derivatives along random directions + a few single coordinates
+        for trial in range(6):
+            if trial < 3:
+                U = rng.standard_normal(X.shape)
+            else:
+                U = np.zeros_like(X)
+                bb = int(rng.integers(X.shape[0]))
+                n = int(np.count_nonzero(mask[bb]))
+                U[bb, int(rng.integers(n)), int(rng.integers(X.shape[2])), int(rng.integers(X.shape[3]))] = 1.0
+            args = {"q": q, "k": k, "v": v}
+            plus, minus = dict(args), dict(args)
+            plus[name] = X + eps * U
+            minus[name] = X - eps * U
+            fd = (_loss(plus["q"], plus["k"], plus["v"], do, mask, slopes, scale)
+                  - _loss(minus["q"], minus["k"], minus["v"], do, mask, slopes, scale)) / (2 * eps)
+            an = float(np.sum(G * U))
+            assert abs(fd - an) <= 1e-7 * max(1.0, abs(an)), (name, trial, fd, an)
+    # gradient is exactly zero at padded positions
+    for G in (dQ, dK, dV):
+        assert np.all(G[mask == 0] == 0)
+
+
+# ---------------------------------------------------------------- P9: backward identities
+def test_backward_identities():
+    lengths = [9, 4, 13]
+    c = _case(9, lengths, 13, 2, 6)
+    dQ, dK, dV = orc.attention_bwd(c["do"], c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    q, k, do = (c[x].astype(np.float64) for x in ("q", "k", "do"))
+    for b, n in enumerate(lengths):
+        for h in range(2):
+            # loss depends on q, k only through q k^T  =>  <q, dq> = <k, dk>
+            assert np.isclose(np.sum(q[b, :n, h] * dQ[b, :n, h]), np.sum(k[b, :n, h] * dK[b, :n, h]), atol=1e-12)
+            # rows of P sum to one  =>  sum_j dV_j = sum_i dO_i
+            assert np.allclose(dV[b, :n, h].sum(0), do[b, :n, h].sum(0), atol=1e-12)
+    # adding a constant vector to every key of a sequence shifts each score row by a constant:
+    # softmax is unchanged, so dQ.(that vector) summed over ... => sum_j dK_j = 0 per (b, h)
+    for b, n in enumerate(lengths):
+        assert np.allclose(dK[b, :n].sum(0), 0.0, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P10: library routine
+def test_forward_and_backward_match_torch_sdpa_fp64():
+    lengths = [10, 7]
+    L, H, D = 10, 3, 8
+    c = _case(10, lengths, L, H, D)
+    slopes, scale = c["slopes"], c["scale"]
+    O, _ = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], slopes, scale)
+    dQ, dK, dV = orc.attention_bwd(c["do"], c["q"], c["k"], c["v"], c["mask"], slopes, scale)
+    for b, n in enumerate(lengths):
+        tq, tk, tv = (torch.tensor(c[x][b, :n].astype(np.float64)).permute(1, 0, 2).contiguous().requires_grad_(True)
+                      for x in ("q", "k", "v"))                                      # [H, n, D]
+        pos = torch.arange(n, dtype=torch.float64)
+        bias = -torch.tensor(slopes)[:, None, None] * (pos[:, None] - pos[None, :]).abs()[None]
+        out = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=bias, scale=scale)
+        out.backward(torch.tensor(c["do"][b, :n].astype(np.float64)).permute(1, 0, 2))
+        assert np.allclose(out.detach().permute(1, 0, 2).numpy(), O[b, :n], atol=1e-13)
+        for g, ref in ((tq.grad, dQ), (tk.grad, dK), (tv.grad, dV)):
+            assert np.allclose(g.permute(1, 0, 2).numpy(), ref[b, :n], atol=1e-13)
+
+
+# ---------------------------------------------------------------- P11: index maps
+def _parse_fixture():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "tiny_index_map.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *vals = line.split()
+        out[key] = vals
+    idx = []
+    for r in out["indices"]:
+        a, b = r.split(":")
+        idx.extend(range(int(a), int(b) + 1))
+    return ([int(x) for x in out["lengths"]], [int(x) for x in out["cu_seqlens"]], idx,
+            int(out["total_tokens"][0]), int(out["max_seqlen"][0]))
+
+
+def test_index_maps_tiny_fixture():
+    lengths, cu, idx, T, mx = _parse_fixture()
+    b = wl.make_batch("tiny")
+    assert list(b["lengths"]) == lengths
+    got = orc.unpad_index(b["mask"])
+    assert list(got[0]) == lengths and list(got[1]) == cu and list(got[2]) == idx
+    assert got[3] == T and got[4] == mx
+    assert got[1].dtype == np.int32 and got[2].dtype == np.int32
+
+
+@pytest.mark.parametrize("seed,B,L,p", [(0, 3, 7, 0.5), (1, 8, 33, 0.8), (2, 1, 1, 1.0), (3, 5, 16, 0.0),
+                                        (4, 5, 16, 1.0), (5, 2, 130, 0.3), (6, 64, 5, 0.05)])
+def test_index_maps_brute_force(seed, B, L, p):
+    mask = wl.random_mask(seed, B, L, p)
+    mask[mask != 0] = np.random.default_rng(seed).integers(1, 5, size=int(mask.sum()))  # any nonzero keeps
+    lengths, cu, idx, T, mx = orc.unpad_index(mask)
+    assert np.array_equal(idx, np.flatnonzero(mask.reshape(-1)))
+    assert np.array_equal(lengths, (mask != 0).sum(1))
+    assert cu[0] == 0 and np.array_equal(np.diff(cu), lengths) and cu[-1] == T == np.count_nonzero(mask)
+    assert mx == (lengths.max() if B else 0)
+    assert np.all(np.diff(idx) > 0)
+    X = np.random.default_rng(seed + 1).standard_normal((B, L, 3))
+    Y = orc.unpad(X, idx)
+    assert Y.shape == (T, 3)
+    back = orc.pad(Y, idx, B, L)
+    assert np.array_equal(back, X * (mask != 0)[:, :, None])
+    assert np.array_equal(orc.unpad(back, idx), Y)
+    assert np.array_equal(Y, X.reshape(B * L, 3)[np.flatnonzero(mask.reshape(-1))])
+
+
+def test_unpadded_equals_masked_padded():
+    """Packed tokens of sequence b are the rows cu[b]..cu[b+1]-1, at positions 0..len-1."""
+    lengths = [5, 17, 32, 9]
+    c = _case(12, lengths, 32, 2, 8)
+    O, _ = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    _, cu, idx, T, _ = orc.unpad_index(c["mask"])
+    Op = orc.unpad(O, idx)
+    qp, kp, vp = (orc.unpad(c[x], idx) for x in ("q", "k", "v"))
+    for b, n in enumerate(lengths):
+        s, e = cu[b], cu[b + 1]
+        one = orc.attention_fwd(qp[None, s:e], kp[None, s:e], vp[None, s:e], np.ones((1, n), np.int32), c["slopes"], c["scale"])[0]
+        assert np.allclose(one[0], Op[s:e], atol=1e-14)
+
+
+# ---------------------------------------------------------------- P12: numerics of the oracle itself
+def test_shift_invariance_and_large_logits():
+    c = _case(13, [8, 3], 8, 2, 4)
+    O, LSE = orc.attention_fwd(c["q"], c["k"], c["v"], c["mask"], c["slopes"], c["scale"])
+    # adding one vector u to every key shifts row i of the scores by scale*q_i.u: P and O unchanged
+    u = np.random.default_rng(3).standard_normal(4)
+    O2, LSE2 = orc.attention_fwd(c["q"], c["k"] + u, c["v"], c["mask"], c["slopes"], c["scale"])
+    assert np.allclose(O2, O, atol=1e-13)
+    shift = c["scale"] * np.einsum("blhd,d->bhl", c["q"].astype(np.float64), u)
+    for b, n in enumerate(c["lengths"]):
+        assert np.allclose(LSE2[b, :, :n], LSE[b, :, :n] + shift[b, :, :n], atol=1e-12)
+    # huge logits: no overflow, rows still sum to one, output is (nearly) the argmax row of V
+    Ob, LSEb, Pb = orc.attention_fwd(c["q"] * 1e3, c["k"], c["v"], c["mask"], c["slopes"], c["scale"], return_probs=True)
+    assert np.all(np.isfinite(Ob)) and np.all(np.isfinite(LSEb[0])) and np.allclose(Pb[0].sum(-1), 1.0, atol=1e-14)
+
+
+def test_attention_oracle_rejects_non_suffix_padding():
+    c = _case(14, [4], 6, 1, 2)
+    bad = c["mask"].copy()
+    bad[0, 1] = 0
+    with pytest.raises(ValueError):
+        orc.attention_fwd(c["q"], c["k"], c["v"], bad, c["slopes"], c["scale"])
+
+
+# ---------------------------------------------------------------- input generators
+def test_workload_recipes():
+    b = wl.make_batch("bert_base", batch=64)
+    w = b["workload"]
+    assert b["q"].shape == (64, 128, 12, 64) and b["mask"].shape == (64, 128)
+    assert np.all((b["lengths"] >= 16) & (b["lengths"] <= 128))
+    assert np.array_equal(wl.round_to_bf16(b["q"]), b["q"])           # already bf16-representable
+    assert abs(float(b["q"].std()) - 0.125) < 2e-3 and abs(float(b["do"].std()) - 1.0) < 1e-2
+    b2 = wl.make_batch("bert_base", batch=64)
+    assert np.array_equal(b2["lengths"], b["lengths"]) and np.array_equal(b2["k"], b["k"])   # seeded
+    full = wl.draw_lengths(wl.WORKLOADS["bert_base"], np.random.default_rng(1))
+    assert 0.45 < np.mean(full == 128) < 0.75
+    l5 = wl.draw_lengths(wl.WORKLOADS["ragged2048"], np.random.default_rng(2))
+    assert l5.min() >= 8 and l5.max() <= 2048
+    # round-to-nearest-even at the bf16 boundary
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20], dtype=np.float32)
+    assert np.array_equal(wl.round_to_bf16(x), np.array([1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7], dtype=np.float32))
