@@ -1,0 +1,158 @@
+/*
+ * mosaic_attn.h -- C ABI of the MI355X (gfx950) unpad -> ALiBi varlen attention -> pad library.
+ *
+ * The calls follow the encoder layer of the MosaicBERT paper (arXiv 2312.17482), section
+ * "MosaicBERT Architecture Modifications for Fast Pretraining":
+ *   - "Unpadding" paragraph: the real tokens of a padded [B, L] batch are concatenated, in order,
+ *     into one packed sequence of T tokens (mb_unpad_index, mb_unpad), and scattered back (mb_pad);
+ *   - "FlashAttention" + "Attention with Linear Biases" paragraphs, Eq. 1: exact softmax attention,
+ *     computed tile-wise without materialising the score matrix, with the bias  -m_h * |i - j|
+ *     added to the scores, bidirectional (mb_alibi_attn_fwd / mb_alibi_attn_bwd), m_h geometric with
+ *     ratio 2^(-8/H) (mb_alibi_slopes).
+ *
+ * Conventions common to every call
+ *   Pointers   "dev" = device (HBM) pointer, "host" = host pointer.  The caller allocates and owns
+ *              every buffer; the library allocates nothing, keeps no state between calls and never
+ *              frees.  Device pointers must be 16-byte aligned.
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
+ *              work is enqueued on it; no call synchronises with the host.
+ *   Errors     every call returns an mb_status and never throws or aborts.  Arguments are validated
+ *              on the host before anything is launched, so error paths need no GPU.  A message for
+ *              the last failing call on this thread is available from mb_last_error().
+ *   Layouts    packed activations are [T, H, D] with D contiguous; consecutive tokens are
+ *              `row_stride` ELEMENTS apart (row_stride >= H*D, a multiple of 16 bytes), so q, k and v may
+ *              point into one fused [T, 3, H, D] buffer.  The row log-sum-exp is [H, T] float,
+ *              natural log.  Positions used by the bias are positions inside the packed sequence:
+ *              token t of sequence b sits at position t - cu_seqlens[b].
+ *   Precision  MB_BF16 (D must be 64): bf16 operands on the matrix cores, fp32 accumulation and
+ *              fp32 softmax statistics; probabilities and score gradients are rounded to bf16 only
+ *              as matrix operands; outputs are rounded to bf16 once.  MB_F32 (1 <= D <= 128):
+ *              plain fp32 arithmetic throughout.
+ *   Degenerate B == 0, T == 0 and zero-length sequences are legal: MB_OK, nothing written for them.
+ *   Threads    re-entrant; the only global state is the thread-local error string.
+ */
+#ifndef MOSAIC_ATTN_H
+#define MOSAIC_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported from the shared library (everything else in it has hidden visibility). */
+#define MB_API __attribute__((visibility("default")))
+
+typedef enum {
+  MB_OK = 0,
+  MB_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, misaligned pointer, bad stride */
+  MB_ERR_UNSUPPORTED = 2, /* dtype / head_dim / size combination with no kernel */
+  MB_ERR_WORKSPACE = 3,   /* workspace NULL or smaller than mb_alibi_attn_bwd_workspace_bytes */
+  MB_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
+} mb_status;
+
+typedef enum { MB_F32 = 0, MB_BF16 = 1 } mb_dtype;
+
+/* Message describing the last error returned on the calling thread ("" if none). */
+MB_API const char* mb_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+MB_API int mb_version(void);
+
+/*
+ * Head slopes of the ALiBi bias ("Attention with Linear Biases" paragraph: geometric sequence with
+ * ratio 2^(-8/H)); the first term is the ratio itself, so slopes_host[h-1] = 2^(-8h/H), h = 1..H,
+ * for any H (no power-of-two special case).  Evaluated in double, rounded to float.
+ *   slopes_host  host, [H] floats, written.
+ * Errors: H <= 0 or NULL -> MB_ERR_INVALID_ARG.
+ */
+MB_API mb_status mb_alibi_slopes(int H, float* slopes_host);
+
+/*
+ * Index maps of the "Unpadding" paragraph.  mask[b, l] != 0 marks a real token; any 0/nonzero
+ * pattern is accepted (holes allowed).
+ *   mask        dev, [B, L] int32, read.
+ *   seqlens     dev, [B] int32, written: number of real tokens of each row.
+ *   cu_seqlens  dev, [B+1] int32, written: exclusive prefix sum of seqlens, cu[0]=0, cu[B]=T.
+ *   indices     dev, capacity B*L int32; the first T entries are written with the flat positions
+ *               b*L + l of the real tokens in ascending order; the rest is left untouched.
+ *   meta_dev    dev, [2] int32, written: meta[0] = T, meta[1] = max_b seqlens[b].
+ * B*L must be < 2^31.  B == 0: meta = {0, 0}, cu[0] = 0.
+ */
+MB_API mb_status mb_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
+                         int32_t* indices, int32_t* meta_dev, void* stream);
+
+/* Blocking read-back of meta_dev ({T, max_seqlen}) for callers that size buffers on the host.
+ *   meta_host  host, [2] int32, written.  Synchronises `stream`. */
+MB_API mb_status mb_read_meta(const int32_t* meta_dev, int32_t* meta_host, void* stream);
+
+/*
+ * Gather of the "Unpadding" paragraph:  packed[t, :] = padded[indices[t], :]  for t < T.
+ *   padded    dev, [rows_padded, W] elements, read (rows_padded = B*L of the mask).
+ *   indices   dev, [>= T] int32 from mb_unpad_index, read.
+ *   T_cap     upper bound of T used to size the launch (e.g. B*L); rows t >= T are not touched.
+ *   meta_dev  dev, [2] int32 or NULL.  If given, T = min(meta_dev[0], T_cap) is read on the device
+ *             (no host round trip); if NULL, T = T_cap.
+ *   W         row width in elements; W * element_size must be a multiple of 16 bytes.
+ *   packed    dev, [T_cap, W] capacity, rows [0, T) written.
+ */
+MB_API mb_status mb_unpad(const void* padded, const int32_t* indices, int T_cap, const int32_t* meta_dev,
+                   int W, mb_dtype dt, void* packed, void* stream);
+
+/*
+ * Inverse scatter (Figure 1A of the paper, the step back to the padded batch):
+ *   padded[indices[t], :] = packed[t, :] for t < T;  every other row of padded is set to zero bits.
+ * `indices` must be strictly ascending (as mb_unpad_index writes them).  All B*L rows are written.
+ *   packed    dev, [>= T, W], read.      padded  dev, [B*L, W], written in full.
+ *   T_cap, meta_dev, W, dt as for mb_unpad.
+ */
+MB_API mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta_dev,
+                 int B, int L, int W, mb_dtype dt, void* padded, void* stream);
+
+/*
+ * Forward attention, Eq. 1:  for every sequence b, head h and tokens i, j of that sequence
+ *   S_ij = softmax_scale * q_i . k_j - slopes[h] * |i - j|,   P = softmax_j(S),   O_i = sum_j P_ij v_j,
+ *   lse_i = log sum_j exp(S_ij).
+ *   q, k, v      dev, [T, H, D] with row strides q/k/v_row_stride (elements), read.
+ *   cu_seqlens   dev, [B+1] int32, read.  T and max_seqlen are the host's copies of the batch's total
+ *                token count and longest sequence (max_seqlen may be any upper bound, e.g. L).
+ *   slopes       dev, [H] float, read.
+ *   o            dev, [T, H, D] with row stride o_row_stride, written.
+ *   lse          dev, [H, T] float, written.
+ * Errors: MB_BF16 with D != 64, MB_F32 with D > 128 -> MB_ERR_UNSUPPORTED.
+ */
+MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                            int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens,
+                            int B, int T, int max_seqlen, int H, int D, const float* slopes,
+                            float softmax_scale, mb_dtype dt, void* o, int64_t o_row_stride,
+                            float* lse, void* stream);
+
+/* Bytes of device workspace mb_alibi_attn_bwd needs for these sizes (0 on invalid sizes). */
+MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt);
+
+/*
+ * Backward attention: gradients of  sum(O * dO)  for the forward above (the slopes are fixed
+ * constants of the model, so they receive no gradient):
+ *   Delta_i = dO_i . O_i;  dV_j = sum_i P_ij dO_i;  dP_ij = dO_i . v_j;  dS_ij = P_ij (dP_ij - Delta_i);
+ *   dQ_i = softmax_scale * sum_j dS_ij k_j;   dK_j = softmax_scale * sum_i dS_ij q_i.
+ * P is recomputed from q, k and lse; the score matrix is never stored.
+ *   dout, o      dev, [T, H, D] with row strides do_row_stride / o_row_stride, read.
+ *   lse          dev, [H, T] float from the forward, read.
+ *   dq, dk, dv   dev, [T, H, D] with row strides dq/dk/dv_row_stride, written (rows [0, T)).
+ *   workspace    dev, at least mb_alibi_attn_bwd_workspace_bytes(...) bytes, scratch.
+ * Deterministic: no atomics; two calls on the same inputs give identical bits.
+ */
+MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
+                            const void* o, const float* lse, int64_t do_row_stride,
+                            int64_t q_row_stride, int64_t k_row_stride, int64_t v_row_stride,
+                            int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
+                            mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
+                            int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSAIC_ATTN_H */

@@ -1,0 +1,182 @@
+"""ctypes binding of libmosaicattn.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors used purely as device buffers (data_ptr, shape, stride); every step of
+the path runs inside the HIP library.  Importing this module raises if the library is not built:
+there is no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_float, c_int, c_int64, c_size_t, c_void_p
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libmosaicattn.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        "libmosaicattn.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'`." % _LIB_PATH)
+_lib = ctypes.CDLL(_LIB_PATH)
+
+MB_OK, MB_ERR_INVALID_ARG, MB_ERR_UNSUPPORTED, MB_ERR_WORKSPACE, MB_ERR_HIP = range(5)
+MB_F32, MB_BF16 = 0, 1
+
+EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
+           "mb_pad", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes", "mb_alibi_attn_bwd")
+
+_lib.mb_last_error.restype = c_char_p
+_lib.mb_last_error.argtypes = []
+_lib.mb_version.restype = c_int
+_lib.mb_version.argtypes = []
+_lib.mb_alibi_slopes.restype = c_int
+_lib.mb_alibi_slopes.argtypes = [c_int, c_void_p]
+_lib.mb_unpad_index.restype = c_int
+_lib.mb_unpad_index.argtypes = [c_void_p, c_int, c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.mb_read_meta.restype = c_int
+_lib.mb_read_meta.argtypes = [c_void_p, c_void_p, c_void_p]
+_lib.mb_unpad.restype = c_int
+_lib.mb_unpad.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_void_p]
+_lib.mb_pad.restype = c_int
+_lib.mb_pad.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+_lib.mb_alibi_attn_fwd.restype = c_int
+_lib.mb_alibi_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int, c_int,
+                                   c_int, c_int, c_int, c_void_p, c_float, c_int, c_void_p, c_int64, c_void_p,
+                                   c_void_p]
+_lib.mb_alibi_attn_bwd_workspace_bytes.restype = c_size_t
+_lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
+_lib.mb_alibi_attn_bwd.restype = c_int
+_lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
+                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p])
+
+
+class MosaicAttnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("libmosaicattn status %d: %s" % (status, message))
+        self.status = status
+
+
+def raw():
+    """The ctypes library handle, for tests of the C ABI itself."""
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != MB_OK:
+        raise MosaicAttnError(status, _lib.mb_last_error().decode())
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MB_F32
+    if t.dtype == torch.bfloat16:
+        return MB_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _row_stride(t: torch.Tensor) -> int:
+    """[T, H, D] view with contiguous (H, D): returns the token stride in elements."""
+    assert t.dim() == 3 and t.stride(2) == 1 and t.stride(1) == t.shape[2], "need [T, H, D] with dense (H, D)"
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1] * t.shape[2])
+
+
+def mb_version() -> int:
+    return _lib.mb_version()
+
+
+def mb_last_error() -> str:
+    return _lib.mb_last_error().decode()
+
+
+def mb_alibi_slopes(H: int) -> torch.Tensor:
+    """Host tensor [H] float32 of the head slopes."""
+    out = torch.empty(max(H, 0), dtype=torch.float32)
+    _check(_lib.mb_alibi_slopes(H, out.data_ptr() if H > 0 else None))
+    return out
+
+
+def mb_unpad_index(mask: torch.Tensor):
+    """mask [B, L] int32 on the GPU -> (seqlens [B], cu_seqlens [B+1], indices [B*L] (first T valid), meta [2])."""
+    assert mask.dtype == torch.int32 and mask.dim() == 2 and mask.is_contiguous()
+    B, L = mask.shape
+    dev = mask.device
+    seqlens = torch.empty(max(B, 1), dtype=torch.int32, device=dev)[:B]
+    cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    indices = torch.empty(max(B * L, 1), dtype=torch.int32, device=dev)[:B * L]
+    meta = torch.empty(2, dtype=torch.int32, device=dev)
+    _check(_lib.mb_unpad_index(_ptr(mask), B, L, _ptr(seqlens), _ptr(cu), _ptr(indices), _ptr(meta), _stream()))
+    return seqlens, cu, indices, meta
+
+
+def mb_read_meta(meta: torch.Tensor):
+    host = (ctypes.c_int32 * 2)()
+    _check(_lib.mb_read_meta(_ptr(meta), ctypes.addressof(host), _stream()))
+    return int(host[0]), int(host[1])
+
+
+def mb_unpad(padded: torch.Tensor, indices: torch.Tensor, T_cap: int, meta, out: torch.Tensor | None = None):
+    """padded [B*L, W] (any leading shape flattened by the caller) -> packed [T_cap, W]; rows < T written."""
+    assert padded.dim() == 2 and padded.is_contiguous()
+    W = padded.shape[1]
+    if out is None:
+        out = torch.empty((T_cap, W), dtype=padded.dtype, device=padded.device)
+    assert out.is_contiguous() and out.shape[1] == W and out.shape[0] >= T_cap
+    _check(_lib.mb_unpad(_ptr(padded), _ptr(indices), T_cap, _ptr(meta), W, _dtype_code(padded), _ptr(out), _stream()))
+    return out
+
+
+def mb_pad(packed: torch.Tensor, indices: torch.Tensor, T_cap: int, meta, B: int, L: int,
+           out: torch.Tensor | None = None):
+    """packed [>=T, W] -> padded [B*L, W], zero at padded positions."""
+    assert packed.dim() == 2 and packed.is_contiguous()
+    W = packed.shape[1]
+    if out is None:
+        out = torch.empty((B * L, W), dtype=packed.dtype, device=packed.device)
+    assert out.is_contiguous() and tuple(out.shape) == (B * L, W)
+    _check(_lib.mb_pad(_ptr(packed), _ptr(indices), T_cap, _ptr(meta), B, L, W, _dtype_code(packed), _ptr(out),
+                       _stream()))
+    return out
+
+
+def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None):
+    """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32)."""
+    T, H, D = q.shape
+    B = cu_seqlens.numel() - 1
+    if out is None:
+        out = torch.empty((T, H, D), dtype=q.dtype, device=q.device)
+    if lse is None:
+        lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
+    _check(_lib.mb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
+                                  _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
+                                  _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _stream()))
+    return out, lse
+
+
+def mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int:
+    return int(_lib.mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code))
+
+
+def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
+                      dq=None, dk=None, dv=None, workspace=None):
+    """Returns (dq, dk, dv), each [T, H, D]."""
+    T, H, D = q.shape
+    B = cu_seqlens.numel() - 1
+    dq = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dq is None else dq
+    dk = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dk is None else dk
+    dv = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dv is None else dv
+    need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, _dtype_code(q))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(_lib.mb_alibi_attn_bwd(_ptr(dout), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _row_stride(dout),
+                                  _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o), _ptr(cu_seqlens),
+                                  B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale), _dtype_code(q),
+                                  _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
+                                  _ptr(workspace), workspace.numel(), _stream()))
+    return dq, dk, dv

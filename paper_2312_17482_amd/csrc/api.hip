@@ -1,0 +1,255 @@
+// C ABI of libmosaicattn: argument validation on the host (before any launch, so every error path is
+// testable without a GPU), then dispatch to the kernel launchers.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace mb {
+namespace {
+thread_local char g_error[512] = "";
+}
+
+mb_status fail(mb_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_error[0] = '\0'; }
+
+mb_status check_launch(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(MB_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return MB_OK;
+}
+
+namespace {
+
+#define MB_REQUIRE(cond, code, ...) \
+  do {                              \
+    if (!(cond)) return fail(code, __VA_ARGS__); \
+  } while (0)
+
+mb_status check_ptr(const void* p, const char* name) {
+  MB_REQUIRE(p != nullptr, MB_ERR_INVALID_ARG, "%s is NULL", name);
+  MB_REQUIRE(aligned16(p), MB_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+  return MB_OK;
+}
+#define MB_CHECK_PTR(p)                              \
+  do {                                               \
+    const mb_status st_ = check_ptr((p), #p);        \
+    if (st_ != MB_OK) return st_;                    \
+  } while (0)
+
+mb_status check_dtype(mb_dtype dt) {
+  MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  return MB_OK;
+}
+
+mb_status check_stride(int64_t stride, int H, int D, mb_dtype dt, const char* name) {
+  MB_REQUIRE(stride >= (int64_t)H * D, MB_ERR_INVALID_ARG, "%s=%lld is smaller than H*D=%lld", name,
+             (long long)stride, (long long)H * D);
+  MB_REQUIRE((stride * (int64_t)elem_size(dt)) % 16 == 0, MB_ERR_INVALID_ARG,
+             "%s=%lld elements is not a multiple of 16 bytes", name, (long long)stride);
+  return MB_OK;
+}
+#define MB_CHECK_STRIDE(s, H, D)                               \
+  do {                                                         \
+    const mb_status st_ = check_stride((s), (H), (D), dt, #s); \
+    if (st_ != MB_OK) return st_;                         \
+  } while (0)
+
+mb_status check_attn_dims(int B, int T, int max_seqlen, int H, int D, mb_dtype dt) {
+  mb_status st = check_dtype(dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE(B >= 0 && T >= 0 && max_seqlen >= 0, MB_ERR_INVALID_ARG, "negative size (B=%d T=%d max_seqlen=%d)", B,
+             T, max_seqlen);
+  MB_REQUIRE(H > 0 && D > 0, MB_ERR_INVALID_ARG, "H=%d and D=%d must be positive", H, D);
+  MB_REQUIRE(H <= 65535, MB_ERR_UNSUPPORTED, "H=%d exceeds 65535", H);
+  MB_REQUIRE(D <= 128, MB_ERR_UNSUPPORTED, "head_dim %d > 128 has no kernel", D);
+  MB_REQUIRE(D % 8 == 0 || dt == MB_F32, MB_ERR_UNSUPPORTED, "bf16 head_dim %d is not a multiple of 8", D);
+  MB_REQUIRE(dt != MB_F32 || D % 4 == 0, MB_ERR_UNSUPPORTED, "fp32 head_dim %d is not a multiple of 4", D);
+  MB_REQUIRE((int64_t)T * H < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "T*H=%lld exceeds 2^31", (long long)T * H);
+  return MB_OK;
+}
+
+bool use_mfma(mb_dtype dt, int D) { return dt == MB_BF16 && D == 64; }
+
+}  // namespace
+}  // namespace mb
+
+using namespace mb;
+
+extern "C" {
+
+const char* mb_last_error(void) { return g_error; }
+
+int mb_version(void) { return 100; }
+
+mb_status mb_alibi_slopes(int H, float* slopes_host) {
+  clear_error();
+  MB_REQUIRE(H > 0, MB_ERR_INVALID_ARG, "H=%d must be positive", H);
+  MB_REQUIRE(slopes_host != nullptr, MB_ERR_INVALID_ARG, "slopes_host is NULL");
+  for (int h = 1; h <= H; ++h) slopes_host[h - 1] = (float)std::exp2(-8.0 * (double)h / (double)H);
+  return MB_OK;
+}
+
+mb_status mb_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
+                         int32_t* indices, int32_t* meta_dev, void* stream) {
+  clear_error();
+  MB_REQUIRE(B >= 0 && L >= 0, MB_ERR_INVALID_ARG, "negative size (B=%d L=%d)", B, L);
+  MB_REQUIRE((int64_t)B * L < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "B*L=%lld does not fit int32",
+             (long long)B * L);
+  MB_CHECK_PTR(cu_seqlens);
+  MB_CHECK_PTR(meta_dev);
+  if (B > 0) {
+    MB_CHECK_PTR(seqlens);
+    if (L > 0) {
+      MB_CHECK_PTR(mask);
+      MB_CHECK_PTR(indices);
+    }
+  }
+  return launch_unpad_index(mask, B, L, seqlens, cu_seqlens, indices, meta_dev, (hipStream_t)stream);
+}
+
+mb_status mb_read_meta(const int32_t* meta_dev, int32_t* meta_host, void* stream) {
+  clear_error();
+  MB_REQUIRE(meta_dev != nullptr && meta_host != nullptr, MB_ERR_INVALID_ARG, "meta pointer is NULL");
+  hipError_t e = hipMemcpyAsync(meta_host, meta_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return fail(MB_ERR_HIP, "mb_read_meta: %s", hipGetErrorString(e));
+  return MB_OK;
+}
+
+static mb_status check_rows(int T_cap, int W, mb_dtype dt) {
+  mb_status st = check_dtype(dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap=%d is negative", T_cap);
+  MB_REQUIRE(W > 0, MB_ERR_INVALID_ARG, "W=%d must be positive", W);
+  MB_REQUIRE(((int64_t)W * (int64_t)elem_size(dt)) % 16 == 0, MB_ERR_INVALID_ARG,
+             "row of %d elements is not a multiple of 16 bytes", W);
+  MB_REQUIRE((int64_t)W * (int64_t)elem_size(dt) < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "row too wide");
+  return MB_OK;
+}
+
+mb_status mb_unpad(const void* padded, const int32_t* indices, int T_cap, const int32_t* meta_dev, int W,
+                   mb_dtype dt, void* packed, void* stream) {
+  clear_error();
+  mb_status st = check_rows(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  if (T_cap == 0) return MB_OK;
+  MB_CHECK_PTR(padded);
+  MB_CHECK_PTR(indices);
+  MB_CHECK_PTR(packed);
+  return launch_gather_rows(padded, indices, T_cap, meta_dev, (int)(W * elem_size(dt)), packed,
+                            (hipStream_t)stream);
+}
+
+mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta_dev, int B, int L,
+                 int W, mb_dtype dt, void* padded, void* stream) {
+  clear_error();
+  mb_status st = check_rows(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE(B >= 0 && L >= 0, MB_ERR_INVALID_ARG, "negative size (B=%d L=%d)", B, L);
+  MB_REQUIRE((int64_t)B * L < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "B*L=%lld does not fit int32",
+             (long long)B * L);
+  MB_REQUIRE((int64_t)T_cap <= (int64_t)B * L, MB_ERR_INVALID_ARG, "T_cap=%d exceeds B*L=%lld", T_cap,
+             (long long)B * L);
+  if ((int64_t)B * L == 0) return MB_OK;
+  MB_CHECK_PTR(padded);
+  if (T_cap > 0) {
+    MB_CHECK_PTR(packed);
+    MB_CHECK_PTR(indices);
+  }
+  return launch_scatter_rows(packed, indices, T_cap, meta_dev, B * L, (int)(W * elem_size(dt)), padded,
+                             (hipStream_t)stream);
+}
+
+mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
+                            int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
+                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
+                            void* o, int64_t o_row_stride, float* lse, void* stream) {
+  clear_error();
+  mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
+  if (st != MB_OK) return st;
+  MB_CHECK_STRIDE(q_row_stride, H, D);
+  MB_CHECK_STRIDE(k_row_stride, H, D);
+  MB_CHECK_STRIDE(v_row_stride, H, D);
+  MB_CHECK_STRIDE(o_row_stride, H, D);
+  MB_REQUIRE(std::isfinite(softmax_scale), MB_ERR_INVALID_ARG, "softmax_scale is not finite");
+  if (B == 0 || T == 0) return MB_OK;
+  MB_REQUIRE(max_seqlen > 0, MB_ERR_INVALID_ARG, "max_seqlen=0 with T=%d tokens", T);
+  MB_CHECK_PTR(q);
+  MB_CHECK_PTR(k);
+  MB_CHECK_PTR(v);
+  MB_CHECK_PTR(cu_seqlens);
+  MB_CHECK_PTR(slopes);
+  MB_CHECK_PTR(o);
+  MB_CHECK_PTR(lse);
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
+  if (use_mfma(dt, D))
+    return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
+                                (hipStream_t)stream);
+  MB_REQUIRE(max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
+             "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  return launch_attn_fwd_generic(s, dt, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
+                                 (hipStream_t)stream);
+}
+
+size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt) {
+  if (B < 0 || T < 0 || max_seqlen < 0 || H <= 0 || D <= 0 || D > 128) return 0;
+  if (dt != MB_F32 && dt != MB_BF16) return 0;
+  return align_up((size_t)H * (size_t)T * sizeof(float), 256);  // Delta, [H, T] float
+}
+
+mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v, const void* o,
+                            const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
+                            int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
+                            void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
+                            int64_t dv_row_stride, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
+  if (st != MB_OK) return st;
+  MB_CHECK_STRIDE(do_row_stride, H, D);
+  MB_CHECK_STRIDE(q_row_stride, H, D);
+  MB_CHECK_STRIDE(k_row_stride, H, D);
+  MB_CHECK_STRIDE(v_row_stride, H, D);
+  MB_CHECK_STRIDE(o_row_stride, H, D);
+  MB_CHECK_STRIDE(dq_row_stride, H, D);
+  MB_CHECK_STRIDE(dk_row_stride, H, D);
+  MB_CHECK_STRIDE(dv_row_stride, H, D);
+  MB_REQUIRE(std::isfinite(softmax_scale), MB_ERR_INVALID_ARG, "softmax_scale is not finite");
+  if (B == 0 || T == 0) return MB_OK;
+  MB_REQUIRE(max_seqlen > 0, MB_ERR_INVALID_ARG, "max_seqlen=0 with T=%d tokens", T);
+  MB_CHECK_PTR(dout);
+  MB_CHECK_PTR(q);
+  MB_CHECK_PTR(k);
+  MB_CHECK_PTR(v);
+  MB_CHECK_PTR(o);
+  MB_CHECK_PTR(lse);
+  MB_CHECK_PTR(cu_seqlens);
+  MB_CHECK_PTR(slopes);
+  MB_CHECK_PTR(dq);
+  MB_CHECK_PTR(dk);
+  MB_CHECK_PTR(dv);
+  const size_t need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
+  MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
+             "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
+  if (use_mfma(dt, D))
+    return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
+                                o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
+                                (float*)workspace, (hipStream_t)stream);
+  MB_REQUIRE(max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
+             "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  return launch_attn_bwd_generic(s, dt, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride,
+                                 v_row_stride, o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride,
+                                 dv_row_stride, (float*)workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

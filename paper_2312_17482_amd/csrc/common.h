@@ -1,0 +1,52 @@
+// Internal declarations shared by the translation units of libmosaicattn (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mosaic_attn.h"
+
+namespace mb {
+
+// Records a message for mb_last_error() and returns `code`.
+mb_status fail(mb_status code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+// Maps the HIP launch status to MB_OK / MB_ERR_HIP.
+mb_status check_launch(const char* what);
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t elem_size(mb_dtype dt) { return dt == MB_F32 ? 4 : 2; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct AttnShape {
+  int B, T, max_seqlen, H, D;
+  const int32_t* cu_seqlens;
+  const float* slopes;
+  float scale;
+};
+
+// ---- launchers (each enqueues on `stream`, returns MB_OK or MB_ERR_HIP) ----
+mb_status launch_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
+                             int32_t* indices, int32_t* meta, hipStream_t stream);
+mb_status launch_gather_rows(const void* padded, const int32_t* indices, int T_cap, const int32_t* meta,
+                             int row_bytes, void* packed, hipStream_t stream);
+mb_status launch_scatter_rows(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta,
+                              int rows_padded, int row_bytes, void* padded, hipStream_t stream);
+
+// Generic ALU kernels: any D <= 128, fp32 or bf16 storage, fp32 arithmetic.
+static constexpr int kGenericMaxSeqlen = 16384;
+mb_status launch_attn_fwd_generic(const AttnShape& s, mb_dtype dt, const void* q, const void* k, const void* v,
+                                  int64_t qs, int64_t ks, int64_t vs, void* o, int64_t os, float* lse,
+                                  hipStream_t stream);
+mb_status launch_attn_bwd_generic(const AttnShape& s, mb_dtype dt, const void* dout, const void* q, const void* k,
+                                  const void* v, const void* o, const float* lse, int64_t dos, int64_t qs,
+                                  int64_t ks, int64_t vs, int64_t os, void* dq, void* dk, void* dv, int64_t dqs,
+                                  int64_t dks, int64_t dvs, float* delta_ws, hipStream_t stream);
+
+// bf16, D = 64 matrix-core kernels.
+mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
+                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream);
+mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void* q, const void* k, const void* v,
+                               const void* o, const float* lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
+                               int64_t os, void* dq, void* dk, void* dv, int64_t dqs, int64_t dks, int64_t dvs,
+                               float* delta_ws, hipStream_t stream);
+
+}  // namespace mb

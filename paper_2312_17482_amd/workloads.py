@@ -106,13 +106,14 @@ def make_batch(name: str, seed_offset: int = 0, batch: int | None = None) -> dic
 
 
 def random_attention_case(seed: int, lengths, L: int, H: int, D: int, std: float = 1.0,
-                          bf16: bool = False) -> dict:
-    """Free-form case for parity/edge tests: explicit lengths, suffix mask, N(0,std^2) tensors."""
+                          bf16: bool = False, v_std: float | None = None) -> dict:
+    """Free-form case for parity/edge tests: explicit lengths, suffix mask, Q,K ~ N(0,std^2),
+    V ~ N(0,v_std^2) (v_std defaults to std), dO ~ N(0,1)."""
     rng = np.random.default_rng(seed)
     lengths = np.asarray(lengths, dtype=np.int32)
     shape = (len(lengths), L, H, D)
     out = {"lengths": lengths, "mask": suffix_mask(lengths, L)}
-    for key, s in (("q", std), ("k", std), ("v", std), ("do", 1.0)):
+    for key, s in (("q", std), ("k", std), ("v", std if v_std is None else v_std), ("do", 1.0)):
         t = rng.standard_normal(shape, dtype=np.float32) * np.float32(s)
         out[key] = round_to_bf16(t) if bf16 else t
     out["scale"] = 1.0 / float(np.sqrt(D))

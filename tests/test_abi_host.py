@@ -1,0 +1,146 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, computes the slopes, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2312_17482_amd import binding as mb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+lib = mb.raw()
+A = 4096            # a fake, 16-byte aligned "device pointer": must never be dereferenced by these calls
+
+
+def declared_symbols():
+    names = []
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            names += re.findall(r"MB_API\s+[\w\s\*]+?\b(mb_\w+)\s*\(", text)
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 10 and set(names) == set(mb.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert mb.mb_version() >= 100
+
+
+def test_slopes_against_fixture():
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "alibi_slopes.txt"))
+            if l.strip() and not l.startswith("#")]
+    for n, h, p, q in rows:
+        s = mb.mb_alibi_slopes(int(n)).numpy()
+        assert s.dtype == np.float32 and s.shape == (int(n),)
+        assert s[int(h) - 1] == np.float32(2.0 ** (-int(p) / int(q)))
+    with pytest.raises(mb.MosaicAttnError) as e:
+        mb.mb_alibi_slopes(0)
+    assert e.value.status == mb.MB_ERR_INVALID_ARG and "H=0" in str(e.value)
+    assert lib.mb_alibi_slopes(4, None) == mb.MB_ERR_INVALID_ARG
+
+
+def fwd_args(**over):
+    a = dict(q=A, k=A, v=A, qs=768, ks=768, vs=768, cu=A, B=2, T=64, max_seqlen=32, H=12, D=64, slopes=A,
+             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, stream=None)
+    a.update(over)
+    return [a[x] for x in ("q", "k", "v", "qs", "ks", "vs", "cu", "B", "T", "max_seqlen", "H", "D", "slopes", "scale",
+                           "dt", "o", "os", "lse", "stream")]
+
+
+def bwd_args(**over):
+    a = dict(do=A, q=A, k=A, v=A, o=A, lse=A, dos=768, qs=768, ks=768, vs=768, os=768, cu=A, B=2, T=64,
+             max_seqlen=32, H=12, D=64, slopes=A, scale=0.125, dt=mb.MB_BF16, dq=A, dk=A, dv=A, dqs=768, dks=768,
+             dvs=768, ws=A, wsb=1 << 20, stream=None)
+    a.update(over)
+    return [a[x] for x in ("do", "q", "k", "v", "o", "lse", "dos", "qs", "ks", "vs", "os", "cu", "B", "T",
+                           "max_seqlen", "H", "D", "slopes", "scale", "dt", "dq", "dk", "dv", "dqs", "dks", "dvs",
+                           "ws", "wsb", "stream")]
+
+
+@pytest.mark.parametrize("over,status,needle", [
+    (dict(q=None), mb.MB_ERR_INVALID_ARG, "q is NULL"),
+    (dict(lse=None), mb.MB_ERR_INVALID_ARG, "lse is NULL"),
+    (dict(k=A + 2), mb.MB_ERR_INVALID_ARG, "16-byte"),
+    (dict(H=0), mb.MB_ERR_INVALID_ARG, "positive"),
+    (dict(T=-1), mb.MB_ERR_INVALID_ARG, "negative"),
+    (dict(D=256), mb.MB_ERR_UNSUPPORTED, "head_dim"),
+    (dict(D=12, dt=mb.MB_BF16, qs=768), mb.MB_ERR_UNSUPPORTED, "multiple of 8"),
+    (dict(qs=100), mb.MB_ERR_INVALID_ARG, "smaller than H*D"),
+    (dict(vs=772), mb.MB_ERR_INVALID_ARG, "multiple of 16 bytes"),
+    (dict(dt=7), mb.MB_ERR_INVALID_ARG, "dtype"),
+    (dict(scale=float("nan")), mb.MB_ERR_INVALID_ARG, "finite"),
+    (dict(max_seqlen=0), mb.MB_ERR_INVALID_ARG, "max_seqlen"),
+    (dict(dt=mb.MB_F32, D=16, H=2, max_seqlen=1 << 20), mb.MB_ERR_UNSUPPORTED, "max_seqlen"),
+])
+def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
+    assert lib.mb_alibi_attn_fwd(*fwd_args(**over)) == status
+    assert needle in mb.mb_last_error()
+
+
+@pytest.mark.parametrize("over,status,needle", [
+    (dict(do=None), mb.MB_ERR_INVALID_ARG, "dout is NULL"),
+    (dict(dv=None), mb.MB_ERR_INVALID_ARG, "dv is NULL"),
+    (dict(dqs=8), mb.MB_ERR_INVALID_ARG, "smaller than H*D"),
+    (dict(ws=None), mb.MB_ERR_WORKSPACE, "workspace"),
+    (dict(wsb=16), mb.MB_ERR_WORKSPACE, "needed"),
+    (dict(ws=A + 4), mb.MB_ERR_INVALID_ARG, "workspace is not 16-byte"),
+    (dict(D=200), mb.MB_ERR_UNSUPPORTED, "head_dim"),
+])
+def test_bwd_rejects_bad_arguments_without_launching(over, status, needle):
+    assert lib.mb_alibi_attn_bwd(*bwd_args(**over)) == status
+    assert needle in mb.mb_last_error()
+
+
+def test_degenerate_sizes_are_ok_and_touch_nothing():
+    # T == 0 / B == 0: MB_OK before any pointer is looked at or anything is launched
+    assert lib.mb_alibi_attn_fwd(*fwd_args(T=0, q=None, k=None, v=None, o=None, lse=None)) == mb.MB_OK
+    assert lib.mb_alibi_attn_bwd(*bwd_args(B=0, T=0, do=None, ws=None, wsb=0)) == mb.MB_OK
+    assert mb.mb_last_error() == ""
+    assert lib.mb_unpad(None, None, 0, None, 768, mb.MB_BF16, None, None) == mb.MB_OK
+    assert lib.mb_pad(None, None, 0, None, 0, 128, 768, mb.MB_BF16, None, None) == mb.MB_OK
+
+
+def test_workspace_query():
+    need = mb.mb_alibi_attn_bwd_workspace_bytes(256, 27000, 128, 12, 64, mb.MB_BF16)
+    assert need >= 12 * 27000 * 4 and need % 256 == 0
+    assert mb.mb_alibi_attn_bwd_workspace_bytes(1, 1, 1, 0, 64, mb.MB_BF16) == 0
+    assert mb.mb_alibi_attn_bwd_workspace_bytes(1, 1, 1, 1, 64, 9) == 0
+
+
+@pytest.mark.parametrize("args,status,needle", [
+    ((None, A, 16, None, 768, mb.MB_BF16, A, None), mb.MB_ERR_INVALID_ARG, "padded is NULL"),
+    ((A, A, 16, None, 100, mb.MB_BF16, A, None), mb.MB_ERR_INVALID_ARG, "16 bytes"),
+    ((A, A, -1, None, 768, mb.MB_BF16, A, None), mb.MB_ERR_INVALID_ARG, "negative"),
+    ((A, A, 16, None, 0, mb.MB_BF16, A, None), mb.MB_ERR_INVALID_ARG, "positive"),
+    ((A, A + 8, 16, None, 768, mb.MB_BF16, A, None), mb.MB_ERR_INVALID_ARG, "aligned"),
+])
+def test_unpad_rejects_bad_arguments(args, status, needle):
+    assert lib.mb_unpad(*args) == status
+    assert needle in mb.mb_last_error()
+
+
+def test_pad_and_index_reject_bad_arguments():
+    assert lib.mb_pad(A, A, 100, None, 2, 8, 768, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG   # T_cap > B*L
+    assert "exceeds B*L" in mb.mb_last_error()
+    assert lib.mb_pad(A, A, 4, None, 2, 8, 768, mb.MB_BF16, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_unpad_index(None, 2, 8, A, A, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert "mask is NULL" in mb.mb_last_error()
+    assert lib.mb_unpad_index(A, -1, 8, A, A, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_unpad_index(A, 1 << 16, 1 << 16, A, A, A, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert lib.mb_unpad_index(A, 2, 8, A, A, A, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_read_meta(None, None, None) == mb.MB_ERR_INVALID_ARG
+
+
+def test_product_package_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2312_17482_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(from|import)\s+\S*oracle", text, re.M), "%s imports the oracle" % fn
+                assert "mosaic_oracle" not in text, "%s names the oracle module" % fn

@@ -1,0 +1,252 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Tolerances: integer/index/byte results bit-exact.  bf16 attention outputs and gradients: max-abs
+<= 2e-2 and relative Frobenius <= 1e-2.  fp32 path: max-abs <= 1e-4, relative Frobenius <= 1e-5.
+Row log-sum-exp: max-abs <= 1e-3 (bf16 inputs) / 1e-4 (fp32).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2312_17482_amd import workloads as wl
+from tests.helpers import err_stats, run_hip_path, run_oracle, to_dev
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL = (2e-2, 1e-2)
+F32_TOL = (1e-4, 1e-5)
+
+
+@pytest.fixture(scope="module")
+def mb():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2312_17482_amd import binding
+    return binding
+
+
+def check_index_maps(got, mask):
+    lengths, cu, idx, T, mx = orc.unpad_index(mask)
+    assert got["T"] == T and got["max_seqlen"] == mx
+    assert np.array_equal(got["seqlens"], lengths)
+    assert np.array_equal(got["cu"], cu)
+    assert np.array_equal(got["indices"], idx)
+
+
+def compare_attention(got, ref, mask, tol, lse_tol, label, abs_floor_ulps=False):
+    """abs_floor_ulps: for stress cases whose outputs are much larger than 1, the absolute bound is
+    widened to 2^-7 of the largest reference magnitude (a correctly rounded bf16 value of magnitude M
+    is already off by up to M * 2^-8: half a unit in the last of its 8 bits); the benchmark workloads never use this."""
+    valid = mask != 0
+    report = {}
+    for key in ("o", "dq", "dk", "dv"):
+        assert np.all(got[key][~valid] == 0), "%s: %s not zero at padded rows" % (label, key)
+        assert np.all(np.isfinite(got[key])), "%s: %s has non-finite values" % (label, key)
+        ma, rf = err_stats(got[key][valid], ref[key][valid])
+        report[key] = (ma, rf)
+        tol_abs = max(tol[0], 2.0 ** -7 * float(np.max(np.abs(ref[key][valid])))) if abs_floor_ulps else tol[0]
+        assert ma <= tol_abs and rf <= tol[1], "%s: %s max_abs=%.3e rel_fro=%.3e" % (label, key, ma, rf)
+    B, L = mask.shape
+    idx = np.flatnonzero(mask.reshape(-1))
+    lse_ref = np.transpose(ref["lse"], (1, 0, 2)).reshape(ref["lse"].shape[1], B * L)[:, idx]   # [H, T]
+    d = float(np.max(np.abs(got["lse"] - lse_ref)))
+    assert d <= lse_tol, "%s: lse max_abs=%.3e" % (label, d)
+    print(label, {k: "%.2e/%.2e" % v for k, v in report.items()}, "lse %.2e" % d, flush=True)
+
+
+# ------------------------------------------------------------------ index maps and row copies
+@pytest.mark.parametrize("seed,B,L,p", [(0, 4, 32, 0.5), (1, 7, 300, 0.9), (2, 1, 1, 1.0), (3, 5, 16, 0.0),
+                                        (4, 3, 1000, 1.0), (5, 300, 17, 0.3), (6, 2, 5000, 0.01), (7, 256, 128, 0.8)])
+def test_unpad_index_arbitrary_masks_bit_exact(mb, seed, B, L, p):
+    print("unpad_index seed=%d B=%d L=%d p=%.2f" % (seed, B, L, p), flush=True)
+    mask = wl.random_mask(seed, B, L, p)
+    mask[mask != 0] = np.random.default_rng(seed).integers(-3, 9, size=int(mask.sum())) * 2 + 1   # any nonzero keeps
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(mask).cuda())
+    T, mx = mb.mb_read_meta(meta)
+    got = {"T": T, "max_seqlen": mx, "seqlens": seqlens.cpu().numpy(), "cu": cu.cpu().numpy(),
+           "indices": indices[:T].cpu().numpy()}
+    check_index_maps(got, mask)
+
+
+def test_unpad_index_leaves_tail_untouched_and_handles_empty_batch(mb):
+    mask = wl.suffix_mask(np.array([3, 0, 5]), 8)
+    B, L = mask.shape
+    indices = torch.full((B * L,), -7, dtype=torch.int32, device="cuda")
+    seqlens = torch.empty(B, dtype=torch.int32, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    meta = torch.empty(2, dtype=torch.int32, device="cuda")
+    lib = mb.raw()
+    assert lib.mb_unpad_index(torch.from_numpy(mask).cuda().data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(),
+                              indices.data_ptr(), meta.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert indices[:8].tolist() == [0, 1, 2, 16, 17, 18, 19, 20] and torch.all(indices[8:] == -7)
+    assert cu.tolist() == [0, 3, 3, 8] and meta.tolist() == [8, 5]
+    assert lib.mb_unpad_index(None, 0, 8, None, cu.data_ptr(), None, meta.data_ptr(), None) == 0
+    torch.cuda.synchronize()
+    assert cu[0].item() == 0 and meta.tolist() == [0, 0]
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("seed,B,L,W,p", [(0, 4, 32, 32, 0.6), (1, 9, 77, 768, 0.8), (2, 3, 50, 2304, 0.5),
+                                          (3, 2, 40, 8, 1.0), (4, 2, 40, 8, 0.0), (5, 64, 128, 1024, 0.8)])
+def test_unpad_pad_rows_bit_exact(mb, dtype, seed, B, L, W, p):
+    print("unpad/pad seed=%d B=%d L=%d W=%d p=%.1f %s" % (seed, B, L, W, p, dtype), flush=True)
+    mask = wl.random_mask(seed + 100, B, L, p)
+    _, _, idx, T, _ = orc.unpad_index(mask)
+    rng = np.random.default_rng(seed)
+    X = wl.round_to_bf16(rng.standard_normal((B, L, W), dtype=np.float32))
+    X[0, 0, 0] = np.nan if mask[0, 0] == 0 else X[0, 0, 0]        # garbage in a padded row must not leak
+    Xd = torch.from_numpy(X).to(dtype).cuda().view(B * L, W)
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(mask).cuda())
+    sentinel = 12288.0
+    packed = torch.full((B * L + 3, W), sentinel, dtype=dtype, device="cuda")
+    mb.mb_unpad(Xd, indices, B * L, meta, out=packed)
+    ref = orc.unpad(X, idx)
+    got = packed.float().cpu().numpy()
+    assert np.array_equal(got[:T], ref.astype(np.float32)), "gather mismatch"
+    assert np.all(got[T:] == sentinel), "rows beyond T were touched"
+    padded = torch.full((B * L, W), sentinel, dtype=dtype, device="cuda")
+    mb.mb_pad(packed, indices, B * L, meta, B, L, out=padded)
+    ref_pad = orc.pad(ref, idx, B, L).astype(np.float32)
+    gotp = padded.float().cpu().numpy().reshape(B, L, W)
+    assert np.array_equal(gotp, ref_pad)
+    # padded positions are all-zero BITS (not -0.0)
+    raw = padded.view(torch.int16 if dtype == torch.bfloat16 else torch.int32).cpu().numpy().reshape(B, L, W)
+    assert np.all(raw[mask == 0] == 0)
+    # without meta (host-known T): same result
+    if T > 0:
+        packed2 = torch.full((T, W), sentinel, dtype=dtype, device="cuda")
+        mb.mb_unpad(Xd, indices, T, None, out=packed2)
+        assert torch.equal(packed2, packed[:T])
+
+
+# ------------------------------------------------------------------ attention, fp32 generic path
+def test_tiny_fp32_full_path(mb):
+    b = wl.make_batch("tiny")
+    slopes = mb.mb_alibi_slopes(2)
+    assert np.array_equal(slopes.numpy(), orc.alibi_slopes(2).astype(np.float32))
+    got = run_hip_path(mb, b, slopes, bf16=False)
+    check_index_maps(got, b["mask"])
+    ref = run_oracle(b, slopes.double().numpy())
+    compare_attention(got, ref, b["mask"], F32_TOL, 1e-4, "tiny fp32")
+
+
+@pytest.mark.parametrize("D,H,lengths,L", [(16, 2, [1, 2, 65, 64, 0, 130], 130), (128, 1, [33, 7], 40), (4, 3, [200], 200)])
+def test_generic_fp32_shapes(mb, D, H, lengths, L):
+    c = wl.random_attention_case(21, lengths, L, H, D)
+    slopes = mb.mb_alibi_slopes(H)
+    got = run_hip_path(mb, c, slopes, bf16=False)
+    check_index_maps(got, c["mask"])
+    ref = run_oracle(c, slopes.double().numpy())
+    compare_attention(got, ref, c["mask"], F32_TOL, 1e-4, "generic fp32 D=%d" % D)
+
+
+def test_fp32_scale_one_matches_eq1_literally(mb):
+    """Eq. 1 as printed has no 1/sqrt(d): scale = 1."""
+    c = wl.random_attention_case(22, [9, 31], 31, 2, 16, std=0.5)
+    slopes = mb.mb_alibi_slopes(2)
+    got = run_hip_path(mb, c, slopes, bf16=False, scale=1.0)
+    ref = run_oracle(c, slopes.double().numpy(), scale=1.0)
+    compare_attention(got, ref, c["mask"], F32_TOL, 1e-4, "fp32 scale=1")
+
+
+# ------------------------------------------------------------------ attention, bf16 matrix-core path
+@pytest.mark.parametrize("name,lengths,L,H,std,v_std", [
+    ("ragged-small", [5, 17, 32, 9, 1, 0, 33, 64, 31, 128, 127, 97], 128, 3, 1.0, 1.0),
+    ("sharp", [128, 100, 60, 16], 128, 4, 1.0, 1.0),
+    ("soft", [128, 77, 128, 19], 128, 12, 0.125, 0.125),
+    # logits of a few hundred: exercises the max subtraction; V kept O(1) because the absolute
+    # tolerance is stated for O(1) outputs (bf16 rounding alone is 2^-9 relative)
+    ("large-logits", [128, 45, 90], 128, 2, 4.0, 0.5),
+    ("multi-tile", [129, 300, 257, 64, 511, 1], 512, 2, 0.5, 0.5),
+])
+def test_bf16_attention_cases(mb, name, lengths, L, H, std, v_std):
+    print("bf16 case", name, flush=True)
+    c = wl.random_attention_case(31, lengths, L, H, 64, std=std, bf16=True, v_std=v_std)
+    slopes = mb.mb_alibi_slopes(H)
+    got = run_hip_path(mb, c, slopes, bf16=True)
+    check_index_maps(got, c["mask"])
+    ref = run_oracle(c, slopes.double().numpy())
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 " + name, abs_floor_ulps=(name == "large-logits"))
+
+
+def test_bf16_zero_slopes_and_scale_one(mb):
+    c = wl.random_attention_case(32, [128, 50, 3], 128, 2, 64, std=0.3, bf16=True)
+    slopes = torch.zeros(2)
+    got = run_hip_path(mb, c, slopes, bf16=True, scale=1.0)
+    ref = run_oracle(c, np.zeros(2), scale=1.0)
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 zero slopes")
+
+
+@pytest.mark.parametrize("name", ["bert_base", "bert_large"])
+def test_bf16_full_size_workloads(mb, name):
+    """The benchmark's workloads at full size, every sequence and head checked."""
+    print("full-size", name, flush=True)
+    b = wl.make_batch(name)
+    H = b["workload"].H
+    slopes = mb.mb_alibi_slopes(H)
+    got = run_hip_path(mb, b, slopes, bf16=True)
+    check_index_maps(got, b["mask"])
+    ref = run_oracle(b, slopes.double().numpy())
+    compare_attention(got, ref, b["mask"], BF16_TOL, 1e-3, name)
+
+
+@pytest.mark.parametrize("name,nseq", [("long512", 12), ("ragged2048", 6)])
+def test_bf16_long_workloads_sampled(mb, name, nseq):
+    """Long workloads at full size on the GPU; the oracle checks a sample of sequences (each cropped
+    to its own length, which does not change its result), always including the longest and shortest."""
+    print("full-size sampled", name, flush=True)
+    b = wl.make_batch(name)
+    H, L = b["workload"].H, b["workload"].L
+    slopes = mb.mb_alibi_slopes(H)
+    got = run_hip_path(mb, b, slopes, bf16=True)
+    check_index_maps(got, b["mask"])
+    order = np.argsort(b["lengths"])
+    pick = sorted(set([int(order[0]), int(order[-1])] + [int(x) for x in np.random.default_rng(5).choice(len(order), nseq, replace=False)]))
+    ref = run_oracle(b, slopes.double().numpy(), seq_ids=pick)
+    for key in ("o", "dq", "dk", "dv"):
+        assert np.all(got[key][b["mask"] == 0] == 0) and np.all(np.isfinite(got[key]))
+    for s in pick:
+        n = int(b["lengths"][s])
+        for key in ("o", "dq", "dk", "dv"):
+            ma, rf = err_stats(got[key][s, :n], ref[s][key])
+            assert ma <= BF16_TOL[0] and rf <= BF16_TOL[1], "%s seq %d (len %d) %s: %.3e %.3e" % (name, s, n, key, ma, rf)
+        lse_got = got["lse"][:, got["cu"][s]:got["cu"][s + 1]]
+        assert np.max(np.abs(lse_got - ref[s]["lse"])) <= 1e-3
+    print(name, "sampled sequences", pick, "ok", flush=True)
+
+
+def test_bf16_run_to_run_bitwise_identical(mb):
+    b = wl.make_batch("bert_base", batch=32)
+    slopes = mb.mb_alibi_slopes(12)
+    a = run_hip_path(mb, b, slopes, bf16=True)
+    c = run_hip_path(mb, b, slopes, bf16=True)
+    assert torch.equal(a["o_packed"], c["o_packed"]) and torch.equal(a["lse_dev"], c["lse_dev"])
+    assert torch.equal(a["dqkv_packed"], c["dqkv_packed"])
+
+
+def test_bf16_outputs_do_not_write_outside_their_rows(mb):
+    """Guard rows after T and the gap columns of a strided output stay untouched."""
+    c = wl.random_attention_case(33, [100, 28], 128, 2, 64, std=0.5, bf16=True)
+    B, L, H, D = c["q"].shape
+    mask_d = torch.from_numpy(c["mask"]).cuda()
+    seqlens, cu, indices, meta = mb.mb_unpad_index(mask_d)
+    T, mx = mb.mb_read_meta(meta)
+    qkv = to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(B * L, 3 * H * D), True)
+    qkv = mb.mb_unpad(qkv, indices, B * L, meta)[:T].view(T, 3, H, D)
+    dout = mb.mb_unpad(to_dev(c["do"].reshape(B * L, H * D), True), indices, B * L, meta)[:T].view(T, H, D)
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    guard = 777.0
+    obuf = torch.full((T + 4, 2, H, D), guard, dtype=torch.bfloat16, device="cuda")      # stride 2*H*D, slot 0 used
+    lse = torch.full((H, T), guard, dtype=torch.float32, device="cuda")
+    o, _ = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, mx, slopes, c["scale"], out=obuf[:T, 0], lse=lse)
+    gbuf = torch.full((T + 4, 4, H, D), guard, dtype=torch.bfloat16, device="cuda")
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, mx, slopes, c["scale"],
+                         dq=gbuf[:T, 0], dk=gbuf[:T, 1], dv=gbuf[:T, 2])
+    torch.cuda.synchronize()
+    assert torch.all(obuf[T:] == guard) and torch.all(obuf[:T, 1] == guard) and not torch.any(obuf[:T, 0] == guard)
+    assert torch.all(gbuf[T:] == guard) and torch.all(gbuf[:T, 3] == guard)
+    assert not torch.any(lse == guard)
+    # strided result equals the dense one
+    o2, lse2 = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, mx, slopes, c["scale"])
+    assert torch.equal(o2, obuf[:T, 0]) and torch.equal(lse2, lse)
