@@ -1,10 +1,6 @@
-// temporary: routes bf16 D=64 to the generic kernels until the matrix-core kernels land
+// temporary: routes bf16 D=64 backward to the generic kernels until the matrix-core kernel lands
 #include "common.h"
 namespace mb {
-mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
-                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream) {
-  return launch_attn_fwd_generic(s, MB_BF16, q, k, v, qs, ks, vs, o, os, lse, stream);
-}
 mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void* q, const void* k, const void* v,
                                const void* o, const float* lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
                                int64_t os, void* dq, void* dk, void* dv, int64_t dqs, int64_t dks, int64_t dvs,

@@ -1,0 +1,190 @@
+// Forward ALiBi attention on the matrix cores: bf16, head_dim 64, variable-length packed sequences.
+//
+// Computes the attention weights of the paper's Eq. 1, softmax_j(scale * q_i.k_j - m_h*|i-j|), and
+// O = P V tile by tile with a running (online) softmax, so the score matrix never leaves the chip
+// ("FlashAttention" paragraph).  The bias is evaluated in registers from the token distance.
+//
+// Work split: one workgroup (4 waves) per (sequence, head, tile of 128 queries); wave w owns queries
+// 32w..32w+31 of the tile.  K and V tiles of 128 keys are staged in LDS and shared by the 4 waves.
+// Scores are produced TRANSPOSED, S^T = K Q^T (keys along accumulator rows, queries along lanes), so
+//   * a query's row statistics (max, sum) are reductions over a lane's own registers plus one
+//     exchange with the partner lane l^32, and
+//   * the accumulator tile, rounded to bf16, is already the B operand of O^T += V^T P^T.
+#include "common.h"
+#include "mfma_util.h"
+
+namespace mb {
+namespace {
+
+constexpr int kBlockQ = 128;   // queries per workgroup
+constexpr int kBlockK = 128;   // keys per LDS tile
+constexpr int kD = 64;
+constexpr int kKStride = 72;   // LDS row pitch of K in bf16 (144 B): 16-byte row reads spread over banks
+constexpr int kVStride = 80;   // LDS row pitch of V in bf16 (160 B): 4-row transposing reads spread over banks
+
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
+    int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T) {
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockK * kKStride];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockK * kVStride];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int start = cu[b];
+  const int n = cu[b + 1] - start;
+  const int q0 = blockIdx.x * kBlockQ;
+  if (q0 >= n) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int qw = q0 + 32 * wave;          // first query of this wave
+  const bool wave_active = qw < n;
+  const int qi = qw + c;                  // this lane's query (position inside the sequence)
+  const float cs = scale * kLog2e;        // scores are kept in base-2 units
+  const float slope2 = slopes[h] * kLog2e;
+
+  // Q^T fragments (B operand of S^T = K Q^T): lane = query column, 8 consecutive d per k-step.
+  bf16x8 bq[4];
+  {
+    const uint16_t* qrow = q + (int64_t)(start + qi) * qs + h * kD + 8 * g;
+    const bool ok = wave_active && qi < n;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (ok) t = *reinterpret_cast<const u32x4*>(qrow + 16 * s);
+      bq[s] = as_bf16x8(t);
+    }
+  }
+
+  f32x16 oacc[2];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.f; oacc[1][i] = 0.f; }
+  float m_run = -INFINITY;   // running row maximum (base-2 units), identical in both half-waves
+  float l_run = 0.f;         // running row sum, this half-wave's share
+
+  // per-lane pieces of the transposing V reads
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);          // + 4g: this half-wave's keys inside a group of 8
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+
+  for (int j0 = 0; j0 < n; j0 += kBlockK) {
+    if (j0 > 0) __syncthreads();  // everyone is done with the previous tile
+    // ---- stage K, V rows j0..j0+127 of this head in LDS (zeros beyond the sequence end)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int id = tid + 256 * it;
+      const int row = id >> 3, col = (id & 7) * 8;
+      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
+      if (j0 + row < n) {
+        tk = *reinterpret_cast<const u32x4*>(k + (int64_t)(start + j0 + row) * ks + h * kD + col);
+        tv = *reinterpret_cast<const u32x4*>(v + (int64_t)(start + j0 + row) * vs + h * kD + col);
+      }
+      *reinterpret_cast<u32x4*>(&sK[row * kKStride + col]) = tk;
+      *reinterpret_cast<u32x4*>(&sV[row * kVStride + col]) = tv;
+    }
+    __syncthreads();
+    if (!wave_active) continue;
+
+    const int rem = n - j0;                                  // keys left, > 0
+    const int nblk = rem >= kBlockK ? 4 : (rem + 31) >> 5;   // 32-key blocks in this tile
+
+    // ---- S^T = K Q^T
+    f32x16 sacc[4];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[jb][i] = 0.f;
+      if (jb < nblk) {
+        const uint16_t* krow = &sK[(jb * 32 + c) * kKStride + 8 * g];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
+      }
+    }
+
+    // ---- scale, bias, mask, tile maximum
+    const float fi = (float)(qi - j0 - 4 * g);
+    const int lim = rem - 4 * g;  // key (jb*32 + 8*(v/4) + v%4) is real iff that number < lim
+    float mt = -INFINITY;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      if (jb < nblk) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
+          float x = fmaf(sacc[jb][i], cs, -slope2 * fabsf(fi - (float)cj));
+          if (rem < kBlockK && cj >= lim) x = -INFINITY;
+          sacc[jb][i] = x;
+          mt = fmaxf(mt, x);
+        }
+      }
+    }
+    mt = max_both_halves(mt);
+    const float m_new = fmaxf(m_run, mt);
+    if (j0 > 0) {
+      const float alpha = fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
+    }
+    m_run = m_new;
+
+    // ---- P^T = exp2(S^T - m), row sums, and O^T += V^T P^T
+    float lsum = 0.f;
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      if (jb < nblk) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float p = fast_exp2(sacc[jb][i] - m_new);
+          sacc[jb][i] = p;
+          lsum += p;
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          const bf16x8 bp = pack8(sacc[jb][8 * kk + 0], sacc[jb][8 * kk + 1], sacc[jb][8 * kk + 2],
+                                  sacc[jb][8 * kk + 3], sacc[jb][8 * kk + 4], sacc[jb][8 * kk + 5],
+                                  sacc[jb][8 * kk + 6], sacc[jb][8 * kk + 7]);
+          // keys of this k-step: jb*32 + 16*kk + {4g..4g+3} and the same + 8
+          const uint16_t* vbase = &sV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const s16x4 lo = lds_read_tr4(vbase + 32 * db);
+            const s16x4 hi = lds_read_tr4(vbase + 32 * db + 8 * kVStride);
+            oacc[db] = mfma32(join_tr(lo, hi), bp, oacc[db]);
+          }
+        }
+      }
+    }
+    l_run += lsum;
+  }
+
+  if (!wave_active || qi >= n) return;
+  const float l = sum_both_halves(l_run);   // NB: executed by both lanes of a pair (qi is the same)
+  const float inv = 1.f / l;
+  uint16_t* orow = o + (int64_t)(start + qi) * os + h * kD + 4 * g;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u32x2 w;
+      w[0] = pack_bf16(oacc[db][4 * r + 0] * inv, oacc[db][4 * r + 1] * inv);
+      w[1] = pack_bf16(oacc[db][4 * r + 2] * inv, oacc[db][4 * r + 3] * inv);
+      *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * r) = w;
+    }
+  }
+  if (g == 0) lse[(int64_t)h * T + start + qi] = (m_run + __log2f(l)) * kLn2;
+}
+
+}  // namespace
+
+mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
+                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream) {
+  const int tiles = (s.max_seqlen + kBlockQ - 1) / kBlockQ;
+  if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+                     (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
+                     (uint16_t*)o, os, lse, s.T);
+  return check_launch("attn_fwd_mfma_kernel");
+}
+
+}  // namespace mb
