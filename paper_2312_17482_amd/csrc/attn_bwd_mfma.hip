@@ -1,11 +1,339 @@
-// temporary: routes bf16 D=64 backward to the generic kernels until the matrix-core kernel lands
+// Backward ALiBi attention on the matrix cores: bf16, head_dim 64, variable-length packed sequences.
+//
+// Gradient of sum(O * dO) for the attention of the paper's Eq. 1 (the paper prints no backward; this is
+// the standard derivative, with P recomputed from Q, K and the saved row log-sum-exp instead of being
+// stored -- the same trade the "FlashAttention" paragraph describes for the forward):
+//   Delta_i = dO_i . O_i,  P_ij = exp(S_ij - lse_i),  dV_j = sum_i P_ij dO_i,  dP_ij = dO_i . v_j,
+//   dS_ij = P_ij (dP_ij - Delta_i),  dQ_i = scale sum_j dS_ij k_j,  dK_j = scale sum_i dS_ij q_i.
+//
+// Three kernels, no atomics (results are bitwise reproducible):
+//   delta : Delta = rowsum(dO * O), [H, T] float.
+//   dkv   : one workgroup per (sequence, head, 128 keys); wave w owns 32 keys and walks all queries.
+//           Scores in natural orientation S = Q K^T (queries along accumulator rows, keys along
+//           lanes) so that P and dS, rounded to bf16, are directly the B operands of
+//           dV^T += dO^T P and dK^T += Q^T dS.
+//   dq    : one workgroup per (sequence, head, 128 queries); wave w owns 32 queries and walks all keys.
+//           Transposed scores S^T = K Q^T (as in the forward) so that dS^T is directly the B operand
+//           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.
+// Masking costs nothing: rows beyond the sequence end are staged as zeros and their lse as +inf
+// (P = 0); zero K/V rows make the products with out-of-range keys vanish.
 #include "common.h"
+#include "mfma_util.h"
+
 namespace mb {
+namespace {
+
+constexpr int kD = 64;
+constexpr int kTile = 128;
+constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
+
+// ------------------------------------------------------------------------------------------------ delta
+// 8 lanes per (token, head) row: 16 bytes of dO and O each, then a 3-step butterfly.
+__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
+                                                             const uint16_t* __restrict__ o, int64_t dos, int64_t os,
+                                                             int T, int H, float* __restrict__ delta) {
+  const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
+  const int sub = threadIdx.x & 7;
+  float acc = 0.f;
+  const bool ok = row < (int64_t)T * H;
+  int t = 0, h = 0;
+  if (ok) {
+    t = (int)(row / H);
+    h = (int)(row - (int64_t)t * H);
+    const u32x4 a = *reinterpret_cast<const u32x4*>(dout + (int64_t)t * dos + h * kD + 8 * sub);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(o + (int64_t)t * os + h * kD + 8 * sub);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(a[i] << 16), __uint_as_float(b[i] << 16), acc);
+      acc = fmaf(__uint_as_float(a[i] & 0xffff0000u), __uint_as_float(b[i] & 0xffff0000u), acc);
+    }
+  }
+  acc += __shfl_xor(acc, 1, 64);
+  acc += __shfl_xor(acc, 2, 64);
+  acc += __shfl_xor(acc, 4, 64);
+  if (ok && sub == 0) delta[(int64_t)h * T + t] = acc;
+}
+
+// Stage rows r0..r0+127 of one head ([*, 64] bf16, token stride `stride`) into LDS with pitch kPitch;
+// rows at or beyond n become zeros.
+__device__ __forceinline__ void stage_tile(uint16_t* dst, const uint16_t* __restrict__ src, int64_t stride,
+                                           int r0, int n, int tid) {
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int id = tid + 256 * it;
+    const int row = id >> 3, col = (id & 7) * 8;
+    u32x4 t = {0u, 0u, 0u, 0u};
+    if (r0 + row < n) t = *reinterpret_cast<const u32x4*>(src + (int64_t)(r0 + row) * stride + col);
+    *reinterpret_cast<u32x4*>(&dst[row * kPitch + col]) = t;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ dK, dV
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
+    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
+    int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
+    float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T) {
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[kTile * kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t sG[kTile * kPitch];   // dO
+  __shared__ __attribute__((aligned(16))) float sLse[kTile];             // lse in base-2 units, +inf past the end
+  __shared__ __attribute__((aligned(16))) float sDelta[kTile];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int start = cu[b];
+  const int n = cu[b + 1] - start;
+  const int kv0 = blockIdx.x * kTile;
+  if (kv0 >= n) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int kw = kv0 + 32 * wave;
+  const bool wave_active = kw < n;
+  const int kj = kw + c;                      // this lane's key
+  const float cs = scale * kLog2e;
+  const float slope2 = slopes[h] * kLog2e;
+
+  // K^T and V^T fragments (B operands): lane = key column, 8 consecutive d per k-step.
+  bf16x8 bk[4], bv[4];
+  {
+    const bool ok = wave_active && kj < n;
+    const uint16_t* krow = k + (int64_t)(start + kj) * ks + h * kD + 8 * g;
+    const uint16_t* vrow = v + (int64_t)(start + kj) * vs + h * kD + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
+      if (ok) {
+        tk = *reinterpret_cast<const u32x4*>(krow + 16 * s);
+        tv = *reinterpret_cast<const u32x4*>(vrow + 16 * s);
+      }
+      bk[s] = as_bf16x8(tk);
+      bv[s] = as_bf16x8(tv);
+    }
+  }
+
+  f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows (two blocks of 32), keys along lanes
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
+
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+
+  for (int i0 = 0; i0 < n; i0 += kTile) {
+    if (i0 > 0) __syncthreads();
+    stage_tile(sQ, q + (int64_t)start * qs + h * kD, qs, i0, n, tid);
+    stage_tile(sG, dout + (int64_t)start * dos + h * kD, dos, i0, n, tid);
+    if (tid < kTile) {
+      const bool ok = i0 + tid < n;
+      sLse[tid] = ok ? lse[(int64_t)h * T + start + i0 + tid] * kLog2e : INFINITY;
+      sDelta[tid] = ok ? delta[(int64_t)h * T + start + i0 + tid] : 0.f;
+    }
+    __syncthreads();
+    if (!wave_active) continue;
+
+    const int rem = n - i0;
+    const int nblk = rem >= kTile ? 4 : (rem + 31) >> 5;
+    const float fj = (float)(kj - i0 - 4 * g);
+#pragma unroll 1
+    for (int ib = 0; ib < nblk; ++ib) {
+      // S = Q K^T and dP = dO V^T for queries i0+32ib.., this wave's keys
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+      const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
+      const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
+        pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
+      }
+      // P = exp2(S*cs - slope2*|i-j| - lse2_i),  dS = P (dP - Delta_i); accumulator row = query
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
+        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+        const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * r + e;
+          const float ci = (float)(32 * ib + 8 * r + e);
+          const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fj - ci));
+          const float p = fast_exp2(x - lv[e]);
+          sacc[i] = p;
+          pacc[i] = p * (pacc[i] - dl[e]);
+        }
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
+                                sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
+        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+        const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
+          dvacc[db] = mfma32(ag, bp, dvacc[db]);
+          const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
+          dkacc[db] = mfma32(aq, bs, dkacc[db]);
+        }
+      }
+    }
+  }
+
+  if (!wave_active || kj >= n) return;
+  uint16_t* dkrow = dk + (int64_t)(start + kj) * dks + h * kD + 4 * g;
+  uint16_t* dvrow = dv + (int64_t)(start + kj) * dvs + h * kD + 4 * g;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u32x2 w;
+      w[0] = pack_bf16(dkacc[db][4 * r + 0] * scale, dkacc[db][4 * r + 1] * scale);
+      w[1] = pack_bf16(dkacc[db][4 * r + 2] * scale, dkacc[db][4 * r + 3] * scale);
+      *reinterpret_cast<u32x2*>(dkrow + 32 * db + 8 * r) = w;
+      w[0] = pack_bf16(dvacc[db][4 * r + 0], dvacc[db][4 * r + 1]);
+      w[1] = pack_bf16(dvacc[db][4 * r + 2], dvacc[db][4 * r + 3]);
+      *reinterpret_cast<u32x2*>(dvrow + 32 * db + 8 * r) = w;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ dQ
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
+    int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
+    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T) {
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kTile * kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kTile * kPitch];
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int start = cu[b];
+  const int n = cu[b + 1] - start;
+  const int q0 = blockIdx.x * kTile;
+  if (q0 >= n) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int qw = q0 + 32 * wave;
+  const bool wave_active = qw < n;
+  const int qi = qw + c;
+  const bool q_ok = wave_active && qi < n;
+  const float cs = scale * kLog2e;
+  const float slope2 = slopes[h] * kLog2e;
+
+  bf16x8 bq[4], bg[4];   // Q^T and dO^T fragments (B operands): lane = query column
+  {
+    const uint16_t* qrow = q + (int64_t)(start + qi) * qs + h * kD + 8 * g;
+    const uint16_t* grow = dout + (int64_t)(start + qi) * dos + h * kD + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 tq = {0u, 0u, 0u, 0u}, tg = {0u, 0u, 0u, 0u};
+      if (q_ok) {
+        tq = *reinterpret_cast<const u32x4*>(qrow + 16 * s);
+        tg = *reinterpret_cast<const u32x4*>(grow + 16 * s);
+      }
+      bq[s] = as_bf16x8(tq);
+      bg[s] = as_bf16x8(tg);
+    }
+  }
+  const float lse2 = q_ok ? lse[(int64_t)h * T + start + qi] * kLog2e : INFINITY;
+  const float dlt = q_ok ? delta[(int64_t)h * T + start + qi] : 0.f;
+
+  f32x16 dqacc[2];   // dQ^T: d along accumulator rows, queries along lanes
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
+
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+
+  for (int j0 = 0; j0 < n; j0 += kTile) {
+    if (j0 > 0) __syncthreads();
+    stage_tile(sK, k + (int64_t)start * ks + h * kD, ks, j0, n, tid);
+    stage_tile(sV, v + (int64_t)start * vs + h * kD, vs, j0, n, tid);
+    __syncthreads();
+    if (!wave_active) continue;
+
+    const int rem = n - j0;
+    const int nblk = rem >= kTile ? 4 : (rem + 31) >> 5;
+    const float fi = (float)(qi - j0 - 4 * g);
+    const int lim = rem - 4 * g;   // key (32jb + 8*(i/4) + i%4) of this half-wave is real iff that number < lim
+#pragma unroll 1
+    for (int jb = 0; jb < nblk; ++jb) {
+      f32x16 sacc, pacc;   // S^T = K Q^T, dP^T = V dO^T: keys along accumulator rows
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+      const uint16_t* krow = &sK[(32 * jb + c) * kPitch + 8 * g];
+      const uint16_t* vrow = &sV[(32 * jb + c) * kPitch + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sacc = mfma32(lds_read8(krow + 16 * s), bq[s], sacc);
+        pacc = mfma32(lds_read8(vrow + 16 * s), bg[s], pacc);
+      }
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float cj = (float)(32 * jb + 8 * (i >> 2) + (i & 3));
+        const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fi - cj));
+        const float p = fast_exp2(x - lse2);
+        float ds = p * (pacc[i] - dlt);
+        // a key past the sequence end has a zero K row, but its p may overflow (its score was never
+        // part of lse): force the product with that zero row to be 0, not inf * 0
+        if (rem < kTile && 32 * jb + 8 * (i >> 2) + (i & 3) >= lim) ds = 0.f;
+        pacc[i] = ds;
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+        const int roff = (32 * jb + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const bf16x8 ak = join_tr(lds_read_tr4(&sK[roff + 32 * db]), lds_read_tr4(&sK[roff + 32 * db + 8 * kPitch]));
+          dqacc[db] = mfma32(ak, bs, dqacc[db]);
+        }
+      }
+    }
+  }
+
+  if (!q_ok) return;
+  uint16_t* dqrow = dq + (int64_t)(start + qi) * dqs + h * kD + 4 * g;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u32x2 w;
+      w[0] = pack_bf16(dqacc[db][4 * r + 0] * scale, dqacc[db][4 * r + 1] * scale);
+      w[1] = pack_bf16(dqacc[db][4 * r + 2] * scale, dqacc[db][4 * r + 3] * scale);
+      *reinterpret_cast<u32x2*>(dqrow + 32 * db + 8 * r) = w;
+    }
+  }
+}
+
+}  // namespace
+
 mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void* q, const void* k, const void* v,
                                const void* o, const float* lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
                                int64_t os, void* dq, void* dk, void* dv, int64_t dqs, int64_t dks, int64_t dvs,
                                float* delta_ws, hipStream_t stream) {
-  return launch_attn_bwd_generic(s, MB_BF16, dout, q, k, v, o, lse, dos, qs, ks, vs, os, dq, dk, dv, dqs, dks, dvs,
-                                 delta_ws, stream);
+  if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
+  const int64_t rows = (int64_t)s.T * s.H;
+  hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream,
+                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, delta_ws);
+  mb_status st = check_launch("attn_bwd_delta_kernel");
+  if (st != MB_OK) return st;
+  const int tiles = (s.max_seqlen + kTile - 1) / kTile;
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T);
+  st = check_launch("attn_bwd_dkv_kernel");
+  if (st != MB_OK) return st;
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T);
+  return check_launch("attn_bwd_dq_kernel");
 }
+
 }  // namespace mb
