@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: unpad -> ALiBi varlen attention fwd+bwd -> pad.
+
+One "step" is one pass of the whole path over one synthetic batch that is already resident in HBM:
+  mb_unpad_index(mask) -> mb_read_meta -> mb_unpad(fused QKV), mb_unpad(dO) -> mb_alibi_attn_fwd ->
+  mb_alibi_attn_bwd -> mb_pad(O), mb_pad(dQKV).
+Prints ONE JSON line.  `value` = attention flops on real tokens (14*H*D*sum(len^2): forward QK^T and PV,
+backward's five products including the recomputation of the scores) divided by the whole step time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (2.5 PFLOP/s)
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by
+# what the same counters read for a plain copy of known size (see profiles/).  None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bert_base")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--detail", action="store_true", help="also time each call of the path separately")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path needs no communication; every box has "
+              "one GPU). --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2312_17482_amd import binding as mb      # raises if the HIP library is missing
+    from paper_2312_17482_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    batch = wl.make_batch(args.workload)
+    w = batch["workload"]
+    B, L, H, D = w.B, w.L, w.H, w.D
+    bf16 = w.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    lengths = batch["lengths"]
+    T_host = int(lengths.sum())
+    f_fwd, f_bwd = wl.attention_flops(lengths, H, D)
+
+    def dev_t(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).to(tdt).to(dev)
+
+    mask = torch.from_numpy(batch["mask"]).to(dev)
+    qkv_padded = dev_t(np.concatenate([batch[x].reshape(B * L, H * D) for x in ("q", "k", "v")], axis=1))
+    do_padded = dev_t(batch["do"].reshape(B * L, H * D))
+    slopes = mb.mb_alibi_slopes(H).to(dev)
+    scale = batch["scale"]
+
+    # every buffer of the step is allocated once, at capacity B*L
+    cap = B * L
+    qkv = torch.empty((cap, 3, H, D), dtype=tdt, device=dev)
+    dout = torch.empty((cap, H, D), dtype=tdt, device=dev)
+    o = torch.empty((cap, H, D), dtype=tdt, device=dev)
+    dqkv = torch.empty((cap, 3, H, D), dtype=tdt, device=dev)
+    o_padded = torch.empty((cap, H * D), dtype=tdt, device=dev)
+    dqkv_padded = torch.empty((cap, 3 * H * D), dtype=tdt, device=dev)
+    ws_bytes = mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16 if bf16 else mb.MB_F32)
+    workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    lse_buf = torch.empty(H * cap, dtype=torch.float32, device=dev)
+    seqlens = torch.empty(B, dtype=torch.int32, device=dev)
+    cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    indices = torch.empty(cap, dtype=torch.int32, device=dev)
+    meta = torch.empty(2, dtype=torch.int32, device=dev)
+    lib = mb.raw()
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream
+
+    ev = {}
+
+    def step(record=None):
+        st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
+                                meta.data_ptr(), sp)
+        assert st == 0, mb.mb_last_error()
+        T, max_seqlen = mb.mb_read_meta(meta)
+        mb.mb_unpad(qkv_padded, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
+        mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
+        q_, k_, v_ = qkv[:T, 0], qkv[:T, 1], qkv[:T, 2]
+        lse = lse_buf[:H * T].view(H, T)
+        if record is not None:
+            record[0].record(stream)
+        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, max_seqlen, slopes, scale, out=o[:T], lse=lse)
+        if record is not None:
+            record[1].record(stream)
+        mb.mb_alibi_attn_bwd(dout[:T], q_, k_, v_, o[:T], lse, cu, max_seqlen, slopes, scale,
+                             dq=dqkv[:T, 0], dk=dqkv[:T, 1], dv=dqkv[:T, 2], workspace=workspace)
+        if record is not None:
+            record[2].record(stream)
+        mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
+        mb.mb_pad(dqkv.view(cap, 3 * H * D), indices, cap, meta, B, L, out=dqkv_padded)
+        return T
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        T = step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    assert T == T_host
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+
+    value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) * 1e-12
+    esize = 2 if bf16 else 4
+    out = {
+        "metric": "ALiBi varlen attention fwd+bwd TFLOP/s (whole unpad->attention->pad step)",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": "%s: B=%d L=%d H=%d D=%d, T=%d real tokens, sum(len^2)=%d" % (
+            w.name, B, L, H, D, T_host, int((lengths.astype(np.int64) ** 2).sum()))},
+        "tokens_per_s": round(T_host / (ms_per_step * 1e-3), 1),
+        "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 3),
+        "attention_only": {
+            "fwd_ms": round(fwd_ms, 5), "bwd_ms": round(bwd_ms, 5),
+            "fwd_tflops": round(f_fwd / (fwd_ms * 1e-3) * 1e-12, 2),
+            "bwd_tflops": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2),
+            "fwd_bwd_tflops": round((f_fwd + f_bwd) / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12, 2),
+            "fwd_bwd_tflops_no_recompute_convention": round((f_fwd + f_bwd) * 12.0 / 14.0 / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12, 2),
+            "pct_of_bf16_mfma_peak": round(100.0 * (f_fwd + f_bwd) / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 3),
+        },
+        "roofline": {
+            "kernel": "mb_alibi_attn_bwd (backward attention call)", "bound": "mfma",
+            "achieved": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(f_bwd / (bwd_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 5),
+            "traffic": MEASURED_TRAFFIC.get(w.name),
+        },
+        "paper_context": "MosaicBERT-Base: 79.6 GLUE in 1.13 h on 8xA100-80GB (end-to-end pretraining; not comparable)",
+    }
+
+    if args.detail:
+        out["detail_us"] = time_each_call(mb, lib, locals())
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(batch, f_fwd + f_bwd)
+    print(json.dumps(out))
+
+
+def time_each_call(mb, lib, env):
+    """Each call of the path alone, 50 back-to-back launches between two events (amortises launch gaps)."""
+    import torch
+    g = env
+    T, max_seqlen = mb.mb_read_meta(g["meta"])
+    B, L, H, D, cap = g["B"], g["L"], g["H"], g["D"], g["cap"]
+    qkv, dout, o, dqkv = g["qkv"], g["dout"], g["o"], g["dqkv"]
+    q_, k_, v_ = qkv[:T, 0], qkv[:T, 1], qkv[:T, 2]
+    lse = g["lse_buf"][:H * T].view(H, T)
+    calls = {
+        "unpad_index": lambda: lib.mb_unpad_index(g["mask"].data_ptr(), B, L, g["seqlens"].data_ptr(), g["cu"].data_ptr(),
+                                                  g["indices"].data_ptr(), g["meta"].data_ptr(), g["sp"]),
+        "unpad_qkv": lambda: mb.mb_unpad(g["qkv_padded"], g["indices"], cap, g["meta"], out=qkv.view(cap, 3 * H * D)),
+        "unpad_do": lambda: mb.mb_unpad(g["do_padded"], g["indices"], cap, g["meta"], out=dout.view(cap, H * D)),
+        "attn_fwd": lambda: mb.mb_alibi_attn_fwd(q_, k_, v_, g["cu"], max_seqlen, g["slopes"], g["scale"], out=o[:T], lse=lse),
+        "attn_bwd": lambda: mb.mb_alibi_attn_bwd(dout[:T], q_, k_, v_, o[:T], lse, g["cu"], max_seqlen, g["slopes"], g["scale"],
+                                                 dq=dqkv[:T, 0], dk=dqkv[:T, 1], dv=dqkv[:T, 2], workspace=g["workspace"]),
+        "pad_o": lambda: mb.mb_pad(o.view(cap, H * D), g["indices"], cap, g["meta"], B, L, out=g["o_padded"]),
+        "pad_dqkv": lambda: mb.mb_pad(dqkv.view(cap, 3 * H * D), g["indices"], cap, g["meta"], B, L, out=g["dqkv_padded"]),
+    }
+    res = {}
+    for name, fn in calls.items():
+        for _ in range(5):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(50):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        res[name] = round(a.elapsed_time(b) * 1e3 / 50, 2)
+    esize = 2 if g["bf16"] else 4
+    W1, W3 = H * D * esize, 3 * H * D * esize
+    res["unpad_qkv_GBs"] = round(2 * T * W3 / (res["unpad_qkv"] * 1e-6) * 1e-9, 1)
+    res["pad_dqkv_GBs"] = round((T + cap) * W3 / (res["pad_dqkv"] * 1e-6) * 1e-9, 1)
+    res["pad_o_GBs"] = round((T + cap) * W1 / (res["pad_o"] * 1e-6) * 1e-9, 1)
+    return res
+
+
+def cpu_baseline(batch, flops):
+    """The CPU oracle, as it stands, on the same batch (the whole path once: index maps, gather,
+    attention forward + backward, scatter), timed on this host."""
+    import numpy as np
+    from oracle import mosaic_oracle as orc
+    w = batch["workload"]
+    sub = min(w.B, 128)            # bounded sample: the first `sub` sequences of the batch
+    sl = slice(0, sub)
+    q, k, v, do, mask = (batch[x][sl] for x in ("q", "k", "v", "do", "mask"))
+    lengths = batch["lengths"][sl].astype(np.float64)
+    frac = float((lengths ** 2).sum()) * 14.0 * w.H * w.D / flops
+    slopes = orc.alibi_slopes(w.H)
+    c0, t0 = time.process_time(), time.perf_counter()
+    _, cu, idx, T, mx = orc.unpad_index(mask)
+    qp = orc.unpad(q, idx)
+    O, LSE = orc.attention_fwd(q, k, v, mask, slopes, batch["scale"])
+    dQ, dK, dV = orc.attention_bwd(do, q, k, v, mask, slopes, batch["scale"])
+    back = orc.pad(orc.unpad(O, idx), idx, sub, w.L)
+    c1, t1 = time.process_time(), time.perf_counter()
+    wall = t1 - t0
+    cores = max(1, int(round((c1 - c0) / wall)))
+    return {"value": round(flops * frac / wall * 1e-12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d of %d sequences, whole path once (fp64 numpy), %.1f s wall; host has %d cpus" % (
+                sub, w.B, wall, os.cpu_count()),
+            "tokens_per_s": round(float(lengths.sum()) / wall, 1)}
+
+
+if __name__ == "__main__":
+    main()
