@@ -312,6 +312,217 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------ fused, n <= 128
+// Whole backward of one (sequence, head) with at most 128 tokens in one workgroup: every input is read
+// from HBM once and every output written once.
+//   phase 0  Q, dO rows -> LDS; Delta = rowsum(dO * O) -> LDS (O is read only for this); lse -> LDS;
+//            each wave keeps K and V of its own 32 keys in registers.
+//   phase 1  wave w owns keys 32w..: for every block of 32 queries, S = Q K^T, dP = dO V^T, P, dS in
+//            registers; dV^T += dO^T P, dK^T += Q^T dS; dS (bf16) is also written to LDS as [key][query].
+//   phase 2  the K registers are spilled to LDS over the Q tile; wave w then owns queries 32w.. and
+//            accumulates dQ^T += K^T dS^T reading both operands with transposing LDS reads.
+constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
+
+__global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
+    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse, int64_t dos,
+    int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
+    const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
+    uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T) {
+  __shared__ __attribute__((aligned(16))) uint16_t sQ[kTile * kPitch];      // Q in phase 1, K in phase 2
+  __shared__ __attribute__((aligned(16))) uint16_t sG[kTile * kPitch];      // dO
+  __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
+  __shared__ __attribute__((aligned(16))) float sLse[kTile];
+  __shared__ __attribute__((aligned(16))) float sDelta[kTile];
+
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int start = cu[b];
+  const int n = min(cu[b + 1] - start, kTile);   // the caller promised max_seqlen <= 128
+  if (n <= 0) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int kw = 32 * wave;
+  const bool wave_active = kw < n;
+  const int kj = kw + c;
+  const float cs = scale * kLog2e;
+  const float slope2 = slopes[h] * kLog2e;
+
+  // ---- phase 0
+  bf16x8 bk[4], bv[4];
+  {
+    const bool ok = kj < n;
+    const uint16_t* krow = k + (int64_t)(start + kj) * ks + h * kD + 8 * g;
+    const uint16_t* vrow = v + (int64_t)(start + kj) * vs + h * kD + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
+      if (ok) {
+        tk = *reinterpret_cast<const u32x4*>(krow + 16 * s);
+        tv = *reinterpret_cast<const u32x4*>(vrow + 16 * s);
+      }
+      bk[s] = as_bf16x8(tk);
+      bv[s] = as_bf16x8(tv);
+    }
+  }
+  {
+    u32x4 tq[4], tg[4], to[4];
+    const int col = (tid & 7) * 8;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = 32 * it + (tid >> 3);
+      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
+      if (row < n) {
+        tq[it] = *reinterpret_cast<const u32x4*>(q + (int64_t)(start + row) * qs + h * kD + col);
+        tg[it] = *reinterpret_cast<const u32x4*>(dout + (int64_t)(start + row) * dos + h * kD + col);
+        to[it] = *reinterpret_cast<const u32x4*>(o + (int64_t)(start + row) * os + h * kD + col);
+      }
+    }
+    if (tid < kTile) sLse[tid] = tid < n ? lse[(int64_t)h * T + start + tid] * kLog2e : INFINITY;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = 32 * it + (tid >> 3);
+      *reinterpret_cast<u32x4*>(&sQ[row * kPitch + col]) = tq[it];
+      *reinterpret_cast<u32x4*>(&sG[row * kPitch + col]) = tg[it];
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc = fmaf(__uint_as_float(tg[it][i] << 16), __uint_as_float(to[it][i] << 16), acc);
+        acc = fmaf(__uint_as_float(tg[it][i] & 0xffff0000u), __uint_as_float(to[it][i] & 0xffff0000u), acc);
+      }
+      acc += __shfl_xor(acc, 1, 64);
+      acc += __shfl_xor(acc, 2, 64);
+      acc += __shfl_xor(acc, 4, 64);
+      if ((tid & 7) == 0) sDelta[row] = acc;
+    }
+  }
+  __syncthreads();
+
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+  const int nblk = (n + 31) >> 5;
+
+  // ---- phase 1
+  if (wave_active) {
+    f32x16 dkacc[2], dvacc[2];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
+    const float fj = (float)(kj - 4 * g);
+#pragma unroll 1
+    for (int ib = 0; ib < nblk; ++ib) {
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+      const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
+      const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
+        pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
+        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+        const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * r + e;
+          const float ci = (float)(32 * ib + 8 * r + e);
+          const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fj - ci));
+          const float p = fast_exp2(x - lv[e]);
+          sacc[i] = p;
+          pacc[i] = p * (pacc[i] - dl[e]);
+        }
+        // dS of queries 32ib + 8r + 4g + 0..3 for this lane's key
+        // (a key past the sequence end may hold inf/NaN here -- its score never entered lse -- and
+        // phase 2 multiplies it with a zero K row, so it must be an exact zero in LDS)
+        u32x2 w;
+        w[0] = kj < n ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
+        w[1] = kj < n ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
+        *reinterpret_cast<u32x2*>(&sDs[kj * kDsPitch + 32 * ib + 8 * r + 4 * g]) = w;
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
+                                sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
+        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+        const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
+          dvacc[db] = mfma32(ag, bp, dvacc[db]);
+          const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
+          dkacc[db] = mfma32(aq, bs, dkacc[db]);
+        }
+      }
+    }
+    if (kj < n) {
+      uint16_t* dkrow = dk + (int64_t)(start + kj) * dks + h * kD + 4 * g;
+      uint16_t* dvrow = dv + (int64_t)(start + kj) * dvs + h * kD + 4 * g;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          u32x2 w;
+          w[0] = pack_bf16(dkacc[db][4 * r + 0] * scale, dkacc[db][4 * r + 1] * scale);
+          w[1] = pack_bf16(dkacc[db][4 * r + 2] * scale, dkacc[db][4 * r + 3] * scale);
+          *reinterpret_cast<u32x2*>(dkrow + 32 * db + 8 * r) = w;
+          w[0] = pack_bf16(dvacc[db][4 * r + 0], dvacc[db][4 * r + 1]);
+          w[1] = pack_bf16(dvacc[db][4 * r + 2], dvacc[db][4 * r + 3]);
+          *reinterpret_cast<u32x2*>(dvrow + 32 * db + 8 * r) = w;
+        }
+      }
+    }
+  }
+  __syncthreads();   // all of Q has been read, all of dS written
+
+  // ---- phase 2: K registers -> LDS (over Q); rows of keys >= n are zero because bk was zero-filled
+  if (wave_active) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      *reinterpret_cast<u32x4*>(&sQ[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
+  }
+  __syncthreads();
+  if (!wave_active) return;   // queries 32*wave.. do not exist
+
+  f32x16 dqacc[2];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
+#pragma unroll 1
+  for (int jb = 0; jb < nblk; ++jb) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int krow = 32 * jb + 16 * kk + tr_row;
+      const bf16x8 bs = join_tr(lds_read_tr4(&sDs[krow * kDsPitch + kw + tr_col]),
+                                lds_read_tr4(&sDs[(krow + 8) * kDsPitch + kw + tr_col]));
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const bf16x8 ak = join_tr(lds_read_tr4(&sQ[krow * kPitch + tr_col + 32 * db]),
+                                  lds_read_tr4(&sQ[(krow + 8) * kPitch + tr_col + 32 * db]));
+        dqacc[db] = mfma32(ak, bs, dqacc[db]);
+      }
+    }
+  }
+  const int qi = kw + c;
+  if (qi >= n) return;
+  uint16_t* dqrow = dq + (int64_t)(start + qi) * dqs + h * kD + 4 * g;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u32x2 w;
+      w[0] = pack_bf16(dqacc[db][4 * r + 0] * scale, dqacc[db][4 * r + 1] * scale);
+      w[1] = pack_bf16(dqacc[db][4 * r + 2] * scale, dqacc[db][4 * r + 3] * scale);
+      *reinterpret_cast<u32x2*>(dqrow + 32 * db + 8 * r) = w;
+    }
+  }
+}
+
 }  // namespace
 
 mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void* q, const void* k, const void* v,
@@ -319,6 +530,13 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
                                int64_t os, void* dq, void* dk, void* dv, int64_t dqs, int64_t dks, int64_t dvs,
                                float* delta_ws, hipStream_t stream) {
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
+  if (s.max_seqlen <= kTile) {
+    hipLaunchKernelGGL(attn_bwd_fused128_kernel, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
+                       (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs,
+                       ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv, dqs,
+                       dks, dvs, s.T);
+    return check_launch("attn_bwd_fused128_kernel");
+  }
   const int64_t rows = (int64_t)s.T * s.H;
   hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream,
                      (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, delta_ws);
