@@ -84,29 +84,28 @@ def main():
     stream = torch.cuda.current_stream()
     sp = stream.cuda_stream
 
-    ev = {}
+    q_, k_, v_ = qkv[:, 0], qkv[:, 1], qkv[:, 2]
+    lse = lse_buf.view(H, cap)
 
     def step(record=None):
         st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
                                 meta.data_ptr(), sp)
         assert st == 0, mb.mb_last_error()
-        T, max_seqlen = mb.mb_read_meta(meta)
+        # No host round trip: the token count stays on the device (meta); the attention calls get the
+        # capacity B*L as their row count and L as the bound of the sequence length.
         mb.mb_unpad(qkv_padded, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
         mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
-        q_, k_, v_ = qkv[:T, 0], qkv[:T, 1], qkv[:T, 2]
-        lse = lse_buf[:H * T].view(H, T)
         if record is not None:
             record[0].record(stream)
-        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, max_seqlen, slopes, scale, out=o[:T], lse=lse)
+        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse)
         if record is not None:
             record[1].record(stream)
-        mb.mb_alibi_attn_bwd(dout[:T], q_, k_, v_, o[:T], lse, cu, max_seqlen, slopes, scale,
-                             dq=dqkv[:T, 0], dk=dqkv[:T, 1], dv=dqkv[:T, 2], workspace=workspace)
+        mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
+                             dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace)
         if record is not None:
             record[2].record(stream)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
         mb.mb_pad(dqkv.view(cap, 3 * H * D), indices, cap, meta, B, L, out=dqkv_padded)
-        return T
 
     for _ in range(args.warmup):
         step()
@@ -114,10 +113,11 @@ def main():
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        T = step(events[i])
+        step(events[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    assert T == T_host
+    T, max_seqlen = mb.mb_read_meta(meta)
+    assert T == T_host and max_seqlen == int(lengths.max())
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
@@ -162,19 +162,18 @@ def time_each_call(mb, lib, env):
     """Each call of the path alone, 50 back-to-back launches between two events (amortises launch gaps)."""
     import torch
     g = env
-    T, max_seqlen = mb.mb_read_meta(g["meta"])
+    T, _ = mb.mb_read_meta(g["meta"])
     B, L, H, D, cap = g["B"], g["L"], g["H"], g["D"], g["cap"]
     qkv, dout, o, dqkv = g["qkv"], g["dout"], g["o"], g["dqkv"]
-    q_, k_, v_ = qkv[:T, 0], qkv[:T, 1], qkv[:T, 2]
-    lse = g["lse_buf"][:H * T].view(H, T)
+    q_, k_, v_, lse, max_seqlen = g["q_"], g["k_"], g["v_"], g["lse"], L
     calls = {
         "unpad_index": lambda: lib.mb_unpad_index(g["mask"].data_ptr(), B, L, g["seqlens"].data_ptr(), g["cu"].data_ptr(),
                                                   g["indices"].data_ptr(), g["meta"].data_ptr(), g["sp"]),
         "unpad_qkv": lambda: mb.mb_unpad(g["qkv_padded"], g["indices"], cap, g["meta"], out=qkv.view(cap, 3 * H * D)),
         "unpad_do": lambda: mb.mb_unpad(g["do_padded"], g["indices"], cap, g["meta"], out=dout.view(cap, H * D)),
-        "attn_fwd": lambda: mb.mb_alibi_attn_fwd(q_, k_, v_, g["cu"], max_seqlen, g["slopes"], g["scale"], out=o[:T], lse=lse),
-        "attn_bwd": lambda: mb.mb_alibi_attn_bwd(dout[:T], q_, k_, v_, o[:T], lse, g["cu"], max_seqlen, g["slopes"], g["scale"],
-                                                 dq=dqkv[:T, 0], dk=dqkv[:T, 1], dv=dqkv[:T, 2], workspace=g["workspace"]),
+        "attn_fwd": lambda: mb.mb_alibi_attn_fwd(q_, k_, v_, g["cu"], max_seqlen, g["slopes"], g["scale"], out=o, lse=lse),
+        "attn_bwd": lambda: mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, g["cu"], max_seqlen, g["slopes"], g["scale"],
+                                                 dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=g["workspace"]),
         "pad_o": lambda: mb.mb_pad(o.view(cap, H * D), g["indices"], cap, g["meta"], B, L, out=g["o_padded"]),
         "pad_dqkv": lambda: mb.mb_pad(dqkv.view(cap, 3 * H * D), g["indices"], cap, g["meta"], B, L, out=g["dqkv_padded"]),
     }

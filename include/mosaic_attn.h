@@ -115,8 +115,11 @@ MB_API mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, c
  *   S_ij = softmax_scale * q_i . k_j - slopes[h] * |i - j|,   P = softmax_j(S),   O_i = sum_j P_ij v_j,
  *   lse_i = log sum_j exp(S_ij).
  *   q, k, v      dev, [T, H, D] with row strides q/k/v_row_stride (elements), read.
- *   cu_seqlens   dev, [B+1] int32, read.  T and max_seqlen are the host's copies of the batch's total
- *                token count and longest sequence (max_seqlen may be any upper bound, e.g. L).
+ *   cu_seqlens   dev, [B+1] int32, read.
+ *   T            number of token rows the packed buffers hold; T >= cu_seqlens[B].  It may be a capacity
+ *                (e.g. B*L) known without reading anything back from the device: rows at or beyond
+ *                cu_seqlens[B] are neither read nor written.  T is also the row pitch of lse.
+ *   max_seqlen   any upper bound of the longest sequence (e.g. L); sizes the launch and picks the kernel.
  *   slopes       dev, [H] float, read.
  *   o            dev, [T, H, D] with row stride o_row_stride, written.
  *   lse          dev, [H, T] float, written.

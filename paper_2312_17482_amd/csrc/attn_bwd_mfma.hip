@@ -31,11 +31,12 @@ constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
 // 8 lanes per (token, head) row: 16 bytes of dO and O each, then a 3-step butterfly.
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
                                                              const uint16_t* __restrict__ o, int64_t dos, int64_t os,
-                                                             int T, int H, float* __restrict__ delta) {
+                                                             int T, int H, const int32_t* __restrict__ cu, int B,
+                                                             float* __restrict__ delta) {
   const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
   const int sub = threadIdx.x & 7;
   float acc = 0.f;
-  const bool ok = row < (int64_t)T * H;
+  const bool ok = row < (int64_t)min(T, cu[B]) * H;   // T may be a capacity; only real tokens are touched
   int t = 0, h = 0;
   if (ok) {
     t = (int)(row / H);
@@ -539,7 +540,7 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   }
   const int64_t rows = (int64_t)s.T * s.H;
   hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream,
-                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, delta_ws);
+                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B, delta_ws);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   const int tiles = (s.max_seqlen + kTile - 1) / kTile;

@@ -46,6 +46,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
   float* sq = smem;
   float* ss = smem + D;
   const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, i = t - start;
   const float slope = slopes[h];
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
   float* sg = smem + D;
   float* sds = smem + 2 * D;
   const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, i = t - start;
   const float slope = slopes[h];
@@ -139,6 +141,7 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
   float* sp = smem + 2 * D;
   float* sds = sp + max_seqlen;
   const int t = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, j = t - start;
   const float slope = slopes[h];

@@ -250,3 +250,34 @@ def test_bf16_outputs_do_not_write_outside_their_rows(mb):
     # strided result equals the dense one
     o2, lse2 = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, mx, slopes, c["scale"])
     assert torch.equal(o2, obuf[:T, 0]) and torch.equal(lse2, lse)
+
+
+@pytest.mark.parametrize("bf16,D,L", [(True, 64, 128), (True, 64, 300), (False, 16, 64)])
+def test_capacity_mode_needs_no_host_round_trip(mb, bf16, D, L):
+    """T passed as the capacity B*L and max_seqlen as L (nothing read back from the device) gives the
+    same bits as passing the exact token count, and rows past the last real token stay untouched."""
+    lengths = [L, 17, 0, L // 2, 33]
+    c = wl.random_attention_case(41, lengths, L, 2, D, std=0.5, bf16=bf16)
+    B, _, H, _ = c["q"].shape
+    cap = B * L
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(c["mask"]).cuda())
+    qkv = mb.mb_unpad(to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(cap, 3 * H * D), bf16), indices, cap, meta).view(cap, 3, H, D)
+    dout = mb.mb_unpad(to_dev(c["do"].reshape(cap, H * D), bf16), indices, cap, meta).view(cap, H, D)
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    guard = 3.0
+    o_cap = torch.full((cap, H, D), guard, dtype=tdt, device="cuda")
+    lse_cap = torch.full((H, cap), guard, dtype=torch.float32, device="cuda")
+    mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, c["scale"], out=o_cap, lse=lse_cap)
+    g_cap = torch.full((cap, 3, H, D), guard, dtype=tdt, device="cuda")
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o_cap, lse_cap, cu, L, slopes, c["scale"],
+                         dq=g_cap[:, 0], dk=g_cap[:, 1], dv=g_cap[:, 2])
+    T, mx = mb.mb_read_meta(meta)
+    assert T == sum(lengths)
+    o_ex, lse_ex = mb.mb_alibi_attn_fwd(qkv[:T, 0], qkv[:T, 1], qkv[:T, 2], cu, mx, slopes, c["scale"])
+    g_ex = torch.empty((T, 3, H, D), dtype=tdt, device="cuda")
+    mb.mb_alibi_attn_bwd(dout[:T], qkv[:T, 0], qkv[:T, 1], qkv[:T, 2], o_ex, lse_ex, cu, mx, slopes, c["scale"],
+                         dq=g_ex[:, 0], dk=g_ex[:, 1], dv=g_ex[:, 2])
+    torch.cuda.synchronize()
+    assert torch.equal(o_cap[:T], o_ex) and torch.equal(lse_cap[:, :T], lse_ex) and torch.equal(g_cap[:T], g_ex)
+    assert torch.all(o_cap[T:] == guard) and torch.all(lse_cap[:, T:] == guard) and torch.all(g_cap[T:] == guard)
