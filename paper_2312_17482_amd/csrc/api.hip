@@ -76,7 +76,9 @@ mb_status check_attn_dims(int B, int T, int max_seqlen, int H, int D, mb_dtype d
   return MB_OK;
 }
 
-bool use_mfma(mb_dtype dt, int D) { return dt == MB_BF16 && D == 64; }
+// The matrix-core kernels fold the scale into the exponent (exp2(acc*c - max*c)), which needs c > 0;
+// any other finite scale goes through the generic kernels.
+bool use_mfma(mb_dtype dt, int D, float scale) { return dt == MB_BF16 && D == 64 && scale > 0.f; }
 
 }  // namespace
 }  // namespace mb
@@ -190,7 +192,7 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   MB_CHECK_PTR(o);
   MB_CHECK_PTR(lse);
   const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
-  if (use_mfma(dt, D))
+  if (use_mfma(dt, D, softmax_scale))
     return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
                                 (hipStream_t)stream);
   MB_REQUIRE(max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
@@ -241,7 +243,7 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
   const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
-  if (use_mfma(dt, D))
+  if (use_mfma(dt, D, softmax_scale))
     return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                 o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
                                 (float*)workspace, (hipStream_t)stream);

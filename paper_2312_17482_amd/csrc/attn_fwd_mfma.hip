@@ -175,12 +175,193 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
   if (g == 0) lse[(int64_t)h * T + start + qi] = (m_run + __log2f(l)) * kLn2;
 }
 
+
+// ------------------------------------------------------------------------------------------------ n <= 128
+// Sequences of at most 128 tokens (the pretraining length of the paper): one K/V tile per
+// (sequence, head), so the softmax is a single pass with no running rescale.  Such a unit is tiny
+// (48 KB in, 16 KB out), so the kernel is built for occupancy: one workgroup per (sequence, head),
+// <= 128 registers and 39 KB of LDS, i.e. four workgroups per compute unit whose load, compute and
+// store phases overlap each other.
+//
+// Arithmetic per score is kept to a handful of vector instructions:
+//   * the accumulator of S^T = K Q^T is not zeroed but pre-loaded with bias/scale = -(m_h/scale)|i-j|,
+//     so the matrix core adds the bias; off the diagonal block |i-j| is linear in i and j, which makes
+//     the pre-load one fused multiply-add per score;
+//   * the row maximum is taken on the raw accumulator and the scale is folded into the exponent:
+//     p = exp2(acc * c - max * c), c = scale * log2(e)   (requires scale > 0).
+__global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
+    int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T) {
+  __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockK * kKStride];
+  __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockK * kVStride];
+
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int start = cu[b];
+  const int n = min(cu[b + 1] - start, kBlockK);   // the caller promised max_seqlen <= 128
+  if (n <= 0) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int qi = 32 * wave + c;
+  const bool q_ok = qi < n;
+  const int nblk = (n + 31) >> 5;
+
+  // uniform head bases + 32-bit per-lane offsets
+  const uint16_t* qh = q + (int64_t)start * qs + h * kD;
+  const uint16_t* kh = k + (int64_t)start * ks + h * kD;
+  const uint16_t* vh = v + (int64_t)start * vs + h * kD;
+
+  // ---- Q^T fragments
+  bf16x8 bq[4];
+  {
+    const uint32_t off = (uint32_t)qi * (uint32_t)qs + 8 * g;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 t = {0u, 0u, 0u, 0u};
+      if (q_ok) t = *reinterpret_cast<const u32x4*>(qh + off + 16 * s);
+      bq[s] = as_bf16x8(t);
+    }
+  }
+  // ---- K, V rows -> LDS (rows n..32*nblk-1 as zeros; later rows are never read)
+  {
+    const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+    const uint32_t koff = (uint32_t)st_row * (uint32_t)ks + st_col;
+    const uint32_t voff = (uint32_t)st_row * (uint32_t)vs + st_col;
+    u32x4 tk[4], tv[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < n) {
+        tk[it] = *reinterpret_cast<const u32x4*>(kh + koff + (uint32_t)(32 * it) * (uint32_t)ks);
+        tv[it] = *reinterpret_cast<const u32x4*>(vh + voff + (uint32_t)(32 * it) * (uint32_t)vs);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      if (it < nblk) {
+        *reinterpret_cast<u32x4*>(&sK[(32 * it + st_row) * kKStride + st_col]) = tk[it];
+        *reinterpret_cast<u32x4*>(&sV[(32 * it + st_row) * kVStride + st_col]) = tv[it];
+      }
+    }
+  }
+  __syncthreads();
+  if (32 * wave >= n) return;
+
+  const float cs = scale * kLog2e;
+  const float k1 = slopes[h] / scale;   // bias in units of the raw dot product
+  float fi = (float)(qi - 4 * g);       // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
+  asm volatile("" : "+v"(fi));          // keep the distance arithmetic in floating point
+  const int lim = n - 4 * g;            // key of (jb, v) is real iff cj < lim
+
+  // ---- accumulators pre-loaded with the bias, then S^T = K Q^T on top
+  f32x16 sacc[4];
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) {
+    if (jb < nblk) {
+      if (jb == wave) {   // the block that holds the diagonal
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
+          sacc[jb][i] = -k1 * fabsf(fi - cj);
+        }
+      } else {            // entirely left (j < i) or right (j > i) of the diagonal: |i-j| = +-(fi - cj)
+        const float sk = jb < wave ? k1 : -k1;
+        const float a = -sk * fi;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
+          sacc[jb][i] = fmaf(cj, sk, a);
+        }
+      }
+      if (jb == nblk - 1 && (n & 31)) {   // ragged end: keys >= n get -inf
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
+          sacc[jb][i] = cj >= lim ? -INFINITY : sacc[jb][i];
+        }
+      }
+      const uint16_t* krow = &sK[(jb * 32 + c) * kKStride + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
+    }
+  }
+  // ---- row maximum of the raw accumulators
+  float m = -INFINITY;
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) {
+    if (jb < nblk) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) m = fmaxf(m, sacc[jb][i]);
+    }
+  }
+  m = max_both_halves(m);
+  const float mc = m * cs;
+
+  // ---- P^T = exp2(acc*cs - m*cs), row sum, O^T = V^T P^T
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+  f32x16 oacc[2];
+  float l = 0.f;
+#pragma unroll
+  for (int jb = 0; jb < 4; ++jb) {
+    if (jb < nblk) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
+        sacc[jb][i] = p;
+        l += p;
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bp = pack8(sacc[jb][8 * kk + 0], sacc[jb][8 * kk + 1], sacc[jb][8 * kk + 2],
+                                sacc[jb][8 * kk + 3], sacc[jb][8 * kk + 4], sacc[jb][8 * kk + 5],
+                                sacc[jb][8 * kk + 6], sacc[jb][8 * kk + 7]);
+        const uint16_t* vb = &sV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const s16x4 lo = lds_read_tr4(vb + 32 * db);
+          const s16x4 hi = lds_read_tr4(vb + 32 * db + 8 * kVStride);
+          if (jb == 0 && kk == 0) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            oacc[db] = mfma32(join_tr(lo, hi), bp, zero);
+          } else {
+            oacc[db] = mfma32(join_tr(lo, hi), bp, oacc[db]);
+          }
+        }
+      }
+    }
+  }
+  l = sum_both_halves(l);
+  if (!q_ok) return;
+  const float inv = 1.f / l;
+  uint16_t* orow = o + (int64_t)(start + qi) * os + h * kD + 4 * g;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      u32x2 w;
+      w[0] = pack_bf16(oacc[db][4 * r + 0] * inv, oacc[db][4 * r + 1] * inv);
+      w[1] = pack_bf16(oacc[db][4 * r + 2] * inv, oacc[db][4 * r + 3] * inv);
+      *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * r) = w;
+    }
+  }
+  if (g == 0) lse[(int64_t)h * T + start + qi] = (mc + __log2f(l)) * kLn2;
+}
+
 }  // namespace
 
 mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
                                int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream) {
   const int tiles = (s.max_seqlen + kBlockQ - 1) / kBlockQ;
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
+  if (s.max_seqlen <= kBlockK) {
+    hipLaunchKernelGGL(attn_fwd_short_kernel, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+                       (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
+                       (uint16_t*)o, os, lse, s.T);
+    return check_launch("attn_fwd_short_kernel");
+  }
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
                      (uint16_t*)o, os, lse, s.T);
