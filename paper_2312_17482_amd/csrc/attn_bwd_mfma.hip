@@ -348,7 +348,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
   const bool wave_active = kw < n;
   const int kj = kw + c;
   const float cs = scale * kLog2e;
-  const float slope2 = slopes[h] * kLog2e;
 
   // ---- phase 0
   bf16x8 bk[4], bv[4];
@@ -380,7 +379,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         to[it] = *reinterpret_cast<const u32x4*>(o + (int64_t)(start + row) * os + h * kD + col);
       }
     }
-    if (tid < kTile) sLse[tid] = tid < n ? lse[(int64_t)h * T + start + tid] * kLog2e : INFINITY;
+    // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there) and -Delta
+    if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + start + tid] * kLog2e : -INFINITY;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int row = 32 * it + (tid >> 3);
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       acc += __shfl_xor(acc, 1, 64);
       acc += __shfl_xor(acc, 2, 64);
       acc += __shfl_xor(acc, 4, 64);
-      if ((tid & 7) == 0) sDelta[row] = acc;
+      if ((tid & 7) == 0) sDelta[row] = -acc;
     }
   }
   __syncthreads();
@@ -410,12 +410,32 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     f32x16 dkacc[2], dvacc[2];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
-    const float fj = (float)(kj - 4 * g);
+    // The S accumulator is pre-loaded with bias/scale = -(m_h/scale)|i-j| and the dP accumulator with
+    // -Delta_i, so that after the matrix products  P = exp2(acc_S * c - lse2_i)  and  dS = P * acc_dP.
+    const float k1 = slopes[h] / scale;
+    float fj = (float)(kj - 4 * g);   // i - j = ci - fj with ci = 32ib + 8*(v/4) + v%4
+    asm volatile("" : "+v"(fj));
 #pragma unroll 1
     for (int ib = 0; ib < nblk; ++ib) {
       f32x16 sacc, pacc;
+      const float d0 = (float)(32 * ib) - fj;
+      if (ib == wave) {   // block with the diagonal
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
+        for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
+      } else {            // |i-j| = +-(ci - fj) on the whole block
+        const float sk = ib < wave ? k1 : -k1;
+        const float a = sk * d0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
+      }
+      float nl[16];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
+        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
+        nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
+        pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
+      }
       const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
       const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
 #pragma unroll
@@ -425,20 +445,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
-        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-        const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int i = 4 * r + e;
-          const float ci = (float)(32 * ib + 8 * r + e);
-          const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fj - ci));
-          const float p = fast_exp2(x - lv[e]);
+          const float p = fast_exp2(fmaf(sacc[i], cs, nl[i]));
           sacc[i] = p;
-          pacc[i] = p * (pacc[i] - dl[e]);
+          pacc[i] = p * pacc[i];
         }
-        // dS of queries 32ib + 8r + 4g + 0..3 for this lane's key
         // (a key past the sequence end may hold inf/NaN here -- its score never entered lse -- and
         // phase 2 multiplies it with a zero K row, so it must be an exact zero in LDS)
         u32x2 w;

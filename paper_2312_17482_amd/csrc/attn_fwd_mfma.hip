@@ -193,6 +193,10 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
     uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T) {
+  // Every global access is a full 128-byte row of one head shared by 8 lanes (16 bytes each); the
+  // fragment layouts the matrix cores need are produced by passing through LDS:
+  //   sV first carries the Q tile (rows -> Q^T fragments), then V;  after the S phase each wave reuses
+  //   its own 32 rows of sK to turn its O^T accumulators back into rows.
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockK * kKStride];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockK * kVStride];
 
@@ -204,49 +208,46 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
   const int qi = 32 * wave + c;
-  const bool q_ok = qi < n;
   const int nblk = (n + 31) >> 5;
+  const bool wave_active = wave < nblk;
 
-  // uniform head bases + 32-bit per-lane offsets
-  const uint16_t* qh = q + (int64_t)start * qs + h * kD;
-  const uint16_t* kh = k + (int64_t)start * ks + h * kD;
-  const uint16_t* vh = v + (int64_t)start * vs + h * kD;
-
-  // ---- Q^T fragments
-  bf16x8 bq[4];
+  // ---- coalesced row loads: thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+  u32x4 tq[4], tk[4], tv[4];
   {
-    const uint32_t off = (uint32_t)qi * (uint32_t)qs + 8 * g;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      u32x4 t = {0u, 0u, 0u, 0u};
-      if (q_ok) t = *reinterpret_cast<const u32x4*>(qh + off + 16 * s);
-      bq[s] = as_bf16x8(t);
-    }
-  }
-  // ---- K, V rows -> LDS (rows n..32*nblk-1 as zeros; later rows are never read)
-  {
-    const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+    const uint16_t* qh = q + (int64_t)start * qs + h * kD;
+    const uint16_t* kh = k + (int64_t)start * ks + h * kD;
+    const uint16_t* vh = v + (int64_t)start * vs + h * kD;
+    const uint32_t qoff = (uint32_t)st_row * (uint32_t)qs + st_col;
     const uint32_t koff = (uint32_t)st_row * (uint32_t)ks + st_col;
     const uint32_t voff = (uint32_t)st_row * (uint32_t)vs + st_col;
-    u32x4 tk[4], tv[4];
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      tq[it] = tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
+        tq[it] = *reinterpret_cast<const u32x4*>(qh + qoff + (uint32_t)(32 * it) * (uint32_t)qs);
         tk[it] = *reinterpret_cast<const u32x4*>(kh + koff + (uint32_t)(32 * it) * (uint32_t)ks);
         tv[it] = *reinterpret_cast<const u32x4*>(vh + voff + (uint32_t)(32 * it) * (uint32_t)vs);
       }
     }
+  }
+  // rows n..32*nblk-1 are staged as zeros; rows >= 32*nblk are never read
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      if (it < nblk) {
-        *reinterpret_cast<u32x4*>(&sK[(32 * it + st_row) * kKStride + st_col]) = tk[it];
-        *reinterpret_cast<u32x4*>(&sV[(32 * it + st_row) * kVStride + st_col]) = tv[it];
-      }
+  for (int it = 0; it < 4; ++it) {
+    if (it < nblk) {
+      *reinterpret_cast<u32x4*>(&sV[(32 * it + st_row) * kKStride + st_col]) = tq[it];   // Q, pitch kKStride
+      *reinterpret_cast<u32x4*>(&sK[(32 * it + st_row) * kKStride + st_col]) = tk[it];
     }
   }
   __syncthreads();
-  if (32 * wave >= n) return;
+  bf16x8 bq[4];   // Q^T fragments: lane = query column, 8 consecutive d per k-step
+#pragma unroll
+  for (int s = 0; s < 4; ++s) bq[s] = lds_read8(&sV[qi * kKStride + 16 * s + 8 * g]);
+  __syncthreads();   // Q has been read by everyone: sV may now take V
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    if (it < nblk) *reinterpret_cast<u32x4*>(&sV[(32 * it + st_row) * kVStride + st_col]) = tv[it];
+  }
 
   const float cs = scale * kLog2e;
   const float k1 = slopes[h] / scale;   // bias in units of the raw dot product
@@ -256,46 +257,50 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
 
   // ---- accumulators pre-loaded with the bias, then S^T = K Q^T on top
   f32x16 sacc[4];
-#pragma unroll
-  for (int jb = 0; jb < 4; ++jb) {
-    if (jb < nblk) {
-      if (jb == wave) {   // the block that holds the diagonal
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
-          sacc[jb][i] = -k1 * fabsf(fi - cj);
-        }
-      } else {            // entirely left (j < i) or right (j > i) of the diagonal: |i-j| = +-(fi - cj)
-        const float sk = jb < wave ? k1 : -k1;
-        const float a = -sk * fi;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
-          sacc[jb][i] = fmaf(cj, sk, a);
-        }
-      }
-      if (jb == nblk - 1 && (n & 31)) {   // ragged end: keys >= n get -inf
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
-          sacc[jb][i] = cj >= lim ? -INFINITY : sacc[jb][i];
-        }
-      }
-      const uint16_t* krow = &sK[(jb * 32 + c) * kKStride + 8 * g];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
-    }
-  }
-  // ---- row maximum of the raw accumulators
   float m = -INFINITY;
+  if (wave_active) {
 #pragma unroll
-  for (int jb = 0; jb < 4; ++jb) {
-    if (jb < nblk) {
+    for (int jb = 0; jb < 4; ++jb) {
+      if (jb < nblk) {
+        if (jb == wave) {   // the block that holds the diagonal
 #pragma unroll
-      for (int i = 0; i < 16; ++i) m = fmaxf(m, sacc[jb][i]);
+          for (int i = 0; i < 16; ++i) {
+            const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
+            sacc[jb][i] = -k1 * fabsf(fi - cj);
+          }
+        } else {            // entirely left (j < i) or right (j > i) of the diagonal: |i-j| = +-(fi - cj)
+          const float sk = jb < wave ? k1 : -k1;
+          const float a = -sk * fi;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float cj = (float)(jb * 32 + 8 * (i >> 2) + (i & 3));
+            sacc[jb][i] = fmaf(cj, sk, a);
+          }
+        }
+        if (jb == nblk - 1 && (n & 31)) {   // ragged end: keys >= n get -inf
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
+            sacc[jb][i] = cj >= lim ? -INFINITY : sacc[jb][i];
+          }
+        }
+        const uint16_t* krow = &sK[(jb * 32 + c) * kKStride + 8 * g];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
+      }
     }
+    // ---- row maximum of the raw accumulators
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+      if (jb < nblk) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) m = fmaxf(m, sacc[jb][i]);
+      }
+    }
+    m = max_both_halves(m);
   }
-  m = max_both_halves(m);
+  __syncthreads();   // V is in LDS; nobody reads sK any more
+  if (!wave_active) return;
   const float mc = m * cs;
 
   // ---- P^T = exp2(acc*cs - m*cs), row sum, O^T = V^T P^T
@@ -334,9 +339,12 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     }
   }
   l = sum_both_halves(l);
-  if (!q_ok) return;
   const float inv = 1.f / l;
-  uint16_t* orow = o + (int64_t)(start + qi) * os + h * kD + 4 * g;
+  if (g == 0 && qi < n) lse[(int64_t)h * T + start + qi] = (mc + __log2f(l)) * kLn2;
+
+  // ---- O^T accumulators (lane = query, 4 consecutive d per register group) -> this wave's 32 rows of
+  //      sK -> full rows of 128 bytes, 8 lanes each
+  uint16_t* slab = &sK[(32 * wave) * kKStride];
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -344,10 +352,18 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
       u32x2 w;
       w[0] = pack_bf16(oacc[db][4 * r + 0] * inv, oacc[db][4 * r + 1] * inv);
       w[1] = pack_bf16(oacc[db][4 * r + 2] * inv, oacc[db][4 * r + 3] * inv);
-      *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * r) = w;
+      *reinterpret_cast<u32x2*>(&slab[c * kKStride + 32 * db + 8 * r + 4 * g]) = w;
     }
   }
-  if (g == 0) lse[(int64_t)h * T + start + qi] = (mc + __log2f(l)) * kLn2;
+  // (same wave wrote and reads the slab: LDS operations of one wave complete in order)
+  uint16_t* oh = o + (int64_t)(start + 32 * wave) * os + h * kD;
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = 8 * it + orow;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kKStride + ocol]);
+    if (32 * wave + row < n) *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)os + ocol) = w;
+  }
 }
 
 }  // namespace
