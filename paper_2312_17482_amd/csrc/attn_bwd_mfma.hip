@@ -316,13 +316,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
 
 // ------------------------------------------------------------------------------------------------ fused, n <= 128
 // Whole backward of one (sequence, head) with at most 128 tokens in one workgroup: every input is read
-// from HBM once and every output written once.
-//   phase 0  Q, dO rows -> LDS; Delta = rowsum(dO * O) -> LDS (O is read only for this); lse -> LDS;
-//            each wave keeps K and V of its own 32 keys in registers.
+// from HBM once and every output written once, always as full 128-byte rows shared by 8 lanes; the
+// fragment layouts of the matrix cores are produced by passing through LDS.
+//   phase 0  K, V rows -> LDS -> each wave keeps K^T, V^T fragments of its own 32 keys in registers;
+//            then Q, dO rows -> the same LDS; Delta = rowsum(dO * O) and -lse -> LDS.
 //   phase 1  wave w owns keys 32w..: for every block of 32 queries, S = Q K^T, dP = dO V^T, P, dS in
 //            registers; dV^T += dO^T P, dK^T += Q^T dS; dS (bf16) is also written to LDS as [key][query].
-//   phase 2  the K registers are spilled to LDS over the Q tile; wave w then owns queries 32w.. and
-//            accumulates dQ^T += K^T dS^T reading both operands with transposing LDS reads.
+//   phase 2  dK, dV leave through the (now free) dO tile; the K registers go back to LDS over the Q
+//            tile; wave w then owns queries 32w.. and accumulates dQ^T += K^T dS^T, both operands read
+//            with transposing LDS reads.
 constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
 
 __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
@@ -331,11 +333,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T) {
-  __shared__ __attribute__((aligned(16))) uint16_t sQ[kTile * kPitch];      // Q in phase 1, K in phase 2
-  __shared__ __attribute__((aligned(16))) uint16_t sG[kTile * kPitch];      // dO
+  __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
+  __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
-  __shared__ __attribute__((aligned(16))) float sLse[kTile];
-  __shared__ __attribute__((aligned(16))) float sDelta[kTile];
+  __shared__ __attribute__((aligned(16))) float sLse[kTile];                // -lse, base-2 units
+  __shared__ __attribute__((aligned(16))) float sDelta[kTile];              // -Delta
 
   const int h = blockIdx.x, b = blockIdx.y;
   const int start = cu[b];
@@ -345,69 +347,82 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
   const int kw = 32 * wave;
-  const bool wave_active = kw < n;
+  const int nblk = (n + 31) >> 5;
+  const bool wave_active = wave < nblk;
   const int kj = kw + c;
   const float cs = scale * kLog2e;
 
-  // ---- phase 0
-  bf16x8 bk[4], bv[4];
+  // ---- phase 0: coalesced row loads; thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+  u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
   {
-    const bool ok = kj < n;
-    const uint16_t* krow = k + (int64_t)(start + kj) * ks + h * kD + 8 * g;
-    const uint16_t* vrow = v + (int64_t)(start + kj) * vs + h * kD + 8 * g;
+    const uint16_t* kh = k + (int64_t)start * ks + h * kD;
+    const uint16_t* vh = v + (int64_t)start * vs + h * kD;
+    const uint16_t* qh = q + (int64_t)start * qs + h * kD;
+    const uint16_t* gh = dout + (int64_t)start * dos + h * kD;
+    const uint16_t* oh = o + (int64_t)start * os + h * kD;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
-      if (ok) {
-        tk = *reinterpret_cast<const u32x4*>(krow + 16 * s);
-        tv = *reinterpret_cast<const u32x4*>(vrow + 16 * s);
+    for (int it = 0; it < 4; ++it) {
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < n) {
+        tk[it] = *reinterpret_cast<const u32x4*>(kh + (uint32_t)(32 * it + st_row) * (uint32_t)ks + st_col);
+        tv[it] = *reinterpret_cast<const u32x4*>(vh + (uint32_t)(32 * it + st_row) * (uint32_t)vs + st_col);
       }
-      bk[s] = as_bf16x8(tk);
-      bv[s] = as_bf16x8(tv);
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < n) {
+        tq[it] = *reinterpret_cast<const u32x4*>(qh + (uint32_t)(32 * it + st_row) * (uint32_t)qs + st_col);
+        tg[it] = *reinterpret_cast<const u32x4*>(gh + (uint32_t)(32 * it + st_row) * (uint32_t)dos + st_col);
+        to[it] = *reinterpret_cast<const u32x4*>(oh + (uint32_t)(32 * it + st_row) * (uint32_t)os + st_col);
+      }
     }
   }
-  {
-    u32x4 tq[4], tg[4], to[4];
-    const int col = (tid & 7) * 8;
+  // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there)
+  if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + start + tid] * kLog2e : -INFINITY;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int row = 32 * it + (tid >> 3);
-      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
-      if (row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(q + (int64_t)(start + row) * qs + h * kD + col);
-        tg[it] = *reinterpret_cast<const u32x4*>(dout + (int64_t)(start + row) * dos + h * kD + col);
-        to[it] = *reinterpret_cast<const u32x4*>(o + (int64_t)(start + row) * os + h * kD + col);
-      }
+  for (int it = 0; it < 4; ++it) {
+    if (it < nblk) {   // rows n..32*nblk-1 are zeros; rows >= 32*nblk are never read
+      *reinterpret_cast<u32x4*>(&sA[(32 * it + st_row) * kPitch + st_col]) = tk[it];
+      *reinterpret_cast<u32x4*>(&sB[(32 * it + st_row) * kPitch + st_col]) = tv[it];
     }
-    // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there) and -Delta
-    if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + start + tid] * kLog2e : -INFINITY;
+  }
+  __syncthreads();
+  bf16x8 bk[4], bv[4];   // K^T, V^T fragments (B operands): lane = key column, 8 consecutive d per k-step
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int row = 32 * it + (tid >> 3);
-      *reinterpret_cast<u32x4*>(&sQ[row * kPitch + col]) = tq[it];
-      *reinterpret_cast<u32x4*>(&sG[row * kPitch + col]) = tg[it];
-      float acc = 0.f;
+  for (int s = 0; s < 4; ++s) {
+    bk[s] = lds_read8(&sA[kj * kPitch + 16 * s + 8 * g]);
+    bv[s] = lds_read8(&sB[kj * kPitch + 16 * s + 8 * g]);
+  }
+  __syncthreads();   // K, V have been read by everyone
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        acc = fmaf(__uint_as_float(tg[it][i] << 16), __uint_as_float(to[it][i] << 16), acc);
-        acc = fmaf(__uint_as_float(tg[it][i] & 0xffff0000u), __uint_as_float(to[it][i] & 0xffff0000u), acc);
-      }
-      acc += __shfl_xor(acc, 1, 64);
-      acc += __shfl_xor(acc, 2, 64);
-      acc += __shfl_xor(acc, 4, 64);
-      if ((tid & 7) == 0) sDelta[row] = -acc;
+  for (int it = 0; it < 4; ++it) {
+    const int row = 32 * it + st_row;
+    if (it < nblk) {
+      *reinterpret_cast<u32x4*>(&sA[row * kPitch + st_col]) = tq[it];
+      *reinterpret_cast<u32x4*>(&sB[row * kPitch + st_col]) = tg[it];
     }
+    float acc = 0.f;   // Delta = rowsum(dO * O): 8 lanes per row, 8 elements each
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__uint_as_float(tg[it][i] << 16), __uint_as_float(to[it][i] << 16), acc);
+      acc = fmaf(__uint_as_float(tg[it][i] & 0xffff0000u), __uint_as_float(to[it][i] & 0xffff0000u), acc);
+    }
+    acc += __shfl_xor(acc, 1, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 4, 64);
+    if ((tid & 7) == 0) sDelta[row] = -acc;
   }
   __syncthreads();
 
   const int tr_i = lane & 15, tr_q = lane >> 4;
   const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
   const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
-  const int nblk = (n + 31) >> 5;
 
   // ---- phase 1
+  f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows, this wave's keys along lanes
   if (wave_active) {
-    f32x16 dkacc[2], dvacc[2];
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
     // The S accumulator is pre-loaded with bias/scale = -(m_h/scale)|i-j| and the dP accumulator with
@@ -436,8 +451,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
         pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
       }
-      const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
-      const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
+      const uint16_t* qrow = &sA[(32 * ib + c) * kPitch + 8 * g];
+      const uint16_t* grow = &sB[(32 * ib + c) * kPitch + 8 * g];
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
@@ -452,8 +467,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
           sacc[i] = p;
           pacc[i] = p * pacc[i];
         }
-        // (a key past the sequence end may hold inf/NaN here -- its score never entered lse -- and
-        // phase 2 multiplies it with a zero K row, so it must be an exact zero in LDS)
+        // dS of queries 32ib + 8r + 4g + 0..3 for this lane's key.  A key past the sequence end may hold
+        // inf/NaN here (its score never entered lse) and phase 2 multiplies it with a zero K row, so it
+        // must be an exact zero in LDS.
         u32x2 w;
         w[0] = kj < n ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
         w[1] = kj < n ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
@@ -468,38 +484,49 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
 #pragma unroll
         for (int db = 0; db < 2; ++db) {
-          const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
+          const bf16x8 ag = join_tr(lds_read_tr4(&sB[roff + 32 * db]), lds_read_tr4(&sB[roff + 32 * db + 8 * kPitch]));
           dvacc[db] = mfma32(ag, bp, dvacc[db]);
-          const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
+          const bf16x8 aq = join_tr(lds_read_tr4(&sA[roff + 32 * db]), lds_read_tr4(&sA[roff + 32 * db + 8 * kPitch]));
           dkacc[db] = mfma32(aq, bs, dkacc[db]);
         }
       }
     }
-    if (kj < n) {
-      uint16_t* dkrow = dk + (int64_t)(start + kj) * dks + h * kD + 4 * g;
-      uint16_t* dvrow = dv + (int64_t)(start + kj) * dvs + h * kD + 4 * g;
+  }
+  __syncthreads();   // Q and dO have been read by everyone, all of dS is written
+
+  // Accumulators (lane = token, 4 consecutive d per register group) -> this wave's 32 rows of sB ->
+  // full rows of 128 bytes to global memory.  The slab is private to the wave, and the LDS operations
+  // of one wave complete in order, so no barrier is needed between its uses.
+  uint16_t* slab = &sB[kw * kPitch];
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+  auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride) {
 #pragma unroll
-      for (int db = 0; db < 2; ++db) {
+    for (int db = 0; db < 2; ++db) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          u32x2 w;
-          w[0] = pack_bf16(dkacc[db][4 * r + 0] * scale, dkacc[db][4 * r + 1] * scale);
-          w[1] = pack_bf16(dkacc[db][4 * r + 2] * scale, dkacc[db][4 * r + 3] * scale);
-          *reinterpret_cast<u32x2*>(dkrow + 32 * db + 8 * r) = w;
-          w[0] = pack_bf16(dvacc[db][4 * r + 0], dvacc[db][4 * r + 1]);
-          w[1] = pack_bf16(dvacc[db][4 * r + 2], dvacc[db][4 * r + 3]);
-          *reinterpret_cast<u32x2*>(dvrow + 32 * db + 8 * r) = w;
-        }
+      for (int r = 0; r < 4; ++r) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[db][4 * r + 0] * mul, acc[db][4 * r + 1] * mul);
+        w[1] = pack_bf16(acc[db][4 * r + 2] * mul, acc[db][4 * r + 3] * mul);
+        *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
       }
     }
-  }
-  __syncthreads();   // all of Q has been read, all of dS written
+    uint16_t* oh = out + (int64_t)(start + kw) * stride + h * kD;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = 8 * it + orow;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      if (kw + row < n) *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)stride + ocol) = w;
+    }
+  };
 
-  // ---- phase 2: K registers -> LDS (over Q); rows of keys >= n are zero because bk was zero-filled
+  // ---- phase 2
   if (wave_active) {
+    store_rows(dkacc, scale, dk, dks);
+    store_rows(dvacc, 1.f, dv, dvs);
+    // K registers -> LDS over Q; rows of keys >= n are zeros because they were staged as zeros
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-      *reinterpret_cast<u32x4*>(&sQ[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
+      *reinterpret_cast<u32x4*>(&sA[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
   }
   __syncthreads();
   if (!wave_active) return;   // queries 32*wave.. do not exist
@@ -516,25 +543,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
                                 lds_read_tr4(&sDs[(krow + 8) * kDsPitch + kw + tr_col]));
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
-        const bf16x8 ak = join_tr(lds_read_tr4(&sQ[krow * kPitch + tr_col + 32 * db]),
-                                  lds_read_tr4(&sQ[(krow + 8) * kPitch + tr_col + 32 * db]));
+        const bf16x8 ak = join_tr(lds_read_tr4(&sA[krow * kPitch + tr_col + 32 * db]),
+                                  lds_read_tr4(&sA[(krow + 8) * kPitch + tr_col + 32 * db]));
         dqacc[db] = mfma32(ak, bs, dqacc[db]);
       }
     }
   }
-  const int qi = kw + c;
-  if (qi >= n) return;
-  uint16_t* dqrow = dq + (int64_t)(start + qi) * dqs + h * kD + 4 * g;
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      u32x2 w;
-      w[0] = pack_bf16(dqacc[db][4 * r + 0] * scale, dqacc[db][4 * r + 1] * scale);
-      w[1] = pack_bf16(dqacc[db][4 * r + 2] * scale, dqacc[db][4 * r + 3] * scale);
-      *reinterpret_cast<u32x2*>(dqrow + 32 * db + 8 * r) = w;
-    }
-  }
+  store_rows(dqacc, scale, dq, dqs);
 }
 
 }  // namespace
