@@ -19,9 +19,22 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (2.5 PFLOP/s)
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by
-# what the same counters read for a plain copy of known size (see profiles/).  None until measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
+# file (KiB per dispatch), each scaled by what the same counter reads for a plain row copy of known size
+# (--copy-calibration: FETCH_SIZE reads 66063.6 KiB for 131072 KiB copied -> factor 1.984; WRITE_SIZE reads
+# 131072.0 KiB -> factor 1.0).  Summaries: profiles/bert_base_attn_bwd_hbm_traffic.md.
+COPY_FACTOR_FETCH = 131072.0 / 66063.6
+COPY_FACTOR_WRITE = 1.0
+MEASURED_TRAFFIC_KIB = {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE) KiB per dispatch
+    "bert_base": {"attn_bwd_fused128_kernel": (101998.6, 121333.5), "attn_fwd_short_kernel": (60748.3, 41788.3)},
+}
+
+
+def measured_traffic_bytes(workload, kernel):
+    kib = MEASURED_TRAFFIC_KIB.get(workload, {}).get(kernel)
+    if kib is None:
+        return None
+    return int(round((kib[0] * COPY_FACTOR_FETCH + kib[1] * COPY_FACTOR_WRITE) * 1024))
 
 
 def main():
@@ -32,6 +45,9 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also time each call of the path separately")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed steps, run a plain row copy of known size (128 MiB in, 128 MiB out, 5 launches of "
+                         "gather_rows_kernel with 65536 rows) so that HBM counters of a profiler run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no communication; every box has "
@@ -124,6 +140,13 @@ def main():
 
     value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) * 1e-12
     esize = 2 if bf16 else 4
+    # algorithmic HBM bytes of one backward launch: dO, Q, K, V, O read and dQ, dK, dV written once each
+    # ([T,H,D] elements) plus the row log-sum-exp read ([H,T] float)
+    bwd_bytes = 8 * T_host * H * D * esize + 4 * H * T_host
+    if bf16 and D == 64:
+        bwd_kernel = "attn_bwd_fused128_kernel" if L <= 128 else "attn_bwd_dkv_kernel + attn_bwd_dq_kernel + attn_bwd_delta_kernel"
+    else:
+        bwd_kernel = "bwd_generic_row_kernel + bwd_generic_col_kernel"
     out = {
         "metric": "ALiBi varlen attention fwd+bwd TFLOP/s (whole unpad->attention->pad step)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -141,17 +164,34 @@ def main():
             "fwd_bwd_tflops_no_recompute_convention": round((f_fwd + f_bwd) * 12.0 / 14.0 / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12, 2),
             "pct_of_bf16_mfma_peak": round(100.0 * (f_fwd + f_bwd) / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 3),
         },
+        # Dominant kernel: the backward attention kernel.  At max_len 128 it moves 8 [T,H,D] tensors for
+        # 10*H*D*sum(len^2) flops (~73 flop/byte, machine balance ~312), so HBM is the roof that binds;
+        # the fraction of the matrix-core peak is given beside it.
         "roofline": {
-            "kernel": "mb_alibi_attn_bwd (backward attention call)", "bound": "mfma",
+            "kernel": bwd_kernel, "bound": "hbm",
+            "achieved": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 5),
+            "algorithmic_bytes": bwd_bytes, "traffic": measured_traffic_bytes(w.name, bwd_kernel),
+        },
+        "roofline_mfma": {
+            "kernel": bwd_kernel, "bound": "mfma",
             "achieved": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": round(f_bwd / (bwd_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 5),
-            "traffic": MEASURED_TRAFFIC.get(w.name),
         },
         "paper_context": "MosaicBERT-Base: 79.6 GLUE in 1.13 h on 8xA100-80GB (end-to-end pretraining; not comparable)",
     }
 
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
+    if args.copy_calibration:
+        rows, width = 65536, 1024                      # 65536 rows x 2048 bytes = 128 MiB each way
+        src = torch.ones((rows, width), dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        ident = torch.arange(rows, dtype=torch.int32, device=dev)
+        for _ in range(5):
+            mb.mb_unpad(src, ident, rows, None, out=dst)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = "5 x gather_rows_kernel grid=%d: reads 131072 KiB, writes 131072 KiB per launch" % (rows // 8)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batch, f_fwd + f_bwd)
