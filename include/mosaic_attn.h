@@ -24,10 +24,10 @@
  *              point into one fused [T, 3, H, D] buffer.  The row log-sum-exp is [H, T] float,
  *              natural log.  Positions used by the bias are positions inside the packed sequence:
  *              token t of sequence b sits at position t - cu_seqlens[b].
- *   Precision  MB_BF16 (D must be 64): bf16 operands on the matrix cores, fp32 accumulation and
- *              fp32 softmax statistics; probabilities and score gradients are rounded to bf16 only
- *              as matrix operands; outputs are rounded to bf16 once.  MB_F32 (1 <= D <= 128):
- *              plain fp32 arithmetic throughout.
+ *   Precision  MB_BF16 with D = 64: bf16 operands on the matrix cores, fp32 accumulation and fp32
+ *              softmax statistics; probabilities and score gradients are rounded to bf16 only as
+ *              matrix operands; outputs are rounded to bf16 once.  MB_F32 (D <= 128, multiple of 4)
+ *              and MB_BF16 with other D (<= 128, multiple of 8): plain fp32 arithmetic throughout.
  *   Degenerate B == 0, T == 0 and zero-length sequences are legal: MB_OK, nothing written for them.
  *   Threads    re-entrant; the only global state is the thread-local error string.
  */
@@ -111,6 +111,15 @@ MB_API mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, c
                  int B, int L, int W, mb_dtype dt, void* padded, void* stream);
 
 /*
+ * Companion of token_rows: sets to zero bits every row of `padded` that is NOT listed in `indices`
+ * (the padding rows), leaving the listed rows alone.  After an attention call that wrote its output
+ * straight into the padded layout this completes what mb_pad would have produced.
+ *   indices, T_cap, meta_dev, B, L, W, dt as for mb_pad;  padded  dev, [B*L, W].
+ */
+MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta_dev, int B, int L, int W,
+                                 mb_dtype dt, void* padded, void* stream);
+
+/*
  * Forward attention, Eq. 1:  for every sequence b, head h and tokens i, j of that sequence
  *   S_ij = softmax_scale * q_i . k_j - slopes[h] * |i - j|,   P = softmax_j(S),   O_i = sum_j P_ij v_j,
  *   lse_i = log sum_j exp(S_ij).
@@ -123,13 +132,20 @@ MB_API mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, c
  *   slopes       dev, [H] float, read.
  *   o            dev, [T, H, D] with row stride o_row_stride, written.
  *   lse          dev, [H, T] float, written.
- * Errors: MB_BF16 with D != 64, MB_F32 with D > 128 -> MB_ERR_UNSUPPORTED.
+ *   token_rows   dev, [>= cu_seqlens[B]] int32, or NULL.  NULL: token t is row t of q, k, v and o (packed
+ *                buffers).  Otherwise token t is row token_rows[t] of all four buffers: passing the
+ *                `indices` of mb_unpad_index lets the call read a padded [B*L, ...] batch directly and
+ *                write o into the padded layout, i.e. the gather of mb_unpad and the scatter of mb_pad
+ *                happen inside the attention kernel's own row loads and stores (rows of o that belong to
+ *                padding are not written: see mb_zero_padding).  lse stays packed, [H, T].
+ * Errors: head_dim > 128 -> MB_ERR_UNSUPPORTED.  MB_BF16 with D = 64 and softmax_scale > 0 runs on the
+ * matrix cores; every other supported combination runs the generic fp32-arithmetic kernels.
  */
 MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens,
                             int B, int T, int max_seqlen, int H, int D, const float* slopes,
                             float softmax_scale, mb_dtype dt, void* o, int64_t o_row_stride,
-                            float* lse, void* stream);
+                            float* lse, const int32_t* token_rows, void* stream);
 
 /* Bytes of device workspace mb_alibi_attn_bwd needs for these sizes (0 on invalid sizes). */
 MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt);
@@ -144,6 +160,7 @@ MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, in
  *   lse          dev, [H, T] float from the forward, read.
  *   dq, dk, dv   dev, [T, H, D] with row strides dq/dk/dv_row_stride, written (rows [0, T)).
  *   workspace    dev, at least mb_alibi_attn_bwd_workspace_bytes(...) bytes, scratch.
+ *   token_rows   as in the forward; applies to dout, q, k, v, o, dq, dk and dv alike.
  * Deterministic: no atomics; two calls on the same inputs give identical bits.
  */
 MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
@@ -153,7 +170,7 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
-                            size_t workspace_bytes, void* stream);
+                            size_t workspace_bytes, const int32_t* token_rows, void* stream);
 
 #ifdef __cplusplus
 }

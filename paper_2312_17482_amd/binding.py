@@ -22,7 +22,8 @@ MB_OK, MB_ERR_INVALID_ARG, MB_ERR_UNSUPPORTED, MB_ERR_WORKSPACE, MB_ERR_HIP = ra
 MB_F32, MB_BF16 = 0, 1
 
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
-           "mb_pad", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes", "mb_alibi_attn_bwd")
+           "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
+           "mb_alibi_attn_bwd")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -38,15 +39,17 @@ _lib.mb_unpad.restype = c_int
 _lib.mb_unpad.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_void_p]
 _lib.mb_pad.restype = c_int
 _lib.mb_pad.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
+_lib.mb_zero_padding.restype = c_int
+_lib.mb_zero_padding.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p]
 _lib.mb_alibi_attn_fwd.restype = c_int
 _lib.mb_alibi_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int, c_int,
                                    c_int, c_int, c_int, c_void_p, c_float, c_int, c_void_p, c_int64, c_void_p,
-                                   c_void_p]
+                                   c_void_p, c_void_p]
 _lib.mb_alibi_attn_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
-                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p])
+                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p])
 
 
 class MosaicAttnError(RuntimeError):
@@ -145,17 +148,29 @@ def mb_pad(packed: torch.Tensor, indices: torch.Tensor, T_cap: int, meta, B: int
     return out
 
 
-def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None):
-    """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32)."""
-    T, H, D = q.shape
+def mb_zero_padding(padded: torch.Tensor, indices: torch.Tensor, T_cap: int, meta, B: int, L: int):
+    """Zero the rows of padded [B*L, W] that `indices` does not list."""
+    assert padded.dim() == 2 and padded.is_contiguous() and padded.shape[0] == B * L
+    _check(_lib.mb_zero_padding(_ptr(indices), T_cap, _ptr(meta), B, L, padded.shape[1], _dtype_code(padded),
+                                _ptr(padded), _stream()))
+    return padded
+
+
+def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None,
+                      token_rows=None, T=None):
+    """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32).
+    With token_rows the views are over a padded batch ([B*L, H, D]) and T (the lse pitch) must be given."""
+    _, H, D = q.shape
+    T = q.shape[0] if T is None else T
     B = cu_seqlens.numel() - 1
     if out is None:
-        out = torch.empty((T, H, D), dtype=q.dtype, device=q.device)
+        out = torch.empty((q.shape[0], H, D), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
     _check(_lib.mb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                   _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
-                                  _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _stream()))
+                                  _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _ptr(token_rows),
+                                  _stream()))
     return out, lse
 
 
@@ -164,13 +179,14 @@ def mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int
 
 
 def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
-                      dq=None, dk=None, dv=None, workspace=None):
-    """Returns (dq, dk, dv), each [T, H, D]."""
-    T, H, D = q.shape
+                      dq=None, dk=None, dv=None, workspace=None, token_rows=None, T=None):
+    """Returns (dq, dk, dv), each [T, H, D] (padded-batch views when token_rows is given)."""
+    R, H, D = q.shape
+    T = R if T is None else T
     B = cu_seqlens.numel() - 1
-    dq = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dq is None else dq
-    dk = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dk is None else dk
-    dv = torch.empty((T, H, D), dtype=q.dtype, device=q.device) if dv is None else dv
+    dq = torch.empty((R, H, D), dtype=q.dtype, device=q.device) if dq is None else dq
+    dk = torch.empty((R, H, D), dtype=q.dtype, device=q.device) if dk is None else dk
+    dv = torch.empty((R, H, D), dtype=q.dtype, device=q.device) if dv is None else dv
     need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, _dtype_code(q))
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
@@ -178,5 +194,5 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o), _ptr(cu_seqlens),
                                   B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale), _dtype_code(q),
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
-                                  _ptr(workspace), workspace.numel(), _stream()))
+                                  _ptr(workspace), workspace.numel(), _ptr(token_rows), _stream()))
     return dq, dk, dv

@@ -170,10 +170,27 @@ mb_status mb_pad(const void* packed, const int32_t* indices, int T_cap, const in
                              (hipStream_t)stream);
 }
 
+mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta_dev, int B, int L, int W,
+                          mb_dtype dt, void* padded, void* stream) {
+  clear_error();
+  mb_status st = check_rows(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE(B >= 0 && L >= 0, MB_ERR_INVALID_ARG, "negative size (B=%d L=%d)", B, L);
+  MB_REQUIRE((int64_t)B * L < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "B*L=%lld does not fit int32",
+             (long long)B * L);
+  MB_REQUIRE((int64_t)T_cap <= (int64_t)B * L, MB_ERR_INVALID_ARG, "T_cap=%d exceeds B*L=%lld", T_cap,
+             (long long)B * L);
+  if ((int64_t)B * L == 0) return MB_OK;
+  MB_CHECK_PTR(padded);
+  if (T_cap > 0) MB_CHECK_PTR(indices);
+  return launch_zero_padding(indices, T_cap, meta_dev, B * L, (int)(W * elem_size(dt)), padded,
+                             (hipStream_t)stream);
+}
+
 mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
-                            void* o, int64_t o_row_stride, float* lse, void* stream) {
+                            void* o, int64_t o_row_stride, float* lse, const int32_t* token_rows, void* stream) {
   clear_error();
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
@@ -191,7 +208,9 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   MB_CHECK_PTR(slopes);
   MB_CHECK_PTR(o);
   MB_CHECK_PTR(lse);
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
+  MB_REQUIRE(token_rows == nullptr || aligned16(token_rows), MB_ERR_INVALID_ARG,
+             "token_rows is not 16-byte aligned");
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows};
   if (use_mfma(dt, D, softmax_scale))
     return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
                                 (hipStream_t)stream);
@@ -212,7 +231,8 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
                             int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                             void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
-                            int64_t dv_row_stride, void* workspace, size_t workspace_bytes, void* stream) {
+                            int64_t dv_row_stride, void* workspace, size_t workspace_bytes,
+                            const int32_t* token_rows, void* stream) {
   clear_error();
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
@@ -242,7 +262,9 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
   MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale};
+  MB_REQUIRE(token_rows == nullptr || aligned16(token_rows), MB_ERR_INVALID_ARG,
+             "token_rows is not 16-byte aligned");
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows};
   if (use_mfma(dt, D, softmax_scale))
     return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                 o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,

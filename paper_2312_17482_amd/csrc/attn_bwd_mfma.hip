@@ -32,7 +32,8 @@ constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
                                                              const uint16_t* __restrict__ o, int64_t dos, int64_t os,
                                                              int T, int H, const int32_t* __restrict__ cu, int B,
-                                                             float* __restrict__ delta) {
+                                                             float* __restrict__ delta,
+                                                             const int32_t* __restrict__ rows) {
   const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
   const int sub = threadIdx.x & 7;
   float acc = 0.f;
@@ -41,8 +42,9 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
   if (ok) {
     t = (int)(row / H);
     h = (int)(row - (int64_t)t * H);
-    const u32x4 a = *reinterpret_cast<const u32x4*>(dout + (int64_t)t * dos + h * kD + 8 * sub);
-    const u32x4 b = *reinterpret_cast<const u32x4*>(o + (int64_t)t * os + h * kD + 8 * sub);
+    const int64_t gr = tok_row(rows, t);
+    const u32x4 a = *reinterpret_cast<const u32x4*>(dout + gr * dos + h * kD + 8 * sub);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(o + gr * os + h * kD + 8 * sub);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       acc = fmaf(__uint_as_float(a[i] << 16), __uint_as_float(b[i] << 16), acc);
@@ -57,14 +59,16 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
 
 // Stage rows r0..r0+127 of one head ([*, 64] bf16, token stride `stride`) into LDS with pitch kPitch;
 // rows at or beyond n become zeros.
+// `src` points at column 0 of this head in row 0 of the buffer; token `tok0 + r` of the sequence sits
+// at buffer row tok_row(rows, tok0 + r).
 __device__ __forceinline__ void stage_tile(uint16_t* dst, const uint16_t* __restrict__ src, int64_t stride,
-                                           int r0, int n, int tid) {
+                                           int r0, int n, int tid, const int32_t* __restrict__ rows, int tok0) {
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int id = tid + 256 * it;
     const int row = id >> 3, col = (id & 7) * 8;
     u32x4 t = {0u, 0u, 0u, 0u};
-    if (r0 + row < n) t = *reinterpret_cast<const u32x4*>(src + (int64_t)(r0 + row) * stride + col);
+    if (r0 + row < n) t = *reinterpret_cast<const u32x4*>(src + tok_row(rows, tok0 + r0 + row) * stride + col);
     *reinterpret_cast<u32x4*>(&dst[row * kPitch + col]) = t;
   }
 }
@@ -74,7 +78,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
-    float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T) {
+    float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
+    const int32_t* __restrict__ rows) {
   __shared__ __attribute__((aligned(16))) uint16_t sQ[kTile * kPitch];
   __shared__ __attribute__((aligned(16))) uint16_t sG[kTile * kPitch];   // dO
   __shared__ __attribute__((aligned(16))) float sLse[kTile];             // lse in base-2 units, +inf past the end
@@ -98,8 +103,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
   bf16x8 bk[4], bv[4];
   {
     const bool ok = wave_active && kj < n;
-    const uint16_t* krow = k + (int64_t)(start + kj) * ks + h * kD + 8 * g;
-    const uint16_t* vrow = v + (int64_t)(start + kj) * vs + h * kD + 8 * g;
+    const int64_t gr = ok ? tok_row(rows, start + kj) : 0;
+    const uint16_t* krow = k + gr * ks + h * kD + 8 * g;
+    const uint16_t* vrow = v + gr * vs + h * kD + 8 * g;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
@@ -122,8 +128,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
 
   for (int i0 = 0; i0 < n; i0 += kTile) {
     if (i0 > 0) __syncthreads();
-    stage_tile(sQ, q + (int64_t)start * qs + h * kD, qs, i0, n, tid);
-    stage_tile(sG, dout + (int64_t)start * dos + h * kD, dos, i0, n, tid);
+    stage_tile(sQ, q + h * kD, qs, i0, n, tid, rows, start);
+    stage_tile(sG, dout + h * kD, dos, i0, n, tid, rows, start);
     if (tid < kTile) {
       const bool ok = i0 + tid < n;
       sLse[tid] = ok ? lse[(int64_t)h * T + start + i0 + tid] * kLog2e : INFINITY;
@@ -184,8 +190,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
   }
 
   if (!wave_active || kj >= n) return;
-  uint16_t* dkrow = dk + (int64_t)(start + kj) * dks + h * kD + 4 * g;
-  uint16_t* dvrow = dv + (int64_t)(start + kj) * dvs + h * kD + 4 * g;
+  const int64_t orow_idx = tok_row(rows, start + kj);
+  uint16_t* dkrow = dk + orow_idx * dks + h * kD + 4 * g;
+  uint16_t* dvrow = dv + orow_idx * dvs + h * kD + 4 * g;
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -206,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
-    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T) {
+    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ rows) {
   __shared__ __attribute__((aligned(16))) uint16_t sK[kTile * kPitch];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kTile * kPitch];
 
@@ -227,8 +234,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
 
   bf16x8 bq[4], bg[4];   // Q^T and dO^T fragments (B operands): lane = query column
   {
-    const uint16_t* qrow = q + (int64_t)(start + qi) * qs + h * kD + 8 * g;
-    const uint16_t* grow = dout + (int64_t)(start + qi) * dos + h * kD + 8 * g;
+    const int64_t gr = q_ok ? tok_row(rows, start + qi) : 0;
+    const uint16_t* qrow = q + gr * qs + h * kD + 8 * g;
+    const uint16_t* grow = dout + gr * dos + h * kD + 8 * g;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       u32x4 tq = {0u, 0u, 0u, 0u}, tg = {0u, 0u, 0u, 0u};
@@ -253,8 +261,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
 
   for (int j0 = 0; j0 < n; j0 += kTile) {
     if (j0 > 0) __syncthreads();
-    stage_tile(sK, k + (int64_t)start * ks + h * kD, ks, j0, n, tid);
-    stage_tile(sV, v + (int64_t)start * vs + h * kD, vs, j0, n, tid);
+    stage_tile(sK, k + h * kD, ks, j0, n, tid, rows, start);
+    stage_tile(sV, v + h * kD, vs, j0, n, tid, rows, start);
     __syncthreads();
     if (!wave_active) continue;
 
@@ -300,7 +308,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
   }
 
   if (!q_ok) return;
-  uint16_t* dqrow = dq + (int64_t)(start + qi) * dqs + h * kD + 4 * g;
+  uint16_t* dqrow = dq + tok_row(rows, start + qi) * dqs + h * kD + 4 * g;
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -327,12 +335,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
 //            with transposing LDS reads.
 constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
 
+// kRows: the activation buffers are a padded batch and token t sits at row rows[t].
+template <bool kRows>
 __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
-    uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T) {
+    uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
   __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
@@ -356,26 +366,33 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
   {
-    const uint16_t* kh = k + (int64_t)start * ks + h * kD;
-    const uint16_t* vh = v + (int64_t)start * vs + h * kD;
-    const uint16_t* qh = q + (int64_t)start * qs + h * kD;
-    const uint16_t* gh = dout + (int64_t)start * dos + h * kD;
-    const uint16_t* oh = o + (int64_t)start * os + h * kD;
+    // buffer row of the 4 tokens this thread moves, relative to `base` rows
+    int64_t gr[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      if (kRows) gr[it] = 32 * it + st_row < n ? (int64_t)rows[start + 32 * it + st_row] : 0;
+      else gr[it] = start + 32 * it + st_row;
+    }
+    const uint16_t* kh = k + h * kD + st_col;
+    const uint16_t* vh = v + h * kD + st_col;
+    const uint16_t* qh = q + h * kD + st_col;
+    const uint16_t* gh = dout + h * kD + st_col;
+    const uint16_t* oh = o + h * kD + st_col;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
-        tk[it] = *reinterpret_cast<const u32x4*>(kh + (uint32_t)(32 * it + st_row) * (uint32_t)ks + st_col);
-        tv[it] = *reinterpret_cast<const u32x4*>(vh + (uint32_t)(32 * it + st_row) * (uint32_t)vs + st_col);
+        tk[it] = *reinterpret_cast<const u32x4*>(kh + gr[it] * ks);
+        tv[it] = *reinterpret_cast<const u32x4*>(vh + gr[it] * vs);
       }
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(qh + (uint32_t)(32 * it + st_row) * (uint32_t)qs + st_col);
-        tg[it] = *reinterpret_cast<const u32x4*>(gh + (uint32_t)(32 * it + st_row) * (uint32_t)dos + st_col);
-        to[it] = *reinterpret_cast<const u32x4*>(oh + (uint32_t)(32 * it + st_row) * (uint32_t)os + st_col);
+        tq[it] = *reinterpret_cast<const u32x4*>(qh + gr[it] * qs);
+        tg[it] = *reinterpret_cast<const u32x4*>(gh + gr[it] * dos);
+        to[it] = *reinterpret_cast<const u32x4*>(oh + gr[it] * os);
       }
     }
   }
@@ -510,12 +527,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
       }
     }
-    uint16_t* oh = out + (int64_t)(start + kw) * stride + h * kD;
+    uint16_t* oh = out + h * kD + ocol;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int row = 8 * it + orow;
       const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
-      if (kw + row < n) *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)stride + ocol) = w;
+      if (kw + row < n) {
+        const int64_t gr = kRows ? (int64_t)rows[start + kw + row] : (int64_t)(start + kw + row);
+        *reinterpret_cast<u32x4*>(oh + gr * stride) = w;
+      }
     }
   };
 
@@ -560,26 +580,31 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
                                float* delta_ws, hipStream_t stream) {
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
   if (s.max_seqlen <= kTile) {
-    hipLaunchKernelGGL(attn_bwd_fused128_kernel, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
-                       (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs,
-                       ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv, dqs,
-                       dks, dvs, s.T);
+#define MB_LAUNCH_FUSED(R)                                                                                        \
+  hipLaunchKernelGGL(attn_bwd_fused128_kernel<R>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs, \
+                     ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv,     \
+                     dqs, dks, dvs, s.T, s.token_rows)
+    if (s.token_rows) MB_LAUNCH_FUSED(true);
+    else MB_LAUNCH_FUSED(false);
+#undef MB_LAUNCH_FUSED
     return check_launch("attn_bwd_fused128_kernel");
   }
   const int64_t rows = (int64_t)s.T * s.H;
   hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream,
-                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B, delta_ws);
+                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B, delta_ws,
+                     s.token_rows);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   const int tiles = (s.max_seqlen + kTile - 1) / kTile;
   hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T);
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows);
   st = check_launch("attn_bwd_dkv_kernel");
   if (st != MB_OK) return st;
   hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T);
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows);
   return check_launch("attn_bwd_dq_kernel");
 }
 

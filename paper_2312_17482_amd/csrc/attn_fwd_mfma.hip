@@ -25,7 +25,7 @@ constexpr int kVStride = 80;   // LDS row pitch of V in bf16 (160 B): 4-row tran
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
-    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T) {
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows) {
   __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockK * kKStride];
   __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockK * kVStride];
 
@@ -46,8 +46,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
   // Q^T fragments (B operand of S^T = K Q^T): lane = query column, 8 consecutive d per k-step.
   bf16x8 bq[4];
   {
-    const uint16_t* qrow = q + (int64_t)(start + qi) * qs + h * kD + 8 * g;
     const bool ok = wave_active && qi < n;
+    const uint16_t* qrow = q + (ok ? tok_row(rows, start + qi) : 0) * qs + h * kD + 8 * g;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       u32x4 t = {0u, 0u, 0u, 0u};
@@ -76,8 +76,9 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
       const int row = id >> 3, col = (id & 7) * 8;
       u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
       if (j0 + row < n) {
-        tk = *reinterpret_cast<const u32x4*>(k + (int64_t)(start + j0 + row) * ks + h * kD + col);
-        tv = *reinterpret_cast<const u32x4*>(v + (int64_t)(start + j0 + row) * vs + h * kD + col);
+        const int64_t gr = tok_row(rows, start + j0 + row);
+        tk = *reinterpret_cast<const u32x4*>(k + gr * ks + h * kD + col);
+        tv = *reinterpret_cast<const u32x4*>(v + gr * vs + h * kD + col);
       }
       *reinterpret_cast<u32x4*>(&sK[row * kKStride + col]) = tk;
       *reinterpret_cast<u32x4*>(&sV[row * kVStride + col]) = tv;
@@ -161,7 +162,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
   if (!wave_active || qi >= n) return;
   const float l = sum_both_halves(l_run);   // NB: executed by both lanes of a pair (qi is the same)
   const float inv = 1.f / l;
-  uint16_t* orow = o + (int64_t)(start + qi) * os + h * kD + 4 * g;
+  uint16_t* orow = o + tok_row(rows, start + qi) * os + h * kD + 4 * g;
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -189,10 +190,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
 //     the pre-load one fused multiply-add per score;
 //   * the row maximum is taken on the raw accumulator and the scale is folded into the exponent:
 //     p = exp2(acc * c - max * c), c = scale * log2(e)   (requires scale > 0).
+// kRows: the activation buffers are a padded batch and token t sits at row rows[t] (the gather and the
+// scatter of the unpadding step happen in this kernel's own row loads and stores).
+template <bool kRows>
 __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
-    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T) {
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows) {
   // Every global access is a full 128-byte row of one head shared by 8 lanes (16 bytes each); the
   // fragment layouts the matrix cores need are produced by passing through LDS:
   //   sV first carries the Q tile (rows -> Q^T fragments), then V;  after the S phase each wave reuses
@@ -214,7 +218,20 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   // ---- coalesced row loads: thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   u32x4 tq[4], tk[4], tv[4];
-  {
+  if (kRows) {
+    int gr[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) gr[it] = 32 * it + st_row < n ? rows[start + 32 * it + st_row] : 0;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tq[it] = tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < n) {
+        tq[it] = *reinterpret_cast<const u32x4*>(q + (int64_t)gr[it] * qs + h * kD + st_col);
+        tk[it] = *reinterpret_cast<const u32x4*>(k + (int64_t)gr[it] * ks + h * kD + st_col);
+        tv[it] = *reinterpret_cast<const u32x4*>(v + (int64_t)gr[it] * vs + h * kD + st_col);
+      }
+    }
+  } else {
     const uint16_t* qh = q + (int64_t)start * qs + h * kD;
     const uint16_t* kh = k + (int64_t)start * ks + h * kD;
     const uint16_t* vh = v + (int64_t)start * vs + h * kD;
@@ -356,13 +373,16 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     }
   }
   // (same wave wrote and reads the slab: LDS operations of one wave complete in order)
-  uint16_t* oh = o + (int64_t)(start + 32 * wave) * os + h * kD;
+  uint16_t* oh = o + (kRows ? (int64_t)0 : (int64_t)(start + 32 * wave) * os) + h * kD;
   const int orow = lane >> 3, ocol = (lane & 7) * 8;
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int row = 8 * it + orow;
     const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kKStride + ocol]);
-    if (32 * wave + row < n) *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)os + ocol) = w;
+    if (32 * wave + row < n) {
+      if (kRows) *reinterpret_cast<u32x4*>(oh + (int64_t)rows[start + 32 * wave + row] * os + ocol) = w;
+      else *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)os + ocol) = w;
+    }
   }
 }
 
@@ -373,14 +393,19 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
   const int tiles = (s.max_seqlen + kBlockQ - 1) / kBlockQ;
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
   if (s.max_seqlen <= kBlockK) {
-    hipLaunchKernelGGL(attn_fwd_short_kernel, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                       (uint16_t*)o, os, lse, s.T);
+    if (s.token_rows)
+      hipLaunchKernelGGL(attn_fwd_short_kernel<true>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+                         (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
+                         (uint16_t*)o, os, lse, s.T, s.token_rows);
+    else
+      hipLaunchKernelGGL(attn_fwd_short_kernel<false>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+                         (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
+                         (uint16_t*)o, os, lse, s.T, s.token_rows);
     return check_launch("attn_fwd_short_kernel");
   }
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                     (uint16_t*)o, os, lse, s.T);
+                     (uint16_t*)o, os, lse, s.T, s.token_rows);
   return check_launch("attn_fwd_mfma_kernel");
 }
 

@@ -41,7 +41,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
                                                          const E* __restrict__ v, int64_t qs, int64_t ks, int64_t vs,
                                                          const int32_t* __restrict__ cu, int B, int T, int H, int D,
                                                          const float* __restrict__ slopes, float scale,
-                                                         E* __restrict__ o, int64_t os, float* __restrict__ lse) {
+                                                         E* __restrict__ o, int64_t os, float* __restrict__ lse,
+                                                         const int32_t* __restrict__ rows) {
   extern __shared__ float smem[];
   float* sq = smem;
   float* ss = smem + D;
@@ -50,11 +51,11 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, i = t - start;
   const float slope = slopes[h];
-  for (int d = lane; d < D; d += 64) sq[d] = to_f32(q[(int64_t)t * qs + h * D + d]);
+  for (int d = lane; d < D; d += 64) sq[d] = to_f32(q[tok_row(rows, t) * qs + h * D + d]);
   __syncthreads();
   float m = -INFINITY;
   for (int j = lane; j < n; j += 64) {
-    const E* kr = k + (int64_t)(start + j) * ks + h * D;
+    const E* kr = k + tok_row(rows, start + j) * ks + h * D;
     float dot = 0.f;
     for (int d = 0; d < D; ++d) dot = fmaf(sq[d], to_f32(kr[d]), dot);
     const float s = scale * dot - slope * fabsf((float)(i - j));
@@ -73,8 +74,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
   const float inv = 1.f / z;
   for (int d = lane; d < D; d += 64) {
     float acc = 0.f;
-    for (int j = 0; j < n; ++j) acc = fmaf(ss[j], to_f32(v[(int64_t)(start + j) * vs + h * D + d]), acc);
-    from_f32(&o[(int64_t)t * os + h * D + d], acc * inv);
+    for (int j = 0; j < n; ++j) acc = fmaf(ss[j], to_f32(v[tok_row(rows, start + j) * vs + h * D + d]), acc);
+    from_f32(&o[tok_row(rows, t) * os + h * D + d], acc * inv);
   }
   if (lane == 0) lse[(int64_t)h * T + t] = m + logf(z);
 }
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
     const E* __restrict__ dout, const E* __restrict__ q, const E* __restrict__ k, const E* __restrict__ v,
     const E* __restrict__ o, const float* __restrict__ lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
     int64_t os, const int32_t* __restrict__ cu, int B, int T, int H, int D, const float* __restrict__ slopes,
-    float scale, E* __restrict__ dq, int64_t dqs, float* __restrict__ delta) {
+    float scale, E* __restrict__ dq, int64_t dqs, float* __restrict__ delta, const int32_t* __restrict__ rows) {
   extern __shared__ float smem[];
   float* sq = smem;
   float* sg = smem + D;
@@ -98,18 +99,18 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
   const float slope = slopes[h];
   float part = 0.f;
   for (int d = lane; d < D; d += 64) {
-    const float g = to_f32(dout[(int64_t)t * dos + h * D + d]);
-    sq[d] = to_f32(q[(int64_t)t * qs + h * D + d]);
+    const float g = to_f32(dout[tok_row(rows, t) * dos + h * D + d]);
+    sq[d] = to_f32(q[tok_row(rows, t) * qs + h * D + d]);
     sg[d] = g;
-    part = fmaf(g, to_f32(o[(int64_t)t * os + h * D + d]), part);
+    part = fmaf(g, to_f32(o[tok_row(rows, t) * os + h * D + d]), part);
   }
   const float dlt = wave_sum(part);
   if (lane == 0) delta[(int64_t)h * T + t] = dlt;
   __syncthreads();
   const float l = lse[(int64_t)h * T + t];
   for (int j = lane; j < n; j += 64) {
-    const E* kr = k + (int64_t)(start + j) * ks + h * D;
-    const E* vr = v + (int64_t)(start + j) * vs + h * D;
+    const E* kr = k + tok_row(rows, start + j) * ks + h * D;
+    const E* vr = v + tok_row(rows, start + j) * vs + h * D;
     float dot = 0.f, dp = 0.f;
     for (int d = 0; d < D; ++d) {
       dot = fmaf(sq[d], to_f32(kr[d]), dot);
@@ -121,8 +122,8 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
   __syncthreads();
   for (int d = lane; d < D; d += 64) {
     float acc = 0.f;
-    for (int j = 0; j < n; ++j) acc = fmaf(sds[j], to_f32(k[(int64_t)(start + j) * ks + h * D + d]), acc);
-    from_f32(&dq[(int64_t)t * dqs + h * D + d], scale * acc);
+    for (int j = 0; j < n; ++j) acc = fmaf(sds[j], to_f32(k[tok_row(rows, start + j) * ks + h * D + d]), acc);
+    from_f32(&dq[tok_row(rows, t) * dqs + h * D + d], scale * acc);
   }
 }
 
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
     const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos, int64_t qs, int64_t ks,
     int64_t vs, const int32_t* __restrict__ cu, int B, int T, int H, int D, int max_seqlen,
     const float* __restrict__ slopes, float scale, E* __restrict__ dk, E* __restrict__ dv, int64_t dks,
-    int64_t dvs) {
+    int64_t dvs, const int32_t* __restrict__ rows) {
   extern __shared__ float smem[];
   float* sk = smem;
   float* sv = smem + D;
@@ -146,13 +147,13 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
   const int start = cu[b], n = cu[b + 1] - start, j = t - start;
   const float slope = slopes[h];
   for (int d = lane; d < D; d += 64) {
-    sk[d] = to_f32(k[(int64_t)t * ks + h * D + d]);
-    sv[d] = to_f32(v[(int64_t)t * vs + h * D + d]);
+    sk[d] = to_f32(k[tok_row(rows, t) * ks + h * D + d]);
+    sv[d] = to_f32(v[tok_row(rows, t) * vs + h * D + d]);
   }
   __syncthreads();
   for (int i = lane; i < n; i += 64) {
-    const E* qr = q + (int64_t)(start + i) * qs + h * D;
-    const E* gr = dout + (int64_t)(start + i) * dos + h * D;
+    const E* qr = q + tok_row(rows, start + i) * qs + h * D;
+    const E* gr = dout + tok_row(rows, start + i) * dos + h * D;
     float dot = 0.f, dp = 0.f;
     for (int d = 0; d < D; ++d) {
       dot = fmaf(to_f32(qr[d]), sk[d], dot);
@@ -166,11 +167,11 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
   for (int d = lane; d < D; d += 64) {
     float av = 0.f, ak = 0.f;
     for (int i = 0; i < n; ++i) {
-      av = fmaf(sp[i], to_f32(dout[(int64_t)(start + i) * dos + h * D + d]), av);
-      ak = fmaf(sds[i], to_f32(q[(int64_t)(start + i) * qs + h * D + d]), ak);
+      av = fmaf(sp[i], to_f32(dout[tok_row(rows, start + i) * dos + h * D + d]), av);
+      ak = fmaf(sds[i], to_f32(q[tok_row(rows, start + i) * qs + h * D + d]), ak);
     }
-    from_f32(&dv[(int64_t)t * dvs + h * D + d], av);
-    from_f32(&dk[(int64_t)t * dks + h * D + d], scale * ak);
+    from_f32(&dv[tok_row(rows, t) * dvs + h * D + d], av);
+    from_f32(&dk[tok_row(rows, t) * dks + h * D + d], scale * ak);
   }
 }
 
@@ -179,7 +180,7 @@ mb_status fwd_t(const AttnShape& s, const void* q, const void* k, const void* v,
                 void* o, int64_t os, float* lse, hipStream_t stream) {
   const size_t smem = sizeof(float) * ((size_t)s.D + s.max_seqlen);
   hipLaunchKernelGGL(fwd_generic_kernel<E>, dim3(s.T, s.H), dim3(64), smem, stream, (const E*)q, (const E*)k,
-                     (const E*)v, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H, s.D, s.slopes, s.scale, (E*)o, os, lse);
+                     (const E*)v, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H, s.D, s.slopes, s.scale, (E*)o, os, lse, s.token_rows);
   return check_launch("fwd_generic_kernel");
 }
 
@@ -190,13 +191,13 @@ mb_status bwd_t(const AttnShape& s, const void* dout, const void* q, const void*
   const size_t smem_row = sizeof(float) * (2 * (size_t)s.D + s.max_seqlen);
   hipLaunchKernelGGL(bwd_generic_row_kernel<E>, dim3(s.T, s.H), dim3(64), smem_row, stream, (const E*)dout,
                      (const E*)q, (const E*)k, (const E*)v, (const E*)o, lse, dos, qs, ks, vs, os, s.cu_seqlens, s.B,
-                     s.T, s.H, s.D, s.slopes, s.scale, (E*)dq, dqs, delta);
+                     s.T, s.H, s.D, s.slopes, s.scale, (E*)dq, dqs, delta, s.token_rows);
   mb_status st = check_launch("bwd_generic_row_kernel");
   if (st != MB_OK) return st;
   const size_t smem_col = sizeof(float) * (2 * (size_t)s.D + 2 * (size_t)s.max_seqlen);
   hipLaunchKernelGGL(bwd_generic_col_kernel<E>, dim3(s.T, s.H), dim3(64), smem_col, stream, (const E*)dout,
                      (const E*)q, (const E*)k, (const E*)v, lse, delta, dos, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H,
-                     s.D, s.max_seqlen, s.slopes, s.scale, (E*)dk, (E*)dv, dks, dvs);
+                     s.D, s.max_seqlen, s.slopes, s.scale, (E*)dk, (E*)dv, dks, dvs, s.token_rows);
   return check_launch("bwd_generic_col_kernel");
 }
 

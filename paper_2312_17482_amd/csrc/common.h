@@ -21,7 +21,14 @@ struct AttnShape {
   const int32_t* cu_seqlens;
   const float* slopes;
   float scale;
+  const int32_t* token_rows;   // NULL, or [T]: row of token t inside the activation buffers
 };
+
+// Row of packed token t inside the activation buffers: t itself, or token_rows[t] when the call reads
+// and writes a padded batch directly.
+__device__ __forceinline__ int64_t tok_row(const int32_t* __restrict__ rows, int t) {
+  return rows ? (int64_t)rows[t] : (int64_t)t;
+}
 
 // ---- launchers (each enqueues on `stream`, returns MB_OK or MB_ERR_HIP) ----
 mb_status launch_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
@@ -30,6 +37,9 @@ mb_status launch_gather_rows(const void* padded, const int32_t* indices, int T_c
                              int row_bytes, void* packed, hipStream_t stream);
 mb_status launch_scatter_rows(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta,
                               int rows_padded, int row_bytes, void* padded, hipStream_t stream);
+
+mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta, int rows_padded,
+                              int row_bytes, void* padded, hipStream_t stream);
 
 // Generic ALU kernels: any D <= 128, fp32 or bf16 storage, fp32 arithmetic.
 static constexpr int kGenericMaxSeqlen = 16384;

@@ -122,6 +122,8 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const uint4* __re
 
 // Block = 8 consecutive padded rows p0..p0+7.  Wave 0 finds t0 = first t with indices[t] >= p0 by a
 // 64-ary search (indices ascending); the rows of the block that are kept then sit at t0, t0+1, ...
+// kCopy = false: only the rows that are not listed in `indices` are written (with zeros).
+template <bool kCopy>
 __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __restrict__ packed,
                                                                 const int32_t* __restrict__ indices, int T_cap,
                                                                 const int32_t* __restrict__ meta, int rows_padded,
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
   uint4* dst = padded + (size_t)p * units;
   const int lane = threadIdx.x % kLanesPerRow;
   if (kept) {
-    copy_row(packed + (size_t)(t0 + c) * units, dst, units, lane);
+    if (kCopy) copy_row(packed + (size_t)(t0 + c) * units, dst, units, lane);
   } else {
     const uint4 z = make_uint4(0u, 0u, 0u, 0u);
     for (int u = lane; u < units; u += kLanesPerRow) dst[u] = z;
@@ -189,9 +191,17 @@ mb_status launch_gather_rows(const void* padded, const int32_t* indices, int T_c
 mb_status launch_scatter_rows(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta,
                               int rows_padded, int row_bytes, void* padded, hipStream_t stream) {
   const int blocks = (rows_padded + kRowsPerBlock - 1) / kRowsPerBlock;
-  hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)packed, indices,
-                     T_cap, meta, rows_padded, row_bytes / 16, (uint4*)padded);
+  hipLaunchKernelGGL(scatter_rows_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)packed,
+                     indices, T_cap, meta, rows_padded, row_bytes / 16, (uint4*)padded);
   return check_launch("scatter_rows_kernel");
+}
+
+mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta, int rows_padded,
+                              int row_bytes, void* padded, hipStream_t stream) {
+  const int blocks = (rows_padded + kRowsPerBlock - 1) / kRowsPerBlock;
+  hipLaunchKernelGGL(scatter_rows_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)nullptr,
+                     indices, T_cap, meta, rows_padded, row_bytes / 16, (uint4*)padded);
+  return check_launch("scatter_rows_kernel<zero only>");
 }
 
 }  // namespace mb

@@ -46,20 +46,20 @@ def test_slopes_against_fixture():
 
 def fwd_args(**over):
     a = dict(q=A, k=A, v=A, qs=768, ks=768, vs=768, cu=A, B=2, T=64, max_seqlen=32, H=12, D=64, slopes=A,
-             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, stream=None)
+             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, rows=None, stream=None)
     a.update(over)
     return [a[x] for x in ("q", "k", "v", "qs", "ks", "vs", "cu", "B", "T", "max_seqlen", "H", "D", "slopes", "scale",
-                           "dt", "o", "os", "lse", "stream")]
+                           "dt", "o", "os", "lse", "rows", "stream")]
 
 
 def bwd_args(**over):
     a = dict(do=A, q=A, k=A, v=A, o=A, lse=A, dos=768, qs=768, ks=768, vs=768, os=768, cu=A, B=2, T=64,
              max_seqlen=32, H=12, D=64, slopes=A, scale=0.125, dt=mb.MB_BF16, dq=A, dk=A, dv=A, dqs=768, dks=768,
-             dvs=768, ws=A, wsb=1 << 20, stream=None)
+             dvs=768, ws=A, wsb=1 << 20, rows=None, stream=None)
     a.update(over)
     return [a[x] for x in ("do", "q", "k", "v", "o", "lse", "dos", "qs", "ks", "vs", "os", "cu", "B", "T",
                            "max_seqlen", "H", "D", "slopes", "scale", "dt", "dq", "dk", "dv", "dqs", "dks", "dvs",
-                           "ws", "wsb", "stream")]
+                           "ws", "wsb", "rows", "stream")]
 
 
 @pytest.mark.parametrize("over,status,needle", [
@@ -76,6 +76,7 @@ def bwd_args(**over):
     (dict(scale=float("nan")), mb.MB_ERR_INVALID_ARG, "finite"),
     (dict(max_seqlen=0), mb.MB_ERR_INVALID_ARG, "max_seqlen"),
     (dict(dt=mb.MB_F32, D=16, H=2, max_seqlen=1 << 20), mb.MB_ERR_UNSUPPORTED, "max_seqlen"),
+    (dict(rows=A + 4), mb.MB_ERR_INVALID_ARG, "token_rows"),
 ])
 def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
     assert lib.mb_alibi_attn_fwd(*fwd_args(**over)) == status
@@ -134,6 +135,9 @@ def test_pad_and_index_reject_bad_arguments():
     assert lib.mb_unpad_index(A, 1 << 16, 1 << 16, A, A, A, A, None) == mb.MB_ERR_UNSUPPORTED
     assert lib.mb_unpad_index(A, 2, 8, A, A, A, None, None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_read_meta(None, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_zero_padding(A, 100, None, 2, 8, 768, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_zero_padding(A, 4, None, 2, 8, 768, mb.MB_BF16, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_zero_padding(None, 0, None, 0, 8, 768, mb.MB_BF16, None, None) == mb.MB_OK
 
 
 def test_product_package_never_imports_the_oracle():

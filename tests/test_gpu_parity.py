@@ -281,3 +281,41 @@ def test_capacity_mode_needs_no_host_round_trip(mb, bf16, D, L):
     torch.cuda.synchronize()
     assert torch.equal(o_cap[:T], o_ex) and torch.equal(lse_cap[:, :T], lse_ex) and torch.equal(g_cap[:T], g_ex)
     assert torch.all(o_cap[T:] == guard) and torch.all(lse_cap[:, T:] == guard) and torch.all(g_cap[T:] == guard)
+
+
+@pytest.mark.parametrize("bf16,D,L,holes", [(True, 64, 128, False), (True, 64, 128, True), (True, 64, 300, False),
+                                             (False, 16, 64, False), (True, 32, 40, False)])
+def test_token_rows_mode_equals_explicit_unpad_and_pad(mb, bf16, D, L, holes):
+    """Attention reading and writing the padded batch directly (token_rows = indices) + mb_zero_padding
+    gives bit-for-bit what mb_unpad -> attention -> mb_pad gives."""
+    print("token_rows bf16=%s D=%d L=%d holes=%s" % (bf16, D, L, holes), flush=True)
+    lengths = [L, 17, 0, L // 2, 33, 1]
+    c = wl.random_attention_case(51, lengths, L, 2, D, std=0.5, bf16=bf16)
+    if holes:   # any 0/1 mask: the kept tokens of a row form its sequence
+        c["mask"] = wl.random_mask(52, len(lengths), L, 0.7)
+    B, _, H, _ = c["q"].shape
+    cap = B * L
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    slopes_h = mb.mb_alibi_slopes(H)
+    ref = run_hip_path(mb, c, slopes_h, bf16=bf16)            # explicit unpad -> attention -> pad
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(c["mask"]).cuda())
+    qkv_p = to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(cap, 3 * H * D), bf16).view(cap, 3, H, D)
+    do_p = to_dev(c["do"].reshape(cap, H * D), bf16).view(cap, H, D)
+    slopes = slopes_h.cuda()
+    garbage = 5.0
+    o_p = torch.full((cap, H, D), garbage, dtype=tdt, device="cuda")
+    lse = torch.full((H, cap), garbage, dtype=torch.float32, device="cuda")
+    mb.mb_alibi_attn_fwd(qkv_p[:, 0], qkv_p[:, 1], qkv_p[:, 2], cu, L, slopes, c["scale"], out=o_p, lse=lse,
+                         token_rows=indices, T=cap)
+    mb.mb_zero_padding(o_p.view(cap, H * D), indices, cap, meta, B, L)
+    g_p = torch.full((cap, 3, H, D), garbage, dtype=tdt, device="cuda")
+    mb.mb_alibi_attn_bwd(do_p, qkv_p[:, 0], qkv_p[:, 1], qkv_p[:, 2], o_p, lse, cu, L, slopes, c["scale"],
+                         dq=g_p[:, 0], dk=g_p[:, 1], dv=g_p[:, 2], token_rows=indices, T=cap)
+    mb.mb_zero_padding(g_p.view(cap, 3 * H * D), indices, cap, meta, B, L)
+    torch.cuda.synchronize()
+    T = ref["T"]
+    assert np.array_equal(o_p.double().cpu().numpy().reshape(B, L, H, D), ref["o"])
+    got = g_p.double().cpu().numpy().reshape(B, L, 3, H, D)
+    assert np.array_equal(got[:, :, 0], ref["dq"]) and np.array_equal(got[:, :, 1], ref["dk"])
+    assert np.array_equal(got[:, :, 2], ref["dv"])
+    assert np.array_equal(lse[:, :T].double().cpu().numpy(), ref["lse"]) and torch.all(lse[:, T:] == garbage)
