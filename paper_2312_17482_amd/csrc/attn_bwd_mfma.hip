@@ -8,15 +8,17 @@
 //
 // Three kernels, no atomics (results are bitwise reproducible):
 //   delta : Delta = rowsum(dO * O), [H, T] float.
-//   dkv   : one workgroup per (sequence, head, 128 keys); wave w owns 32 keys and walks all queries.
+//   dkv   : one workgroup per (sequence, head, 128 keys); wave w owns 32 keys and streams all queries.
 //           Scores in natural orientation S = Q K^T (queries along accumulator rows, keys along
 //           lanes) so that P and dS, rounded to bf16, are directly the B operands of
 //           dV^T += dO^T P and dK^T += Q^T dS.
-//   dq    : one workgroup per (sequence, head, 128 queries); wave w owns 32 queries and walks all keys.
+//   dq    : one workgroup per (sequence, head, 128 queries); wave w owns 32 queries and streams all keys.
 //           Transposed scores S^T = K Q^T (as in the forward) so that dS^T is directly the B operand
 //           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.
 // Masking costs nothing: rows beyond the sequence end are staged as zeros and their lse as +inf
 // (P = 0); zero K/V rows make the products with out-of-range keys vanish.
+#include <type_traits>
+
 #include "common.h"
 #include "mfma_util.h"
 
@@ -57,35 +59,30 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
   if (ok && sub == 0) delta[(int64_t)h * T + t] = acc;
 }
 
-// Stage rows r0..r0+127 of one head ([*, 64] bf16, token stride `stride`) into LDS with pitch kPitch;
-// rows at or beyond n become zeros.
-// `src` points at column 0 of this head in row 0 of the buffer; token `tok0 + r` of the sequence sits
-// at buffer row tok_row(rows, tok0 + r).
-__device__ __forceinline__ void stage_tile(uint16_t* dst, const uint16_t* __restrict__ src, int64_t stride,
-                                           int r0, int n, int tid, const int32_t* __restrict__ rows, int tok0) {
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int id = tid + 256 * it;
-    const int row = id >> 3, col = (id & 7) * 8;
-    u32x4 t = {0u, 0u, 0u, 0u};
-    if (r0 + row < n) t = *reinterpret_cast<const u32x4*>(src + tok_row(rows, tok0 + r0 + row) * stride + col);
-    *reinterpret_cast<u32x4*>(&dst[row * kPitch + col]) = t;
-  }
-}
+// ------------------------------------------------------------------------------------------------ any length
+// Both kernels below stream their second operand in tiles of 64 rows through two LDS buffers: while
+// one tile is consumed the next travels HBM -> registers -> the other buffer (one barrier per tile).
+// Global memory is touched only as full 128-byte rows of one head; fragments and output rows pass
+// through LDS.  Workgroups are dispatched longest sequence first.
+constexpr int kTileS = 64;                          // rows of a streamed tile
+constexpr int kHalf = kTileS * kPitch;              // elements of one streamed operand tile (4608)
+constexpr int kBuf = 2 * kHalf;                     // one buffer: two operand tiles (= 128 rows of pitch 72)
 
 // ------------------------------------------------------------------------------------------------ dK, dV
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
+// One workgroup per (sequence, head, 128 keys); wave w owns keys 32w.. and streams all queries.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
     const int32_t* __restrict__ rows) {
-  __shared__ __attribute__((aligned(16))) uint16_t sQ[kTile * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t sG[kTile * kPitch];   // dO
-  __shared__ __attribute__((aligned(16))) float sLse[kTile];             // lse in base-2 units, +inf past the end
-  __shared__ __attribute__((aligned(16))) float sDelta[kTile];
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: Q tile, dO tile
+  __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
+  __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
+  __shared__ int s_seq;
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
+  const int h = blockIdx.y;
   const int start = cu[b];
   const int n = cu[b + 1] - start;
   const int kv0 = blockIdx.x * kTile;
@@ -96,128 +93,201 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
   const int kw = kv0 + 32 * wave;
   const bool wave_active = kw < n;
   const int kj = kw + c;                      // this lane's key
+  const int kblk = (kv0 >> 5) + wave;         // index of this wave's block of 32 keys
+  const int ntiles = (n + kTileS - 1) / kTileS;
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   const float cs = scale * kLog2e;
-  const float slope2 = slopes[h] * kLog2e;
+  const float k1 = slopes[h] / scale;
 
-  // K^T and V^T fragments (B operands): lane = key column, 8 consecutive d per k-step.
+  // ---- K, V rows of this workgroup's 128 keys (coalesced) -> LDS -> K^T, V^T fragments
   bf16x8 bk[4], bv[4];
   {
-    const bool ok = wave_active && kj < n;
-    const int64_t gr = ok ? tok_row(rows, start + kj) : 0;
-    const uint16_t* krow = k + gr * ks + h * kD + 8 * g;
-    const uint16_t* vrow = v + gr * vs + h * kD + 8 * g;
+    u32x4 tk[4], tv[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      const int j = kv0 + 32 * it + st_row;
+      if (j < n) {
+        const int64_t gr = tok_row(rows, start + j);
+        tk[it] = *reinterpret_cast<const u32x4*>(k + gr * ks + h * kD + st_col);
+        tv[it] = *reinterpret_cast<const u32x4*>(v + gr * vs + h * kD + st_col);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      *reinterpret_cast<u32x4*>(&smem[(32 * it + st_row) * kPitch + st_col]) = tk[it];
+      *reinterpret_cast<u32x4*>(&smem[kBuf + (32 * it + st_row) * kPitch + st_col]) = tv[it];
+    }
+    __syncthreads();
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
-      if (ok) {
-        tk = *reinterpret_cast<const u32x4*>(krow + 16 * s);
-        tv = *reinterpret_cast<const u32x4*>(vrow + 16 * s);
-      }
-      bk[s] = as_bf16x8(tk);
-      bv[s] = as_bf16x8(tv);
+      bk[s] = lds_read8(&smem[(32 * wave + c) * kPitch + 16 * s + 8 * g]);
+      bv[s] = lds_read8(&smem[kBuf + (32 * wave + c) * kPitch + 16 * s + 8 * g]);
     }
+    __syncthreads();
   }
+
+  // ---- streamed Q / dO tiles
+  const uint16_t* qh = q + h * kD + st_col;
+  const uint16_t* gh = dout + h * kD + st_col;
+  u32x4 tq[2], tg[2];
+  float tl = 0.f, td = 0.f;
+  auto issue_tile = [&](int i0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      tq[it] = tg[it] = u32x4{0u, 0u, 0u, 0u};
+      const int i = i0 + 32 * it + st_row;
+      if (i < n) {
+        const int64_t gr = tok_row(rows, start + i);
+        tq[it] = *reinterpret_cast<const u32x4*>(qh + gr * qs);
+        tg[it] = *reinterpret_cast<const u32x4*>(gh + gr * dos);
+      }
+    }
+    if (tid < kTileS) {
+      const bool ok = i0 + tid < n;
+      tl = ok ? -lse[(int64_t)h * T + start + i0 + tid] * kLog2e : -INFINITY;
+      td = ok ? -delta[(int64_t)h * T + start + i0 + tid] : 0.f;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    uint16_t* bq_ = smem + buf * kBuf;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      *reinterpret_cast<u32x4*>(&bq_[(32 * it + st_row) * kPitch + st_col]) = tq[it];
+      *reinterpret_cast<u32x4*>(&bq_[kHalf + (32 * it + st_row) * kPitch + st_col]) = tg[it];
+    }
+    if (tid < kTileS) { sL[buf][tid] = tl; sD[buf][tid] = td; }
+  };
 
   f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows (two blocks of 32), keys along lanes
 #pragma unroll
   for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
-
   const int tr_i = lane & 15, tr_q = lane >> 4;
   const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
   const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+  float fj = (float)(kj - 4 * g);   // i - j = ci - fj with ci = i0 + 32ib + 8*(v/4) + v%4
+  asm volatile("" : "+v"(fj));
 
-  for (int i0 = 0; i0 < n; i0 += kTile) {
-    if (i0 > 0) __syncthreads();
-    stage_tile(sQ, q + h * kD, qs, i0, n, tid, rows, start);
-    stage_tile(sG, dout + h * kD, dos, i0, n, tid, rows, start);
-    if (tid < kTile) {
-      const bool ok = i0 + tid < n;
-      sLse[tid] = ok ? lse[(int64_t)h * T + start + i0 + tid] * kLog2e : INFINITY;
-      sDelta[tid] = ok ? delta[(int64_t)h * T + start + i0 + tid] : 0.f;
+  // One block of 32 queries (rows 32ib.. of the staged tile) against this wave's keys.  The S accumulator
+  // is pre-loaded with bias/scale and the dP accumulator with -Delta_i, so that after the products
+  // P = exp2(acc_S * c - lse2_i) and dS = P * acc_dP.  kDiag: the block contains the diagonal.
+  auto qblock = [&](const uint16_t* sQ, const uint16_t* sG, const float* pl, const float* pd, int i0, int ib,
+                    auto diag_tag) {
+    constexpr bool kDiag = decltype(diag_tag)::value;
+    f32x16 sacc, pacc;
+    const float d0 = (float)(i0 + 32 * ib) - fj;
+    if (kDiag) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
+    } else {
+      const float sk = (i0 >> 5) + ib < kblk ? k1 : -k1;
+      const float a = sk * d0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
     }
-    __syncthreads();
-    if (!wave_active) continue;
-
-    const int rem = n - i0;
-    const int nblk = rem >= kTile ? 4 : (rem + 31) >> 5;
-    const float fj = (float)(kj - i0 - 4 * g);
-#pragma unroll 1
-    for (int ib = 0; ib < nblk; ++ib) {
-      // S = Q K^T and dP = dO V^T for queries i0+32ib.., this wave's keys
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
-      const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
-      const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
-        pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
-      }
-      // P = exp2(S*cs - slope2*|i-j| - lse2_i),  dS = P (dP - Delta_i); accumulator row = query
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
-        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-        const float dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * r + e;
-          const float ci = (float)(32 * ib + 8 * r + e);
-          const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fj - ci));
-          const float p = fast_exp2(x - lv[e]);
-          sacc[i] = p;
-          pacc[i] = p * (pacc[i] - dl[e]);
-        }
-      }
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
-                                sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
-        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
-                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
-        const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
-          dvacc[db] = mfma32(ag, bp, dvacc[db]);
-          const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
-          dkacc[db] = mfma32(aq, bs, dkacc[db]);
-        }
-      }
-    }
-  }
-
-  if (!wave_active || kj >= n) return;
-  const int64_t orow_idx = tok_row(rows, start + kj);
-  uint16_t* dkrow = dk + orow_idx * dks + h * kD + 4 * g;
-  uint16_t* dvrow = dv + orow_idx * dvs + h * kD + 4 * g;
-#pragma unroll
-  for (int db = 0; db < 2; ++db) {
+    float nl[16];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      u32x2 w;
-      w[0] = pack_bf16(dkacc[db][4 * r + 0] * scale, dkacc[db][4 * r + 1] * scale);
-      w[1] = pack_bf16(dkacc[db][4 * r + 2] * scale, dkacc[db][4 * r + 3] * scale);
-      *reinterpret_cast<u32x2*>(dkrow + 32 * db + 8 * r) = w;
-      w[0] = pack_bf16(dvacc[db][4 * r + 0], dvacc[db][4 * r + 1]);
-      w[1] = pack_bf16(dvacc[db][4 * r + 2], dvacc[db][4 * r + 3]);
-      *reinterpret_cast<u32x2*>(dvrow + 32 * db + 8 * r) = w;
+      const float4 l4 = *reinterpret_cast<const float4*>(&pl[32 * ib + 8 * r + 4 * g]);
+      const float4 d4 = *reinterpret_cast<const float4*>(&pd[32 * ib + 8 * r + 4 * g]);
+      nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
+      pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
     }
+    const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
+    const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
+      pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float p = fast_exp2(fmaf(sacc[i], cs, nl[i]));
+      sacc[i] = p;
+      pacc[i] = p * pacc[i];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
+                              sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
+      const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                              pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+      const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
+        dvacc[db] = mfma32(ag, bp, dvacc[db]);
+        const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
+        dkacc[db] = mfma32(aq, bs, dkacc[db]);
+      }
+    }
+  };
+
+  issue_tile(0);
+  store_tile(0);
+#pragma unroll 1
+  for (int it = 0; it < ntiles; ++it) {
+    const int i0 = it * kTileS;
+    __syncthreads();   // tile `it` is complete in its buffer; the other buffer is no longer being read
+    if (it + 1 < ntiles) issue_tile(i0 + kTileS);
+    if (wave_active) {
+      const uint16_t* sQ = smem + (it & 1) * kBuf;
+      const uint16_t* sG = sQ + kHalf;
+      const float* pl = sL[it & 1];
+      const float* pd = sD[it & 1];
+      if (2 * it + 1 < kblk || 2 * it > kblk) {   // both query blocks off the diagonal: straight-line code
+        qblock(sQ, sG, pl, pd, i0, 0, std::false_type{});
+        if (i0 + 32 < n) qblock(sQ, sG, pl, pd, i0, 1, std::false_type{});
+      } else {
+        if (2 * it == kblk) qblock(sQ, sG, pl, pd, i0, 0, std::true_type{});
+        else qblock(sQ, sG, pl, pd, i0, 0, std::false_type{});
+        if (i0 + 32 < n) {
+          if (2 * it + 1 == kblk) qblock(sQ, sG, pl, pd, i0, 1, std::true_type{});
+          else qblock(sQ, sG, pl, pd, i0, 1, std::false_type{});
+        }
+      }
+    }
+    if (it + 1 < ntiles) store_tile((it + 1) & 1);
   }
+  __syncthreads();   // the buffers are free: they now carry the output rows
+  if (!wave_active) return;
+
+  uint16_t* slab = &smem[(32 * wave) * kPitch];   // 32 rows private to this wave
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+  auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride) {
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        u32x2 w;
+        w[0] = pack_bf16(acc[db][4 * r + 0] * mul, acc[db][4 * r + 1] * mul);
+        w[1] = pack_bf16(acc[db][4 * r + 2] * mul, acc[db][4 * r + 3] * mul);
+        *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = 8 * it + orow;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      if (kw + row < n) *reinterpret_cast<u32x4*>(out + tok_row(rows, start + kw + row) * stride + h * kD + ocol) = w;
+    }
+  };
+  store_rows(dkacc, scale, dk, dks);
+  store_rows(dvacc, 1.f, dv, dvs);
 }
 
 // ------------------------------------------------------------------------------------------------ dQ
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+// One workgroup per (sequence, head, 128 queries); wave w owns queries 32w.. and streams all keys.
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ rows) {
-  __shared__ __attribute__((aligned(16))) uint16_t sK[kTile * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[kTile * kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
+  __shared__ int s_seq;
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
+  const int h = blockIdx.y;
   const int start = cu[b];
   const int n = cu[b + 1] - start;
   const int q0 = blockIdx.x * kTile;
@@ -229,86 +299,153 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
   const bool wave_active = qw < n;
   const int qi = qw + c;
   const bool q_ok = wave_active && qi < n;
+  const int qblk = (q0 >> 5) + wave;
+  const int ntiles = (n + kTileS - 1) / kTileS;
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   const float cs = scale * kLog2e;
-  const float slope2 = slopes[h] * kLog2e;
+  const float k1 = slopes[h] / scale;
 
-  bf16x8 bq[4], bg[4];   // Q^T and dO^T fragments (B operands): lane = query column
+  // ---- Q, dO rows of this workgroup's 128 queries (coalesced) -> LDS -> Q^T, dO^T fragments
+  bf16x8 bq[4], bg[4];
   {
-    const int64_t gr = q_ok ? tok_row(rows, start + qi) : 0;
-    const uint16_t* qrow = q + gr * qs + h * kD + 8 * g;
-    const uint16_t* grow = dout + gr * dos + h * kD + 8 * g;
+    u32x4 tq[4], tg[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tq[it] = tg[it] = u32x4{0u, 0u, 0u, 0u};
+      const int i = q0 + 32 * it + st_row;
+      if (i < n) {
+        const int64_t gr = tok_row(rows, start + i);
+        tq[it] = *reinterpret_cast<const u32x4*>(q + gr * qs + h * kD + st_col);
+        tg[it] = *reinterpret_cast<const u32x4*>(dout + gr * dos + h * kD + st_col);
+      }
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      *reinterpret_cast<u32x4*>(&smem[(32 * it + st_row) * kPitch + st_col]) = tq[it];
+      *reinterpret_cast<u32x4*>(&smem[kBuf + (32 * it + st_row) * kPitch + st_col]) = tg[it];
+    }
+    __syncthreads();
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      u32x4 tq = {0u, 0u, 0u, 0u}, tg = {0u, 0u, 0u, 0u};
-      if (q_ok) {
-        tq = *reinterpret_cast<const u32x4*>(qrow + 16 * s);
-        tg = *reinterpret_cast<const u32x4*>(grow + 16 * s);
-      }
-      bq[s] = as_bf16x8(tq);
-      bg[s] = as_bf16x8(tg);
+      bq[s] = lds_read8(&smem[(32 * wave + c) * kPitch + 16 * s + 8 * g]);
+      bg[s] = lds_read8(&smem[kBuf + (32 * wave + c) * kPitch + 16 * s + 8 * g]);
     }
+    __syncthreads();
   }
-  const float lse2 = q_ok ? lse[(int64_t)h * T + start + qi] * kLog2e : INFINITY;
-  const float dlt = q_ok ? delta[(int64_t)h * T + start + qi] : 0.f;
+  const float nlse2 = q_ok ? -lse[(int64_t)h * T + start + qi] * kLog2e : -INFINITY;   // -inf: P = 0
+  const float ndlt = q_ok ? -delta[(int64_t)h * T + start + qi] : 0.f;
+
+  // ---- streamed K / V tiles
+  const uint16_t* kh = k + h * kD + st_col;
+  const uint16_t* vh = v + h * kD + st_col;
+  u32x4 tk[2], tv[2];
+  auto issue_tile = [&](int j0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      const int j = j0 + 32 * it + st_row;
+      if (j < n) {
+        const int64_t gr = tok_row(rows, start + j);
+        tk[it] = *reinterpret_cast<const u32x4*>(kh + gr * ks);
+        tv[it] = *reinterpret_cast<const u32x4*>(vh + gr * vs);
+      }
+    }
+  };
+  auto store_tile = [&](int buf) {
+    uint16_t* bk_ = smem + buf * kBuf;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      *reinterpret_cast<u32x4*>(&bk_[(32 * it + st_row) * kPitch + st_col]) = tk[it];
+      *reinterpret_cast<u32x4*>(&bk_[kHalf + (32 * it + st_row) * kPitch + st_col]) = tv[it];
+    }
+  };
 
   f32x16 dqacc[2];   // dQ^T: d along accumulator rows, queries along lanes
 #pragma unroll
   for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
-
   const int tr_i = lane & 15, tr_q = lane >> 4;
   const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
   const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
 
-  for (int j0 = 0; j0 < n; j0 += kTile) {
-    if (j0 > 0) __syncthreads();
-    stage_tile(sK, k + h * kD, ks, j0, n, tid, rows, start);
-    stage_tile(sV, v + h * kD, vs, j0, n, tid, rows, start);
-    __syncthreads();
-    if (!wave_active) continue;
+  // One block of 32 keys (rows 32jb.. of the staged tile) against this wave's queries, transposed
+  // orientation: S^T = K Q^T (+ bias/scale pre-loaded), dP^T = V dO^T (- Delta pre-loaded).
+  // kDiag: the block contains the diagonal.  kRagged: keys at or past `lim` do not exist.
+  auto kblock = [&](const uint16_t* sK, const uint16_t* sV, int j0, int jb, int lim, auto diag_tag, auto ragged_tag) {
+    constexpr bool kDiag = decltype(diag_tag)::value;
+    constexpr bool kRagged = decltype(ragged_tag)::value;
+    float fi = (float)(qi - j0 - 4 * g);   // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
+    asm volatile("" : "+v"(fi));
+    f32x16 sacc, pacc;
+    if (kDiag) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(fi - (float)(jb * 32 + 8 * (i >> 2) + (i & 3)));
+    } else {
+      const float sk = (j0 >> 5) + jb < qblk ? k1 : -k1;
+      const float a = -sk * fi;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) pacc[i] = ndlt;
+    const uint16_t* krow = &sK[(32 * jb + c) * kPitch + 8 * g];
+    const uint16_t* vrow = &sV[(32 * jb + c) * kPitch + 8 * g];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      sacc = mfma32(lds_read8(krow + 16 * s), bq[s], sacc);
+      pacc = mfma32(lds_read8(vrow + 16 * s), bg[s], pacc);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float p = fast_exp2(fmaf(sacc[i], cs, nlse2));
+      float ds = p * pacc[i];
+      // a key past the sequence end has a zero K row, but its p may overflow (its score was never part
+      // of lse): force the product with that zero row to be 0, not inf * 0
+      if (kRagged && 32 * jb + 8 * (i >> 2) + (i & 3) >= lim) ds = 0.f;
+      pacc[i] = ds;
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                              pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+      const int roff = (32 * jb + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const bf16x8 ak = join_tr(lds_read_tr4(&sK[roff + 32 * db]), lds_read_tr4(&sK[roff + 32 * db + 8 * kPitch]));
+        dqacc[db] = mfma32(ak, bs, dqacc[db]);
+      }
+    }
+  };
 
-    const int rem = n - j0;
-    const int nblk = rem >= kTile ? 4 : (rem + 31) >> 5;
-    const float fi = (float)(qi - j0 - 4 * g);
-    const int lim = rem - 4 * g;   // key (32jb + 8*(i/4) + i%4) of this half-wave is real iff that number < lim
+  issue_tile(0);
+  store_tile(0);
 #pragma unroll 1
-    for (int jb = 0; jb < nblk; ++jb) {
-      f32x16 sacc, pacc;   // S^T = K Q^T, dP^T = V dO^T: keys along accumulator rows
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; pacc[i] = 0.f; }
-      const uint16_t* krow = &sK[(32 * jb + c) * kPitch + 8 * g];
-      const uint16_t* vrow = &sV[(32 * jb + c) * kPitch + 8 * g];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        sacc = mfma32(lds_read8(krow + 16 * s), bq[s], sacc);
-        pacc = mfma32(lds_read8(vrow + 16 * s), bg[s], pacc);
-      }
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float cj = (float)(32 * jb + 8 * (i >> 2) + (i & 3));
-        const float x = fmaf(sacc[i], cs, -slope2 * fabsf(fi - cj));
-        const float p = fast_exp2(x - lse2);
-        float ds = p * (pacc[i] - dlt);
-        // a key past the sequence end has a zero K row, but its p may overflow (its score was never
-        // part of lse): force the product with that zero row to be 0, not inf * 0
-        if (rem < kTile && 32 * jb + 8 * (i >> 2) + (i & 3) >= lim) ds = 0.f;
-        pacc[i] = ds;
-      }
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
-                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
-        const int roff = (32 * jb + 16 * kk + tr_row) * kPitch + tr_col;
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const bf16x8 ak = join_tr(lds_read_tr4(&sK[roff + 32 * db]), lds_read_tr4(&sK[roff + 32 * db + 8 * kPitch]));
-          dqacc[db] = mfma32(ak, bs, dqacc[db]);
+  for (int jt = 0; jt < ntiles; ++jt) {
+    const int j0 = jt * kTileS;
+    __syncthreads();
+    if (jt + 1 < ntiles) issue_tile(j0 + kTileS);
+    if (wave_active) {
+      const uint16_t* sK = smem + (jt & 1) * kBuf;
+      const uint16_t* sV = sK + kHalf;
+      const int rem = n - j0;
+      const int lim = rem - 4 * g;
+      if (rem >= kTileS && (2 * jt + 1 < qblk || 2 * jt > qblk)) {   // full tile off the diagonal
+        kblock(sK, sV, j0, 0, lim, std::false_type{}, std::false_type{});
+        kblock(sK, sV, j0, 1, lim, std::false_type{}, std::false_type{});
+      } else {
+        if (2 * jt == qblk) kblock(sK, sV, j0, 0, lim, std::true_type{}, std::true_type{});
+        else kblock(sK, sV, j0, 0, lim, std::false_type{}, std::true_type{});
+        if (rem > 32) {
+          if (2 * jt + 1 == qblk) kblock(sK, sV, j0, 1, lim, std::true_type{}, std::true_type{});
+          else kblock(sK, sV, j0, 1, lim, std::false_type{}, std::true_type{});
         }
       }
     }
+    if (jt + 1 < ntiles) store_tile((jt + 1) & 1);
   }
+  __syncthreads();
+  if (!wave_active) return;
 
-  if (!q_ok) return;
-  uint16_t* dqrow = dq + tok_row(rows, start + qi) * dqs + h * kD + 4 * g;
+  uint16_t* slab = &smem[(32 * wave) * kPitch];
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -316,11 +453,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
       u32x2 w;
       w[0] = pack_bf16(dqacc[db][4 * r + 0] * scale, dqacc[db][4 * r + 1] * scale);
       w[1] = pack_bf16(dqacc[db][4 * r + 2] * scale, dqacc[db][4 * r + 3] * scale);
-      *reinterpret_cast<u32x2*>(dqrow + 32 * db + 8 * r) = w;
+      *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
     }
   }
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = 8 * it + orow;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+    if (qw + row < n) *reinterpret_cast<u32x4*>(dq + tok_row(rows, start + qw + row) * dqs + h * kD + ocol) = w;
+  }
 }
-
 
 // ------------------------------------------------------------------------------------------------ fused, n <= 128
 // Whole backward of one (sequence, head) with at most 128 tokens in one workgroup: every input is read

@@ -6,10 +6,13 @@
 //
 // Work split: one workgroup (4 waves) per (sequence, head, tile of 128 queries); wave w owns queries
 // 32w..32w+31 of the tile.  K and V tiles of 128 keys are staged in LDS and shared by the 4 waves.
+// Global memory is always touched as full 128-byte rows of one head (8 lanes x 16 bytes).
 // Scores are produced TRANSPOSED, S^T = K Q^T (keys along accumulator rows, queries along lanes), so
 //   * a query's row statistics (max, sum) are reductions over a lane's own registers plus one
 //     exchange with the partner lane l^32, and
 //   * the accumulator tile, rounded to bf16, is already the B operand of O^T += V^T P^T.
+#include <type_traits>
+
 #include "common.h"
 #include "mfma_util.h"
 
@@ -22,14 +25,24 @@ constexpr int kD = 64;
 constexpr int kKStride = 72;   // LDS row pitch of K in bf16 (144 B): 16-byte row reads spread over banks
 constexpr int kVStride = 80;   // LDS row pitch of V in bf16 (160 B): 4-row transposing reads spread over banks
 
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
+// Any sequence length: tiles of 64 keys with a running (online) softmax.  LDS holds two K/V tiles: while
+// one is consumed, the next travels HBM -> registers -> the other buffer, so a workgroup waits for memory
+// only on its first tile and there is one barrier per tile.  Registers are kept <= 128 so that four
+// workgroups share a compute unit.  Same arithmetic as the single-tile kernel below (bias pre-loaded
+// into the accumulator, scale folded into the exponent); the running output is rescaled only when some
+// query's maximum actually moved.
+constexpr int kTileK = 64;                                        // keys per LDS tile
+constexpr int kBufElems = kTileK * kKStride + kTileK * kVStride;  // one K tile + one V tile
+
+__global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
     uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows) {
-  __shared__ __attribute__((aligned(16))) uint16_t sK[kBlockK * kKStride];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[kBlockK * kVStride];
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
+  __shared__ int s_seq;
 
-  const int b = blockIdx.z, h = blockIdx.y;
+  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
+  const int h = blockIdx.y;
   const int start = cu[b];
   const int n = cu[b + 1] - start;
   const int q0 = blockIdx.x * kBlockQ;
@@ -40,103 +53,142 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
   const int qw = q0 + 32 * wave;          // first query of this wave
   const bool wave_active = qw < n;
   const int qi = qw + c;                  // this lane's query (position inside the sequence)
-  const float cs = scale * kLog2e;        // scores are kept in base-2 units
-  const float slope2 = slopes[h] * kLog2e;
+  const int qblk = (q0 >> 5) + wave;      // index of this wave's block of 32 queries
+  const int ntiles = (n + kTileK - 1) / kTileK;
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+  const uint16_t* kh = k + h * kD + st_col;
+  const uint16_t* vh = v + h * kD + st_col;
 
-  // Q^T fragments (B operand of S^T = K Q^T): lane = query column, 8 consecutive d per k-step.
-  bf16x8 bq[4];
-  {
-    const bool ok = wave_active && qi < n;
-    const uint16_t* qrow = q + (ok ? tok_row(rows, start + qi) : 0) * qs + h * kD + 8 * g;
+  u32x4 tk[2], tv[2];
+  auto issue_tile = [&](int j0) {   // rows j0 + 32it + st_row of K and V -> registers (zeros past the end)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      u32x4 t = {0u, 0u, 0u, 0u};
-      if (ok) t = *reinterpret_cast<const u32x4*>(qrow + 16 * s);
-      bq[s] = as_bf16x8(t);
+    for (int it = 0; it < 2; ++it) {
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      const int j = j0 + 32 * it + st_row;
+      if (j < n) {
+        const int64_t gr = tok_row(rows, start + j);
+        tk[it] = *reinterpret_cast<const u32x4*>(kh + gr * ks);
+        tv[it] = *reinterpret_cast<const u32x4*>(vh + gr * vs);
+      }
     }
+  };
+  auto store_tile = [&](int buf) {
+    uint16_t* bk_ = smem + buf * kBufElems;
+    uint16_t* bv_ = bk_ + kTileK * kKStride;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      *reinterpret_cast<u32x4*>(&bk_[(32 * it + st_row) * kKStride + st_col]) = tk[it];
+      *reinterpret_cast<u32x4*>(&bv_[(32 * it + st_row) * kVStride + st_col]) = tv[it];
+    }
+  };
+
+  // ---- Q rows (coalesced) -> LDS -> Q^T fragments; the first K/V tile is already on its way
+  {
+    u32x4 tq[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tq[it] = u32x4{0u, 0u, 0u, 0u};
+      const int i = q0 + 32 * it + st_row;
+      if (i < n) tq[it] = *reinterpret_cast<const u32x4*>(q + tok_row(rows, start + i) * qs + h * kD + st_col);
+    }
+    issue_tile(0);
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+      *reinterpret_cast<u32x4*>(&smem[(32 * it + st_row) * kKStride + st_col]) = tq[it];
   }
+  __syncthreads();
+  bf16x8 bq[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) bq[s] = lds_read8(&smem[(32 * wave + c) * kKStride + 16 * s + 8 * g]);
+  __syncthreads();
+  store_tile(0);
+
+  const float cs = scale * kLog2e;
+  const float k1 = slopes[h] / scale;
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
 
   f32x16 oacc[2];
 #pragma unroll
   for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.f; oacc[1][i] = 0.f; }
-  float m_run = -INFINITY;   // running row maximum (base-2 units), identical in both half-waves
+  float m_run = -INFINITY;   // running maximum of the raw accumulator (dot product + bias/scale)
   float l_run = 0.f;         // running row sum, this half-wave's share
 
-  // per-lane pieces of the transposing V reads
-  const int tr_i = lane & 15, tr_q = lane >> 4;
-  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);          // + 4g: this half-wave's keys inside a group of 8
-  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
-
-  for (int j0 = 0; j0 < n; j0 += kBlockK) {
-    if (j0 > 0) __syncthreads();  // everyone is done with the previous tile
-    // ---- stage K, V rows j0..j0+127 of this head in LDS (zeros beyond the sequence end)
+  auto tile = [&](int j0, int jt, auto full_tag) {
+    constexpr bool kFull = decltype(full_tag)::value;
+    const uint16_t* bufK = smem + (jt & 1) * kBufElems;
+    const uint16_t* bufV = bufK + kTileK * kKStride;
+    const int rem = n - j0;
+    const int nblk = kFull ? 2 : (rem >= kTileK ? 2 : (rem + 31) >> 5);
+    float fi = (float)(qi - j0 - 4 * g);   // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
+    asm volatile("" : "+v"(fi));
+    f32x16 sacc[2];
+    if (kFull) {
+      const float sk = 2 * jt < qblk ? k1 : -k1;
+      const float a = -sk * fi;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      const int id = tid + 256 * it;
-      const int row = id >> 3, col = (id & 7) * 8;
-      u32x4 tk = {0u, 0u, 0u, 0u}, tv = {0u, 0u, 0u, 0u};
-      if (j0 + row < n) {
-        const int64_t gr = tok_row(rows, start + j0 + row);
-        tk = *reinterpret_cast<const u32x4*>(k + gr * ks + h * kD + col);
-        tv = *reinterpret_cast<const u32x4*>(v + gr * vs + h * kD + col);
+      for (int jb = 0; jb < 2; ++jb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
+      const uint16_t* krow = &bufK[c * kKStride + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sacc[0] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[0]);
+        sacc[1] = mfma32(lds_read8(krow + 32 * kKStride + 16 * s), bq[s], sacc[1]);
       }
-      *reinterpret_cast<u32x4*>(&sK[row * kKStride + col]) = tk;
-      *reinterpret_cast<u32x4*>(&sV[row * kVStride + col]) = tv;
-    }
-    __syncthreads();
-    if (!wave_active) continue;
-
-    const int rem = n - j0;                                  // keys left, > 0
-    const int nblk = rem >= kBlockK ? 4 : (rem + 31) >> 5;   // 32-key blocks in this tile
-
-    // ---- S^T = K Q^T
-    f32x16 sacc[4];
+    } else {
+      const int lim = rem - 4 * g;
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
+      for (int jb = 0; jb < 2; ++jb) {
+        if (jb < nblk) {
+          const int kblk = 2 * jt + jb;
+          if (kblk == qblk) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[jb][i] = 0.f;
-      if (jb < nblk) {
-        const uint16_t* krow = &sK[(jb * 32 + c) * kKStride + 8 * g];
+            for (int i = 0; i < 16; ++i)
+              sacc[jb][i] = -k1 * fabsf(fi - (float)(jb * 32 + 8 * (i >> 2) + (i & 3)));
+          } else {
+            const float sk = kblk < qblk ? k1 : -k1;
+            const float a = -sk * fi;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
+            for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
+          }
+          if (rem < kTileK && jb == nblk - 1 && (rem & 31)) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              sacc[jb][i] = (jb * 32 + 8 * (i >> 2) + (i & 3)) >= lim ? -INFINITY : sacc[jb][i];
+          }
+          const uint16_t* krow = &bufK[(jb * 32 + c) * kKStride + 8 * g];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
+        }
       }
     }
-
-    // ---- scale, bias, mask, tile maximum
-    const float fi = (float)(qi - j0 - 4 * g);
-    const int lim = rem - 4 * g;  // key (jb*32 + 8*(v/4) + v%4) is real iff that number < lim
     float mt = -INFINITY;
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      if (jb < nblk) {
+    for (int jb = 0; jb < 2; ++jb) {
+      if (kFull || jb < nblk) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
-          float x = fmaf(sacc[jb][i], cs, -slope2 * fabsf(fi - (float)cj));
-          if (rem < kBlockK && cj >= lim) x = -INFINITY;
-          sacc[jb][i] = x;
-          mt = fmaxf(mt, x);
-        }
+        for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[jb][i]);
       }
     }
     mt = max_both_halves(mt);
     const float m_new = fmaxf(m_run, mt);
-    if (j0 > 0) {
-      const float alpha = fast_exp2(m_run - m_new);
+    if (jt > 0 && __any(m_new > m_run)) {   // some query's maximum moved: rescale the running sums
+      const float alpha = fast_exp2((m_run - m_new) * cs);
       l_run *= alpha;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
     }
     m_run = m_new;
-
-    // ---- P^T = exp2(S^T - m), row sums, and O^T += V^T P^T
+    const float mc = m_new * cs;
     float lsum = 0.f;
 #pragma unroll
-    for (int jb = 0; jb < 4; ++jb) {
-      if (jb < nblk) {
+    for (int jb = 0; jb < 2; ++jb) {
+      if (kFull || jb < nblk) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const float p = fast_exp2(sacc[jb][i] - m_new);
+          const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
           sacc[jb][i] = p;
           lsum += p;
         }
@@ -145,24 +197,42 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
           const bf16x8 bp = pack8(sacc[jb][8 * kk + 0], sacc[jb][8 * kk + 1], sacc[jb][8 * kk + 2],
                                   sacc[jb][8 * kk + 3], sacc[jb][8 * kk + 4], sacc[jb][8 * kk + 5],
                                   sacc[jb][8 * kk + 6], sacc[jb][8 * kk + 7]);
-          // keys of this k-step: jb*32 + 16*kk + {4g..4g+3} and the same + 8
-          const uint16_t* vbase = &sV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
+          const uint16_t* vb = &bufV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
 #pragma unroll
           for (int db = 0; db < 2; ++db) {
-            const s16x4 lo = lds_read_tr4(vbase + 32 * db);
-            const s16x4 hi = lds_read_tr4(vbase + 32 * db + 8 * kVStride);
+            const s16x4 lo = lds_read_tr4(vb + 32 * db);
+            const s16x4 hi = lds_read_tr4(vb + 32 * db + 8 * kVStride);
             oacc[db] = mfma32(join_tr(lo, hi), bp, oacc[db]);
           }
         }
       }
     }
     l_run += lsum;
-  }
+  };
 
-  if (!wave_active || qi >= n) return;
-  const float l = sum_both_halves(l_run);   // NB: executed by both lanes of a pair (qi is the same)
+#pragma unroll 1
+  for (int jt = 0; jt < ntiles; ++jt) {
+    const int j0 = jt * kTileK;
+    __syncthreads();   // tile jt is complete in its buffer; the other buffer is no longer being read
+    if (jt + 1 < ntiles) issue_tile(j0 + kTileK);
+
+    if (wave_active) {
+      const int rem = n - j0;
+      // A full tile that lies entirely on one side of the diagonal (the bulk of a long sequence) runs
+      // as straight-line code; every other tile takes the general path with its uniform branches.
+      if (rem >= kTileK && (2 * jt + 1 < qblk || 2 * jt > qblk)) tile(j0, jt, std::true_type{});
+      else tile(j0, jt, std::false_type{});
+    }
+    if (jt + 1 < ntiles) store_tile((jt + 1) & 1);
+  }
+  __syncthreads();   // everyone is done with the K/V buffers: they now carry the output rows
+  if (!wave_active) return;
+
+  const float l = sum_both_halves(l_run);
   const float inv = 1.f / l;
-  uint16_t* orow = o + tok_row(rows, start + qi) * os + h * kD + 4 * g;
+  if (g == 0 && qi < n) lse[(int64_t)h * T + start + qi] = (m_run * cs + __log2f(l)) * kLn2;
+  // O^T accumulators -> 32 LDS rows private to this wave -> full 128-byte rows
+  uint16_t* slab = &smem[(32 * wave) * kKStride];
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -170,12 +240,17 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(
       u32x2 w;
       w[0] = pack_bf16(oacc[db][4 * r + 0] * inv, oacc[db][4 * r + 1] * inv);
       w[1] = pack_bf16(oacc[db][4 * r + 2] * inv, oacc[db][4 * r + 3] * inv);
-      *reinterpret_cast<u32x2*>(orow + 32 * db + 8 * r) = w;
+      *reinterpret_cast<u32x2*>(&slab[c * kKStride + 32 * db + 8 * r + 4 * g]) = w;
     }
   }
-  if (g == 0) lse[(int64_t)h * T + start + qi] = (m_run + __log2f(l)) * kLn2;
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = 8 * it + orow;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kKStride + ocol]);
+    if (qw + row < n) *reinterpret_cast<u32x4*>(o + tok_row(rows, start + qw + row) * os + h * kD + ocol) = w;
+  }
 }
-
 
 // ------------------------------------------------------------------------------------------------ n <= 128
 // Sequences of at most 128 tokens (the pretraining length of the paper): one K/V tile per
@@ -403,10 +478,10 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
                          (uint16_t*)o, os, lse, s.T, s.token_rows);
     return check_launch("attn_fwd_short_kernel");
   }
-  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+  hipLaunchKernelGGL(attn_fwd_tiled_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
                      (uint16_t*)o, os, lse, s.T, s.token_rows);
-  return check_launch("attn_fwd_mfma_kernel");
+  return check_launch("attn_fwd_tiled_kernel");
 }
 
 }  // namespace mb

@@ -30,6 +30,27 @@ __device__ __forceinline__ int64_t tok_row(const int32_t* __restrict__ rows, int
   return rows ? (int64_t)rows[t] : (int64_t)t;
 }
 
+// Longest-sequence-first work order for kernels whose workgroups run for a time that grows with the
+// sequence length: returns the sequence whose length has rank `rank` (0 = longest; ties by index), so
+// that the heaviest workgroups are dispatched first and short ones fill the tail.  Every thread of the
+// block must call it (it contains a barrier); `slot` is one int of LDS.  For B > kSortMaxB the order is
+// left as it is (the O(B) scan per thread would cost more than it saves).
+static constexpr int kSortMaxB = 512;
+__device__ __forceinline__ int seq_by_length_rank(const int32_t* __restrict__ cu, int B, int rank, int* slot) {
+  if (B > kSortMaxB) return rank;
+  for (int cand = threadIdx.x; cand < B; cand += blockDim.x) {
+    const int len = cu[cand + 1] - cu[cand];
+    int r = 0;
+    for (int other = 0; other < B; ++other) {
+      const int lo = cu[other + 1] - cu[other];
+      r += (lo > len || (lo == len && other < cand)) ? 1 : 0;
+    }
+    if (r == rank) *slot = cand;
+  }
+  __syncthreads();
+  return *slot;
+}
+
 // ---- launchers (each enqueues on `stream`, returns MB_OK or MB_ERR_HIP) ----
 mb_status launch_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
                              int32_t* indices, int32_t* meta, hipStream_t stream);
