@@ -17,8 +17,6 @@
 //           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.
 // Masking costs nothing: rows beyond the sequence end are staged as zeros and their lse as +inf
 // (P = 0); zero K/V rows make the products with out-of-range keys vanish.
-#include <type_traits>
-
 #include "common.h"
 #include "mfma_util.h"
 
@@ -170,17 +168,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 
   // One block of 32 queries (rows 32ib.. of the staged tile) against this wave's keys.  The S accumulator
   // is pre-loaded with bias/scale and the dP accumulator with -Delta_i, so that after the products
-  // P = exp2(acc_S * c - lse2_i) and dS = P * acc_dP.  kDiag: the block contains the diagonal.
-  auto qblock = [&](const uint16_t* sQ, const uint16_t* sG, const float* pl, const float* pd, int i0, int ib,
-                    auto diag_tag) {
-    constexpr bool kDiag = decltype(diag_tag)::value;
+  // P = exp2(acc_S * c - lse2_i) and dS = P * acc_dP.  Rows past the sequence end are staged as zeros
+  // with lse = +inf, which makes their P and dS exact zeros: no branch around the accumulating code.
+  auto qblock = [&](const uint16_t* sQ, const uint16_t* sG, const float* pl, const float* pd, int i0, int ib) {
     f32x16 sacc, pacc;
     const float d0 = (float)(i0 + 32 * ib) - fj;
-    if (kDiag) {
+    const int qb = (i0 >> 5) + ib;
+    if (qb == kblk) {   // block with the diagonal
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
-    } else {
-      const float sk = (i0 >> 5) + ib < kblk ? k1 : -k1;
+    } else {            // |i-j| = +-(ci - fj) on the whole block
+      const float sk = qb < kblk ? k1 : -k1;
       const float a = sk * d0;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
@@ -235,17 +233,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
       const uint16_t* sG = sQ + kHalf;
       const float* pl = sL[it & 1];
       const float* pd = sD[it & 1];
-      if (2 * it + 1 < kblk || 2 * it > kblk) {   // both query blocks off the diagonal: straight-line code
-        qblock(sQ, sG, pl, pd, i0, 0, std::false_type{});
-        if (i0 + 32 < n) qblock(sQ, sG, pl, pd, i0, 1, std::false_type{});
-      } else {
-        if (2 * it == kblk) qblock(sQ, sG, pl, pd, i0, 0, std::true_type{});
-        else qblock(sQ, sG, pl, pd, i0, 0, std::false_type{});
-        if (i0 + 32 < n) {
-          if (2 * it + 1 == kblk) qblock(sQ, sG, pl, pd, i0, 1, std::true_type{});
-          else qblock(sQ, sG, pl, pd, i0, 1, std::false_type{});
-        }
-      }
+      qblock(sQ, sG, pl, pd, i0, 0);
+      qblock(sQ, sG, pl, pd, i0, 1);
     }
     if (it + 1 < ntiles) store_tile((it + 1) & 1);
   }
@@ -368,19 +357,19 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
 
   // One block of 32 keys (rows 32jb.. of the staged tile) against this wave's queries, transposed
-  // orientation: S^T = K Q^T (+ bias/scale pre-loaded), dP^T = V dO^T (- Delta pre-loaded).
-  // kDiag: the block contains the diagonal.  kRagged: keys at or past `lim` do not exist.
-  auto kblock = [&](const uint16_t* sK, const uint16_t* sV, int j0, int jb, int lim, auto diag_tag, auto ragged_tag) {
-    constexpr bool kDiag = decltype(diag_tag)::value;
-    constexpr bool kRagged = decltype(ragged_tag)::value;
+  // orientation: S^T = K Q^T (+ bias/scale pre-loaded), dP^T = V dO^T (- Delta pre-loaded).  The code
+  // that accumulates dQ exists once with no branch around it; a ragged last tile only zeroes the dS of
+  // the keys that do not exist.
+  auto kblock = [&](const uint16_t* sK, const uint16_t* sV, int j0, int jb, int rem) {
     float fi = (float)(qi - j0 - 4 * g);   // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
     asm volatile("" : "+v"(fi));
     f32x16 sacc, pacc;
-    if (kDiag) {
+    const int kb = (j0 >> 5) + jb;
+    if (kb == qblk) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(fi - (float)(jb * 32 + 8 * (i >> 2) + (i & 3)));
     } else {
-      const float sk = (j0 >> 5) + jb < qblk ? k1 : -k1;
+      const float sk = kb < qblk ? k1 : -k1;
       const float a = -sk * fi;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
@@ -395,13 +384,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
       pacc = mfma32(lds_read8(vrow + 16 * s), bg[s], pacc);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float p = fast_exp2(fmaf(sacc[i], cs, nlse2));
-      float ds = p * pacc[i];
+    for (int i = 0; i < 16; ++i) pacc[i] = fast_exp2(fmaf(sacc[i], cs, nlse2)) * pacc[i];
+    if (rem < kTileS) {
       // a key past the sequence end has a zero K row, but its p may overflow (its score was never part
       // of lse): force the product with that zero row to be 0, not inf * 0
-      if (kRagged && 32 * jb + 8 * (i >> 2) + (i & 3) >= lim) ds = 0.f;
-      pacc[i] = ds;
+      const int lim = rem - 4 * g;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) pacc[i] = (32 * jb + 8 * (i >> 2) + (i & 3)) >= lim ? 0.f : pacc[i];
     }
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
@@ -427,18 +416,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
       const uint16_t* sK = smem + (jt & 1) * kBuf;
       const uint16_t* sV = sK + kHalf;
       const int rem = n - j0;
-      const int lim = rem - 4 * g;
-      if (rem >= kTileS && (2 * jt + 1 < qblk || 2 * jt > qblk)) {   // full tile off the diagonal
-        kblock(sK, sV, j0, 0, lim, std::false_type{}, std::false_type{});
-        kblock(sK, sV, j0, 1, lim, std::false_type{}, std::false_type{});
-      } else {
-        if (2 * jt == qblk) kblock(sK, sV, j0, 0, lim, std::true_type{}, std::true_type{});
-        else kblock(sK, sV, j0, 0, lim, std::false_type{}, std::true_type{});
-        if (rem > 32) {
-          if (2 * jt + 1 == qblk) kblock(sK, sV, j0, 1, lim, std::true_type{}, std::true_type{});
-          else kblock(sK, sV, j0, 1, lim, std::false_type{}, std::true_type{});
-        }
-      }
+      kblock(sK, sV, j0, 0, rem);
+      kblock(sK, sV, j0, 1, rem);
     }
     if (jt + 1 < ntiles) store_tile((jt + 1) & 1);
   }

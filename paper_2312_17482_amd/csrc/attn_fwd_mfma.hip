@@ -11,8 +11,6 @@
 //   * a query's row statistics (max, sum) are reductions over a lane's own registers plus one
 //     exchange with the partner lane l^32, and
 //   * the accumulator tile, rounded to bf16, is already the B operand of O^T += V^T P^T.
-#include <type_traits>
-
 #include "common.h"
 #include "mfma_util.h"
 
@@ -115,63 +113,48 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   float m_run = -INFINITY;   // running maximum of the raw accumulator (dot product + bias/scale)
   float l_run = 0.f;         // running row sum, this half-wave's share
 
-  auto tile = [&](int j0, int jt, auto full_tag) {
-    constexpr bool kFull = decltype(full_tag)::value;
+  // One tile of 64 keys.  The code that touches the running output exists once, with no branch
+  // around it: a ragged last tile is handled by pre-loading -inf for the keys that do not exist (their
+  // K rows are staged as zeros), so that only the accumulator pre-load has variants.
+  auto tile = [&](int j0, int jt) {
     const uint16_t* bufK = smem + (jt & 1) * kBufElems;
     const uint16_t* bufV = bufK + kTileK * kKStride;
     const int rem = n - j0;
-    const int nblk = kFull ? 2 : (rem >= kTileK ? 2 : (rem + 31) >> 5);
     float fi = (float)(qi - j0 - 4 * g);   // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
     asm volatile("" : "+v"(fi));
     f32x16 sacc[2];
-    if (kFull) {
-      const float sk = 2 * jt < qblk ? k1 : -k1;
-      const float a = -sk * fi;
+#pragma unroll
+    for (int jb = 0; jb < 2; ++jb) {
+      const int kblk = 2 * jt + jb;
+      if (kblk == qblk) {   // the block that holds the diagonal
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[jb][i] = -k1 * fabsf(fi - (float)(jb * 32 + 8 * (i >> 2) + (i & 3)));
+      } else {              // |i-j| = +-(fi - cj) on the whole block
+        const float sk = kblk < qblk ? k1 : -k1;
+        const float a = -sk * fi;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
+      }
+    }
+    if (rem < kTileK) {   // ragged end: keys >= n get -inf
+      const int lim = rem - 4 * g;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
-      const uint16_t* krow = &bufK[c * kKStride + 8 * g];
+        for (int i = 0; i < 16; ++i)
+          sacc[jb][i] = (jb * 32 + 8 * (i >> 2) + (i & 3)) >= lim ? -INFINITY : sacc[jb][i];
+    }
+    const uint16_t* krow = &bufK[c * kKStride + 8 * g];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        sacc[0] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[0]);
-        sacc[1] = mfma32(lds_read8(krow + 32 * kKStride + 16 * s), bq[s], sacc[1]);
-      }
-    } else {
-      const int lim = rem - 4 * g;
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
-        if (jb < nblk) {
-          const int kblk = 2 * jt + jb;
-          if (kblk == qblk) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              sacc[jb][i] = -k1 * fabsf(fi - (float)(jb * 32 + 8 * (i >> 2) + (i & 3)));
-          } else {
-            const float sk = kblk < qblk ? k1 : -k1;
-            const float a = -sk * fi;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
-          }
-          if (rem < kTileK && jb == nblk - 1 && (rem & 31)) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              sacc[jb][i] = (jb * 32 + 8 * (i >> 2) + (i & 3)) >= lim ? -INFINITY : sacc[jb][i];
-          }
-          const uint16_t* krow = &bufK[(jb * 32 + c) * kKStride + 8 * g];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) sacc[jb] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[jb]);
-        }
-      }
+    for (int s = 0; s < 4; ++s) {
+      sacc[0] = mfma32(lds_read8(krow + 16 * s), bq[s], sacc[0]);
+      sacc[1] = mfma32(lds_read8(krow + 32 * kKStride + 16 * s), bq[s], sacc[1]);
     }
     float mt = -INFINITY;
 #pragma unroll
-    for (int jb = 0; jb < 2; ++jb) {
-      if (kFull || jb < nblk) {
+    for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[jb][i]);
-      }
-    }
+      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[jb][i]);
     mt = max_both_halves(mt);
     const float m_new = fmaxf(m_run, mt);
     if (jt > 0 && __any(m_new > m_run)) {   // some query's maximum moved: rescale the running sums
@@ -185,25 +168,23 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     float lsum = 0.f;
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
-      if (kFull || jb < nblk) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
-          sacc[jb][i] = p;
-          lsum += p;
-        }
+      for (int i = 0; i < 16; ++i) {
+        const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
+        sacc[jb][i] = p;
+        lsum += p;
+      }
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          const bf16x8 bp = pack8(sacc[jb][8 * kk + 0], sacc[jb][8 * kk + 1], sacc[jb][8 * kk + 2],
-                                  sacc[jb][8 * kk + 3], sacc[jb][8 * kk + 4], sacc[jb][8 * kk + 5],
-                                  sacc[jb][8 * kk + 6], sacc[jb][8 * kk + 7]);
-          const uint16_t* vb = &bufV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bp = pack8(sacc[jb][8 * kk + 0], sacc[jb][8 * kk + 1], sacc[jb][8 * kk + 2],
+                                sacc[jb][8 * kk + 3], sacc[jb][8 * kk + 4], sacc[jb][8 * kk + 5],
+                                sacc[jb][8 * kk + 6], sacc[jb][8 * kk + 7]);
+        const uint16_t* vb = &bufV[(jb * 32 + 16 * kk + tr_row) * kVStride + tr_col];
 #pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            const s16x4 lo = lds_read_tr4(vb + 32 * db);
-            const s16x4 hi = lds_read_tr4(vb + 32 * db + 8 * kVStride);
-            oacc[db] = mfma32(join_tr(lo, hi), bp, oacc[db]);
-          }
+        for (int db = 0; db < 2; ++db) {
+          const s16x4 lo = lds_read_tr4(vb + 32 * db);
+          const s16x4 hi = lds_read_tr4(vb + 32 * db + 8 * kVStride);
+          oacc[db] = mfma32(join_tr(lo, hi), bp, oacc[db]);
         }
       }
     }
@@ -216,13 +197,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     __syncthreads();   // tile jt is complete in its buffer; the other buffer is no longer being read
     if (jt + 1 < ntiles) issue_tile(j0 + kTileK);
 
-    if (wave_active) {
-      const int rem = n - j0;
-      // A full tile that lies entirely on one side of the diagonal (the bulk of a long sequence) runs
-      // as straight-line code; every other tile takes the general path with its uniform branches.
-      if (rem >= kTileK && (2 * jt + 1 < qblk || 2 * jt > qblk)) tile(j0, jt, std::true_type{});
-      else tile(j0, jt, std::false_type{});
-    }
+    if (wave_active) tile(j0, jt);
     if (jt + 1 < ntiles) store_tile((jt + 1) & 1);
   }
   __syncthreads();   // everyone is done with the K/V buffers: they now carry the output rows
