@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also time each call of the path separately")
+    ap.add_argument("--full-length", action="store_true",
+                    help="every sequence gets max_len tokens (no padding): shows what the attention kernels reach "
+                         "without ragged tiles; not the benchmark configuration")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps, run a plain row copy of known size (128 MiB in, 128 MiB out, 5 launches of "
                          "gather_rows_kernel with 65536 rows) so that HBM counters of a profiler run can be scaled")
@@ -63,7 +66,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    batch = wl.make_batch(args.workload)
+    batch = wl.make_batch(args.workload, full_length=args.full_length)
     w = batch["workload"]
     B, L, H, D = w.B, w.L, w.H, w.D
     bf16 = w.dtype == "bf16"
@@ -180,8 +183,9 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": "%s: B=%d L=%d H=%d D=%d, T=%d real tokens, sum(len^2)=%d" % (
-            w.name, B, L, H, D, T_host, int((lengths.astype(np.int64) ** 2).sum()))},
+        "config": {"workload": "%s%s: B=%d L=%d H=%d D=%d, T=%d real tokens, sum(len^2)=%d" % (
+            w.name, " (all sequences full length)" if args.full_length else "", B, L, H, D, T_host,
+            int((lengths.astype(np.int64) ** 2).sum()))},
         "tokens_per_s": round(T_host / (ms_per_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 3),
         "attention_only": {

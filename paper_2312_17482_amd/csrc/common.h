@@ -63,7 +63,9 @@ mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* 
                               int row_bytes, void* padded, hipStream_t stream);
 
 // Generic ALU kernels: any D <= 128, fp32 or bf16 storage, fp32 arithmetic.
-static constexpr int kGenericMaxSeqlen = 16384;
+// Their backward keeps two score rows of max_seqlen floats plus two head vectors in LDS and must stay
+// within the 64 KB a kernel may use without opting in to more.
+static constexpr int kGenericMaxSeqlen = 8000;
 mb_status launch_attn_fwd_generic(const AttnShape& s, mb_dtype dt, const void* q, const void* k, const void* v,
                                   int64_t qs, int64_t ks, int64_t vs, void* o, int64_t os, float* lse,
                                   hipStream_t stream);

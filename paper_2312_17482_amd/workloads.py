@@ -81,7 +81,7 @@ def suffix_mask(lengths: np.ndarray, L: int) -> np.ndarray:
     return (np.arange(L, dtype=np.int32)[None, :] < np.asarray(lengths)[:, None]).astype(np.int32)
 
 
-def make_batch(name: str, seed_offset: int = 0, batch: int | None = None) -> dict:
+def make_batch(name: str, seed_offset: int = 0, batch: int | None = None, full_length: bool = False) -> dict:
     """Draw one batch of the named workload.
 
     Returns a dict with: workload, lengths [B], mask [B,L] int32, q/k/v/do
@@ -96,6 +96,8 @@ def make_batch(name: str, seed_offset: int = 0, batch: int | None = None) -> dic
             assert batch == 4
     rng = np.random.default_rng(BASE_SEED + w.cfg + 1000 * seed_offset)
     lengths = draw_lengths(w, rng)
+    if full_length:          # no padding at all: every sequence has max_len tokens (kernel capability runs)
+        lengths = np.full(w.B, w.L, dtype=np.int32)
     shape = (w.B, w.L, w.H, w.D)
     out = {"workload": w, "lengths": lengths, "mask": suffix_mask(lengths, w.L)}
     for key, std in (("q", w.qkv_std), ("k", w.qkv_std), ("v", w.qkv_std), ("do", 1.0)):

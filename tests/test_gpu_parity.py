@@ -319,3 +319,39 @@ def test_token_rows_mode_equals_explicit_unpad_and_pad(mb, bf16, D, L, holes):
     assert np.array_equal(got[:, :, 0], ref["dq"]) and np.array_equal(got[:, :, 1], ref["dk"])
     assert np.array_equal(got[:, :, 2], ref["dv"])
     assert np.array_equal(lse[:, :T].double().cpu().numpy(), ref["lse"]) and torch.all(lse[:, T:] == garbage)
+
+
+@pytest.mark.parametrize("scale", [-0.2, 0.0])
+def test_bf16_nonpositive_scale_takes_the_generic_kernels(mb, scale):
+    """The matrix-core kernels need scale > 0; any other finite scale must still be computed correctly."""
+    c = wl.random_attention_case(61, [70, 128, 5], 128, 2, 64, std=0.5, bf16=True)
+    slopes = mb.mb_alibi_slopes(2)
+    got = run_hip_path(mb, c, slopes, bf16=True, scale=scale)
+    ref = run_oracle(c, slopes.double().numpy(), scale=scale)
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 scale=%g" % scale)
+
+
+def test_all_sequences_empty_and_single_token_batches(mb):
+    """Capacity mode with no real token at all: nothing is written, nothing faults; then B = 1, n = 1."""
+    B, L, H, D = 3, 64, 2, 64
+    cap = B * L
+    mask = torch.zeros((B, L), dtype=torch.int32, device="cuda")
+    seqlens, cu, indices, meta = mb.mb_unpad_index(mask)
+    assert mb.mb_read_meta(meta) == (0, 0) and cu.tolist() == [0, 0, 0, 0]
+    x = torch.full((cap, 3, H, D), 2.0, dtype=torch.bfloat16, device="cuda")
+    o = torch.full((cap, H, D), 7.0, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((H, cap), 7.0, dtype=torch.float32, device="cuda")
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    for msl in (L, 1000):        # single-tile kernels, then the any-length kernels
+        mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu, msl, slopes, 0.125, out=o, lse=lse)
+        g = torch.full((cap, 3, H, D), 7.0, dtype=torch.bfloat16, device="cuda")
+        mb.mb_alibi_attn_bwd(o, x[:, 0], x[:, 1], x[:, 2], o, lse, cu, msl, slopes, 0.125, dq=g[:, 0], dk=g[:, 1], dv=g[:, 2])
+        torch.cuda.synchronize()
+        assert torch.all(o == 7.0) and torch.all(lse == 7.0) and torch.all(g == 7.0)
+    padded = mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L)
+    assert torch.all(padded == 0)
+    c = wl.random_attention_case(62, [1], 1, 1, 64, bf16=True)
+    got = run_hip_path(mb, c, mb.mb_alibi_slopes(1), bf16=True)
+    ref = run_oracle(c, mb.mb_alibi_slopes(1).double().numpy())
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "single token")
+    assert np.array_equal(got["o"][0, 0], c["v"][0, 0].astype(np.float64))      # O = V for a length-1 sequence
