@@ -21,12 +21,12 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # file (KiB per dispatch), each scaled by what the same counter reads for a plain row copy of known size
-# (--copy-calibration: FETCH_SIZE reads 66063.6 KiB for 131072 KiB copied -> factor 1.984; WRITE_SIZE reads
-# 131072.0 KiB -> factor 1.0).  Summaries: profiles/bert_base_attn_bwd_hbm_traffic.md.
-COPY_FACTOR_FETCH = 131072.0 / 66063.6
+# (--copy-calibration: FETCH_SIZE reads 66064.4 KiB for 131072 KiB copied -> factor 1.984; WRITE_SIZE reads
+# 131072.0 KiB -> factor 1.0).  Summaries: profiles/bert_base_attn_hbm_traffic.md.
+COPY_FACTOR_FETCH = 131072.0 / 66064.4
 COPY_FACTOR_WRITE = 1.0
 MEASURED_TRAFFIC_KIB = {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE) KiB per dispatch
-    "bert_base": {"attn_bwd_fused128_kernel": (101998.6, 121333.5), "attn_fwd_short_kernel": (60748.3, 41788.3)},
+    "bert_base": {"attn_bwd_fused128_kernel": (102001.1, 121333.5), "attn_fwd_short_kernel": (60747.7, 41788.3)},
 }
 
 
@@ -178,6 +178,21 @@ def main():
         bwd_kernel = "attn_bwd_fused128_kernel" if L <= 128 else "attn_bwd_dkv_kernel + attn_bwd_dq_kernel + attn_bwd_delta_kernel"
     else:
         bwd_kernel = "bwd_generic_row_kernel + bwd_generic_col_kernel"
+    roof_hbm = {
+        "kernel": bwd_kernel, "bound": "hbm",
+        "achieved": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+        "frac": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 5),
+        "algorithmic_bytes": bwd_bytes, "traffic": measured_traffic_bytes(w.name, bwd_kernel),
+    }
+    roof_mfma = {
+        "kernel": bwd_kernel, "bound": "mfma",
+        "achieved": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(f_bwd / (bwd_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 5),
+        "algorithmic_flops": f_bwd, "flop_per_byte": round(f_bwd / bwd_bytes, 1), "traffic": None,
+    }
+    hbm_binds = f_bwd / bwd_bytes < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    roof_primary, roof_other = (roof_hbm, roof_mfma) if hbm_binds else (roof_mfma, roof_hbm)
+
     out = {
         "metric": "ALiBi varlen attention fwd+bwd TFLOP/s (whole unpad->attention->pad step)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -196,20 +211,10 @@ def main():
             "fwd_bwd_tflops_no_recompute_convention": round((f_fwd + f_bwd) * 12.0 / 14.0 / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12, 2),
             "pct_of_bf16_mfma_peak": round(100.0 * (f_fwd + f_bwd) / ((fwd_ms + bwd_ms) * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 3),
         },
-        # Dominant kernel: the backward attention kernel.  At max_len 128 it moves 8 [T,H,D] tensors for
-        # 10*H*D*sum(len^2) flops (~73 flop/byte, machine balance ~312), so HBM is the roof that binds;
-        # the fraction of the matrix-core peak is given beside it.
-        "roofline": {
-            "kernel": bwd_kernel, "bound": "hbm",
-            "achieved": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-            "frac": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 5),
-            "algorithmic_bytes": bwd_bytes, "traffic": measured_traffic_bytes(w.name, bwd_kernel),
-        },
-        "roofline_mfma": {
-            "kernel": bwd_kernel, "bound": "mfma",
-            "achieved": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(f_bwd / (bwd_ms * 1e-3) * 1e-12 / PEAK_BF16_TFLOPS, 5),
-        },
+        # Dominant kernel: the backward attention.  `roofline` prices it against the roof that binds at this
+        # workload's arithmetic intensity (flops per algorithmic byte against the machine balance of
+        # 2500 TFLOP/s : 8 TB/s = 312 flop/byte); `roofline_other` gives the other roof.
+        "roofline": roof_primary, "roofline_other": roof_other,
         "gather_scatter_fused_into_attention": {
             "ms_per_step": round(ms_fused, 5), "value": round((f_fwd + f_bwd) / (ms_fused * 1e-3) * 1e-12, 3),
             "unit": "TFLOP/s", "tokens_per_s": round(T_host / (ms_fused * 1e-3), 1),
