@@ -484,17 +484,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
   const int kj = kw + c;
   const float cs = scale * kLog2e;
 
+  // Token r of the sequence sits at buffer row row_of(r).  With token_rows, rows listed in ascending
+  // order whose first and last differ by n - 1 are consecutive (the usual case: padding is a suffix of
+  // each batch row); then no per-token index load is needed.
+  int64_t row0 = start;
+  bool contig = true;
+  if (kRows) {
+    row0 = rows[start];
+    contig = rows[start + n - 1] - (int)row0 == n - 1;
+  }
+  auto row_of = [&](int r) -> int64_t { return contig ? row0 + r : (int64_t)rows[start + r]; };
+
   // ---- phase 0: coalesced row loads; thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
   {
-    // buffer row of the 4 tokens this thread moves, relative to `base` rows
+    // buffer row of the 4 tokens this thread moves
     int64_t gr[4];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      if (kRows) gr[it] = 32 * it + st_row < n ? (int64_t)rows[start + 32 * it + st_row] : 0;
-      else gr[it] = start + 32 * it + st_row;
-    }
+    for (int it = 0; it < 4; ++it) gr[it] = 32 * it + st_row < n ? row_of(32 * it + st_row) : 0;
     const uint16_t* kh = k + h * kD + st_col;
     const uint16_t* vh = v + h * kD + st_col;
     const uint16_t* qh = q + h * kD + st_col;
@@ -655,8 +663,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       const int row = 8 * it + orow;
       const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
       if (kw + row < n) {
-        const int64_t gr = kRows ? (int64_t)rows[start + kw + row] : (int64_t)(start + kw + row);
-        *reinterpret_cast<u32x4*>(oh + gr * stride) = w;
+        *reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride) = w;
       }
     }
   };

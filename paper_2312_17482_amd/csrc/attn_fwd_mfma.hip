@@ -268,17 +268,26 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   // ---- coalesced row loads: thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   u32x4 tq[4], tk[4], tv[4];
+  // Rows listed in ascending order whose first and last differ by n - 1 are consecutive (the usual
+  // case: padding is a suffix of each batch row); then no per-token index load is needed.
+  int row0 = 0;
+  bool contig = true;
   if (kRows) {
-    int gr[4];
+    row0 = rows[start];
+    contig = rows[start + n - 1] - row0 == n - 1;
+  }
+  auto row_of = [&](int r) -> int64_t { return contig ? (int64_t)(row0 + r) : (int64_t)rows[start + r]; };
+  if (kRows) {
+    int64_t gr[4];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) gr[it] = 32 * it + st_row < n ? rows[start + 32 * it + st_row] : 0;
+    for (int it = 0; it < 4; ++it) gr[it] = 32 * it + st_row < n ? row_of(32 * it + st_row) : 0;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(q + (int64_t)gr[it] * qs + h * kD + st_col);
-        tk[it] = *reinterpret_cast<const u32x4*>(k + (int64_t)gr[it] * ks + h * kD + st_col);
-        tv[it] = *reinterpret_cast<const u32x4*>(v + (int64_t)gr[it] * vs + h * kD + st_col);
+        tq[it] = *reinterpret_cast<const u32x4*>(q + gr[it] * qs + h * kD + st_col);
+        tk[it] = *reinterpret_cast<const u32x4*>(k + gr[it] * ks + h * kD + st_col);
+        tv[it] = *reinterpret_cast<const u32x4*>(v + gr[it] * vs + h * kD + st_col);
       }
     }
   } else {
@@ -430,7 +439,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     const int row = 8 * it + orow;
     const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kKStride + ocol]);
     if (32 * wave + row < n) {
-      if (kRows) *reinterpret_cast<u32x4*>(oh + (int64_t)rows[start + 32 * wave + row] * os + ocol) = w;
+      if (kRows) *reinterpret_cast<u32x4*>(oh + row_of(32 * wave + row) * os + ocol) = w;
       else *reinterpret_cast<u32x4*>(oh + (uint32_t)row * (uint32_t)os + ocol) = w;
     }
   }
