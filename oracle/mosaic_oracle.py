@@ -172,3 +172,48 @@ def attention_bwd(dO, Q, K, V, mask, slopes, scale):
             dQ[b, :, h] = scale * (dS @ k)
             dK[b, :, h] = scale * (dS.T @ q)
     return dQ, dK, dV
+
+
+# --------------------------------------------------------------------------- Add & LayerNorm in bf16 storage
+# Paper, "Low Precision LayerNorm" paragraph and the "Add & Norm" boxes of Figure 1A: LayerNorm reads and
+# writes bfloat16 instead of float32 (it is bandwidth-bound, so halving the bytes is the point).  The
+# paper fixes storage, not the internal arithmetic; the reading taken is: the residual sum s = x + r is a
+# stored bf16 tensor (rounded to nearest even), the statistics and the normalisation are evaluated from
+# that stored s in full precision, and y is rounded once when stored.  This oracle keeps everything after
+# the rounding of s in float64 and leaves the final rounding of y to the comparison tolerance.
+def _round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding of float64 values to bfloat16 (returned as float64)."""
+    f32 = np.asarray(x, dtype=np.float64).astype(np.float32)          # exact for sums of two bf16 values
+    u = f32.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def add_layernorm_fwd(x, r, gamma, beta, eps, round_sum=True):
+    """s = x + r (r may be None), y = (s - mean) / sqrt(var + eps) * gamma + beta over the last axis,
+    var = mean((s - mean)^2).  x, r: [T, W]; gamma, beta: [W].  Returns (y, s, mean [T], rstd [T])."""
+    s = np.asarray(x, dtype=np.float64)
+    if r is not None:
+        s = s + np.asarray(r, dtype=np.float64)
+        if round_sum:
+            s = _round_to_bf16(s)
+    mean = s.mean(axis=1)
+    var = ((s - mean[:, None]) ** 2).mean(axis=1)
+    rstd = 1.0 / np.sqrt(var + eps)
+    y = (s - mean[:, None]) * rstd[:, None] * np.asarray(gamma, dtype=np.float64) + np.asarray(beta, dtype=np.float64)
+    return y, s, mean, rstd
+
+
+def add_layernorm_bwd(dy, s, gamma, eps):
+    """Gradient of sum(y * dy) for add_layernorm_fwd with respect to s (= to x and to r), gamma and beta.
+    xhat = (s - mean) rstd, g = dy * gamma:  ds = rstd * (g - mean(g) - xhat * mean(g * xhat)),
+    dgamma = sum_t dy * xhat, dbeta = sum_t dy."""
+    dy = np.asarray(dy, dtype=np.float64)
+    s = np.asarray(s, dtype=np.float64)
+    mean = s.mean(axis=1, keepdims=True)
+    var = ((s - mean) ** 2).mean(axis=1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xhat = (s - mean) * rstd
+    g = dy * np.asarray(gamma, dtype=np.float64)
+    ds = rstd * (g - g.mean(axis=1, keepdims=True) - xhat * (g * xhat).mean(axis=1, keepdims=True))
+    return ds, (dy * xhat).sum(axis=0), dy.sum(axis=0)

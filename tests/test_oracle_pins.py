@@ -348,3 +348,71 @@ def test_workload_recipes():
     # round-to-nearest-even at the bf16 boundary
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20], dtype=np.float32)
     assert np.array_equal(wl.round_to_bf16(x), np.array([1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7], dtype=np.float32))
+
+
+# ---------------------------------------------------------------- Add & LayerNorm (bf16 storage)
+def _ln_case(seed, T, W):
+    rng = np.random.default_rng(seed)
+    x = wl.round_to_bf16(rng.standard_normal((T, W), dtype=np.float32) * 1.5)
+    r = wl.round_to_bf16(rng.standard_normal((T, W), dtype=np.float32) + 0.3)
+    gamma = wl.round_to_bf16(1.0 + 0.2 * rng.standard_normal(W, dtype=np.float32))
+    beta = wl.round_to_bf16(0.1 * rng.standard_normal(W, dtype=np.float32))
+    dy = wl.round_to_bf16(rng.standard_normal((T, W), dtype=np.float32))
+    return x, r, gamma, beta, dy
+
+
+def test_layernorm_forward_pins():
+    x, r, gamma, beta, _ = _ln_case(1, 7, 48)
+    y, s, mean, rstd = orc.add_layernorm_fwd(x, r, np.ones(48), np.zeros(48), 0.0)
+    # normalised rows have mean 0 and variance 1
+    assert np.allclose(y.mean(1), 0, atol=1e-13) and np.allclose((y ** 2).mean(1), 1, atol=1e-12)
+    # the stored sum is the exact sum rounded to bf16 (the generator's rounding is an independent routine)
+    assert np.array_equal(s, wl.round_to_bf16((x.astype(np.float64) + r).astype(np.float32)).astype(np.float64))
+    # affine invariance (eps = 0): LN(a s + b) = LN(s) for a > 0; sign flip for a < 0
+    y1, *_ = orc.add_layernorm_fwd(3.0 * s + 5.0, None, gamma, beta, 0.0)
+    y0, *_ = orc.add_layernorm_fwd(s, None, gamma, beta, 0.0)
+    ym, *_ = orc.add_layernorm_fwd(-2.0 * s, None, gamma, np.zeros(48), 0.0)
+    yz, *_ = orc.add_layernorm_fwd(s, None, gamma, np.zeros(48), 0.0)
+    assert np.allclose(y1, y0, atol=1e-12) and np.allclose(ym, -yz, atol=1e-12)
+    # library routine, float64, with eps
+    t = torch.nn.functional.layer_norm(torch.tensor(s), (48,), torch.tensor(gamma.astype(np.float64)),
+                                       torch.tensor(beta.astype(np.float64)), 1e-5)
+    y2, _, mean2, rstd2 = orc.add_layernorm_fwd(s, None, gamma, beta, 1e-5)
+    assert np.allclose(t.numpy(), y2, atol=1e-13)
+    assert np.allclose(mean2, s.mean(1)) and np.allclose(rstd2, 1 / np.sqrt(s.var(1) + 1e-5))
+    # a constant row: variance 0, output = beta (eps keeps it finite)
+    yc, *_ = orc.add_layernorm_fwd(np.full((1, 48), 2.5), None, gamma, beta, 1e-5)
+    assert np.allclose(yc[0], beta, atol=1e-12)
+
+
+def test_layernorm_backward_pins():
+    x, r, gamma, beta, dy = _ln_case(2, 6, 40)
+    eps = 1e-5
+    _, s, _, _ = orc.add_layernorm_fwd(x, r, gamma, beta, eps)
+    ds, dg, db = orc.add_layernorm_bwd(dy, s, gamma, eps)
+    # library autograd, float64
+    ts = torch.tensor(s, requires_grad=True)
+    tg = torch.tensor(gamma.astype(np.float64), requires_grad=True)
+    tb = torch.tensor(beta.astype(np.float64), requires_grad=True)
+    torch.nn.functional.layer_norm(ts, (40,), tg, tb, eps).backward(torch.tensor(dy.astype(np.float64)))
+    assert np.allclose(ts.grad.numpy(), ds, atol=1e-12) and np.allclose(tg.grad.numpy(), dg, atol=1e-12)
+    assert np.allclose(tb.grad.numpy(), db, atol=1e-12)
+    # central differences along random directions
+    rng = np.random.default_rng(3)
+    loss = lambda s_, g_, b_: float(np.sum(orc.add_layernorm_fwd(s_, None, g_, b_, eps)[0] * dy))
+    g64, b64 = gamma.astype(np.float64), beta.astype(np.float64)
+    for _ in range(3):
+        U = rng.standard_normal(s.shape)
+        fd = (loss(s + 1e-6 * U, g64, b64) - loss(s - 1e-6 * U, g64, b64)) / 2e-6
+        assert abs(fd - np.sum(ds * U)) <= 1e-6 * max(1.0, abs(fd))
+        u = rng.standard_normal(40)
+        fd = (loss(s, g64 + 1e-6 * u, b64) - loss(s, g64 - 1e-6 * u, b64)) / 2e-6
+        assert abs(fd - np.sum(dg * u)) <= 1e-6 * max(1.0, abs(fd))
+    # the normalisation removes the mean and the scale of each row: ds is orthogonal to 1 and to xhat
+    xhat = (s - s.mean(1, keepdims=True)) / np.sqrt(s.var(1, keepdims=True) + eps)
+    assert np.allclose(ds.sum(1), 0, atol=1e-12)
+    assert np.allclose((ds * xhat).sum(1) / 40, 0, atol=1e-4)      # exactly 0 only for eps = 0
+    ds0, _, _ = orc.add_layernorm_bwd(dy, s, gamma, 0.0)
+    xhat0 = (s - s.mean(1, keepdims=True)) / np.sqrt(s.var(1, keepdims=True))
+    assert np.allclose((ds0 * xhat0).sum(1), 0, atol=1e-11)
+    assert np.allclose(db, dy.sum(0))
