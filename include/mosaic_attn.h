@@ -172,6 +172,37 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
                             size_t workspace_bytes, const int32_t* token_rows, void* stream);
 
+/*
+ * Add & LayerNorm over packed token rows with 2-byte storage ("Low Precision LayerNorm" paragraph of the
+ * paper: LayerNorm is bandwidth-bound, so it reads and writes bfloat16; "Add & Norm" in Figure 1A):
+ *   s = x + r  (stored, rounded once to the storage type),   mean, var over the W elements of a row,
+ *   y = (s - mean) / sqrt(var + eps) * gamma + beta.         Statistics and normalisation are fp32.
+ *   x, r      dev, [T_cap, W], read; r may be NULL (then s = x and `s` is not written and may be NULL).
+ *   gamma, beta  dev, [W], same type as x, read.
+ *   T_cap, meta_dev  rows [0, T) are processed, T = min(meta_dev[0], T_cap), or T_cap if meta_dev is NULL.
+ *   W         row width; W * element_size a multiple of 16 bytes and at most 4096 bytes.
+ *   y, s      dev, [T_cap, W], written.     mean, rstd  dev, [T_cap] float, written (needed by the backward).
+ */
+MB_API mb_status mb_add_layernorm_fwd(const void* x, const void* r, const void* gamma, const void* beta, int T_cap,
+                                      const int32_t* meta_dev, int W, float eps, mb_dtype dt, void* y, void* s,
+                                      float* mean, float* rstd, void* stream);
+
+/* Bytes of device workspace mb_add_layernorm_bwd needs for rows of W elements (0 on invalid W). */
+MB_API size_t mb_add_layernorm_bwd_workspace_bytes(int W);
+
+/*
+ * Gradient of sum(y * dy) for the call above:  xhat = (s - mean) rstd,  g = dy * gamma,
+ *   ds = rstd * (g - mean(g) - xhat * mean(g * xhat))   (the gradient of both x and r),
+ *   dgamma = sum_t dy * xhat,   dbeta = sum_t dy         (fp32, summed in a fixed order: deterministic).
+ *   dy, s  dev, [T_cap, W], read (s = the stored sum of the forward, or x when r was NULL).
+ *   ds     dev, [T_cap, W], written.   dgamma, dbeta  dev, [W] float, written.
+ *   workspace  dev, at least mb_add_layernorm_bwd_workspace_bytes(W) bytes, scratch.
+ */
+MB_API mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma, const float* mean,
+                                      const float* rstd, int T_cap, const int32_t* meta_dev, int W, mb_dtype dt,
+                                      void* ds, float* dgamma, float* dbeta, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

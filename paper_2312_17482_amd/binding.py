@@ -23,7 +23,8 @@ MB_F32, MB_BF16 = 0, 1
 
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
            "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
-           "mb_alibi_attn_bwd")
+           "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
+           "mb_add_layernorm_bwd")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -50,6 +51,16 @@ _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
                                    + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p])
+
+
+_lib.mb_add_layernorm_fwd.restype = c_int
+_lib.mb_add_layernorm_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_float, c_int,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.mb_add_layernorm_bwd_workspace_bytes.restype = c_size_t
+_lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
+_lib.mb_add_layernorm_bwd.restype = c_int
+_lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
 
 
 class MosaicAttnError(RuntimeError):
@@ -196,3 +207,39 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
                                   _ptr(workspace), workspace.numel(), _ptr(token_rows), _stream()))
     return dq, dk, dv
+
+
+def mb_add_layernorm_fwd(x, r, gamma, beta, eps: float, T_cap=None, meta=None, y=None, s=None, mean=None, rstd=None):
+    """x, r: [rows, W] (r may be None).  Returns (y, s, mean, rstd); s is x itself when r is None."""
+    assert x.dim() == 2 and x.is_contiguous()
+    rows, W = x.shape
+    T_cap = rows if T_cap is None else T_cap
+    y = torch.empty_like(x) if y is None else y
+    if r is not None and s is None:
+        s = torch.empty_like(x)
+    mean = torch.empty(rows, dtype=torch.float32, device=x.device) if mean is None else mean
+    rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if rstd is None else rstd
+    _check(_lib.mb_add_layernorm_fwd(_ptr(x), _ptr(r), _ptr(gamma), _ptr(beta), T_cap, _ptr(meta), W, float(eps),
+                                     _dtype_code(x), _ptr(y), _ptr(s) if r is not None else None, _ptr(mean),
+                                     _ptr(rstd), _stream()))
+    return y, (s if r is not None else x), mean, rstd
+
+
+def mb_add_layernorm_bwd_workspace_bytes(W: int) -> int:
+    return int(_lib.mb_add_layernorm_bwd_workspace_bytes(W))
+
+
+def mb_add_layernorm_bwd(dy, s, gamma, mean, rstd, T_cap=None, meta=None, ds=None, dgamma=None, dbeta=None,
+                         workspace=None):
+    """Returns (ds [rows, W], dgamma [W] float32, dbeta [W] float32)."""
+    rows, W = s.shape
+    T_cap = rows if T_cap is None else T_cap
+    ds = torch.empty_like(s) if ds is None else ds
+    dgamma = torch.empty(W, dtype=torch.float32, device=s.device) if dgamma is None else dgamma
+    dbeta = torch.empty(W, dtype=torch.float32, device=s.device) if dbeta is None else dbeta
+    if workspace is None:
+        workspace = torch.empty(mb_add_layernorm_bwd_workspace_bytes(W), dtype=torch.uint8, device=s.device)
+    _check(_lib.mb_add_layernorm_bwd(_ptr(dy), _ptr(s), _ptr(gamma), _ptr(mean), _ptr(rstd), T_cap, _ptr(meta), W,
+                                     _dtype_code(s), _ptr(ds), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
+                                     workspace.numel(), _stream()))
+    return ds, dgamma, dbeta

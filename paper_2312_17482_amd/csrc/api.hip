@@ -187,6 +187,66 @@ mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta
                              (hipStream_t)stream);
 }
 
+static mb_status check_ln(int T_cap, int W, mb_dtype dt) {
+  mb_status st = check_rows(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE((int64_t)W * (int64_t)elem_size(dt) <= 4096, MB_ERR_UNSUPPORTED, "rows of %d elements exceed 4096 bytes",
+             W);
+  return MB_OK;
+}
+
+mb_status mb_add_layernorm_fwd(const void* x, const void* r, const void* gamma, const void* beta, int T_cap,
+                               const int32_t* meta_dev, int W, float eps, mb_dtype dt, void* y, void* s, float* mean,
+                               float* rstd, void* stream) {
+  clear_error();
+  mb_status st = check_ln(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  MB_REQUIRE(std::isfinite(eps) && eps >= 0.f, MB_ERR_INVALID_ARG, "eps must be finite and non-negative");
+  if (T_cap == 0) return MB_OK;
+  MB_CHECK_PTR(x);
+  MB_CHECK_PTR(gamma);
+  MB_CHECK_PTR(beta);
+  MB_CHECK_PTR(y);
+  MB_CHECK_PTR(mean);
+  MB_CHECK_PTR(rstd);
+  if (r != nullptr) {
+    MB_REQUIRE(aligned16(r), MB_ERR_INVALID_ARG, "r is not 16-byte aligned");
+    MB_CHECK_PTR(s);
+  }
+  return launch_add_layernorm_fwd(dt, x, r, gamma, beta, T_cap, meta_dev, W, eps, y, s, mean, rstd,
+                                  (hipStream_t)stream);
+}
+
+size_t mb_add_layernorm_bwd_workspace_bytes(int W) {
+  if (W <= 0) return 0;
+  return (size_t)kLayerNormMaxParts * 2 * (size_t)W * sizeof(float);
+}
+
+mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma, const float* mean, const float* rstd,
+                               int T_cap, const int32_t* meta_dev, int W, mb_dtype dt, void* ds, float* dgamma,
+                               float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  mb_status st = check_ln(T_cap, W, dt);
+  if (st != MB_OK) return st;
+  MB_CHECK_PTR(dgamma);
+  MB_CHECK_PTR(dbeta);
+  const size_t need = mb_add_layernorm_bwd_workspace_bytes(W);
+  MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
+             "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+  if (T_cap > 0) {
+    MB_CHECK_PTR(dy);
+    MB_CHECK_PTR(s);
+    MB_CHECK_PTR(gamma);
+    MB_CHECK_PTR(mean);
+    MB_CHECK_PTR(rstd);
+    MB_CHECK_PTR(ds);
+  }
+  // with T_cap == 0 only the column-sum pass runs, over zero partial rows: dgamma and dbeta become zeros
+  return launch_add_layernorm_bwd(dt, dy, s, gamma, mean, rstd, T_cap, meta_dev, W, ds, dgamma, dbeta,
+                                  (float*)workspace, (hipStream_t)stream);
+}
+
 mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,

@@ -62,6 +62,15 @@ mb_status launch_scatter_rows(const void* packed, const int32_t* indices, int T_
 mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta, int rows_padded,
                               int row_bytes, void* padded, hipStream_t stream);
 
+// Add & LayerNorm.  The backward writes one partial row of column sums per workgroup, at most this many.
+static constexpr int kLayerNormMaxParts = 1024;
+mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
+                                   int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
+                                   float* rstd, hipStream_t stream);
+mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, const void* gamma, const float* mean,
+                                   const float* rstd, int T_cap, const int32_t* meta, int W, void* ds, float* dgamma,
+                                   float* dbeta, float* part, hipStream_t stream);
+
 // Generic ALU kernels: any D <= 128, fp32 or bf16 storage, fp32 arithmetic.
 // Their backward keeps two score rows of max_seqlen floats plus two head vectors in LDS and must stay
 // within the 64 KB a kernel may use without opting in to more.

@@ -1,0 +1,249 @@
+// Add & LayerNorm over packed token rows with bf16 (or fp32) storage: the "Low Precision LayerNorm" of the
+// paper (LayerNorm reads and writes 2-byte elements because it is bandwidth-bound) together with the
+// residual add in front of it ("Add & Norm" in Figure 1A).  Statistics and normalisation are fp32.
+//
+//   forward :  s = x + r (stored, rounded once),  y = (s - mean) * rstd * gamma + beta
+//   backward:  xhat = (s - mean) rstd, g = dy * gamma,
+//              ds = rstd * (g - mean(g) - xhat * mean(g * xhat)),  dgamma = sum_t dy * xhat,  dbeta = sum_t dy
+//
+// One wave per row, 16-byte pieces, every tensor crosses HBM once.  The column sums of the backward are
+// reduced in a fixed order (per-workgroup partials in the workspace, then one pass over them): no atomics.
+#include "common.h"
+
+namespace mb {
+namespace {
+
+constexpr int kMaxPieces = 4;        // 16-byte pieces per lane: rows up to 64 * 4 * 16 bytes = 4 KB
+constexpr int kLnThreads = 256;
+constexpr int kLnWaves = kLnThreads / 64;
+
+__device__ __forceinline__ float wsum(float x) {
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+template <typename E> struct Piece;      // one 16-byte piece of a row <-> floats
+template <> struct Piece<uint16_t> {
+  static constexpr int kN = 8;
+  static __device__ __forceinline__ void load(const uint16_t* p, float* f) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ uint32_t rne(float x) {   // float -> bf16 bits, nearest even; NaN stays NaN
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+  }
+  static __device__ __forceinline__ void store(uint16_t* p, const float* f) {
+    uint4 u;
+    u.x = rne(f[0]) | (rne(f[1]) << 16);
+    u.y = rne(f[2]) | (rne(f[3]) << 16);
+    u.z = rne(f[4]) | (rne(f[5]) << 16);
+    u.w = rne(f[6]) | (rne(f[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = u;
+  }
+  static __device__ __forceinline__ float round(float x) { return __uint_as_float(rne(x) << 16); }
+};
+template <> struct Piece<float> {
+  static constexpr int kN = 4;
+  static __device__ __forceinline__ void load(const float* p, float* f) {
+    const float4 u = *reinterpret_cast<const float4*>(p);
+    f[0] = u.x; f[1] = u.y; f[2] = u.z; f[3] = u.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* f) {
+    *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+  }
+  static __device__ __forceinline__ float round(float x) { return x; }
+};
+
+template <typename E>
+__global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
+    const E* __restrict__ x, const E* __restrict__ r, const E* __restrict__ gamma, const E* __restrict__ beta,
+    int T_cap, const int32_t* __restrict__ meta, int W, float eps, E* __restrict__ y, E* __restrict__ s,
+    float* __restrict__ mean, float* __restrict__ rstd) {
+  constexpr int N = Piece<E>::kN;
+  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  const int row = blockIdx.x * kLnWaves + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int lane = threadIdx.x & 63;
+  const int pieces = W / N;
+  const E* xr = x + (size_t)row * W;
+  float v[kMaxPieces][N];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxPieces; ++c) {
+    const int pc = lane + 64 * c;
+    if (pc < pieces) {
+      Piece<E>::load(xr + pc * N, v[c]);
+      if (r) {
+        float t[N];
+        Piece<E>::load(r + (size_t)row * W + pc * N, t);
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[c][i] = Piece<E>::round(v[c][i] + t[i]);   // the stored sum is what is normalised
+        Piece<E>::store(s + (size_t)row * W + pc * N, v[c]);
+      }
+#pragma unroll
+      for (int i = 0; i < N; ++i) sum += v[c][i];
+    }
+  }
+  const float mu = wsum(sum) / (float)W;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < kMaxPieces; ++c) {
+    if (lane + 64 * c < pieces) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) { const float d = v[c][i] - mu; sq = fmaf(d, d, sq); }
+    }
+  }
+  const float rs = rsqrtf(wsum(sq) / (float)W + eps);
+#pragma unroll
+  for (int c = 0; c < kMaxPieces; ++c) {
+    const int pc = lane + 64 * c;
+    if (pc < pieces) {
+      float g[N], b[N], out[N];
+      Piece<E>::load(gamma + pc * N, g);
+      Piece<E>::load(beta + pc * N, b);
+#pragma unroll
+      for (int i = 0; i < N; ++i) out[i] = fmaf((v[c][i] - mu) * rs, g[i], b[i]);
+      Piece<E>::store(y + (size_t)row * W + pc * N, out);
+    }
+  }
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+
+// Each wave walks rows  blockIdx*4 + wave, + 4*gridDim, ...: writes ds and keeps per-lane partial column
+// sums; the four waves of a block are then added in a fixed order and written to part[block][2][W].
+template <typename E>
+__global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
+    const E* __restrict__ dy, const E* __restrict__ s, const E* __restrict__ gamma, const float* __restrict__ mean,
+    const float* __restrict__ rstd, int T_cap, const int32_t* __restrict__ meta, int W, E* __restrict__ ds,
+    float* __restrict__ part) {
+  constexpr int N = Piece<E>::kN;
+  extern __shared__ float lds[];   // [kLnWaves][2][W]
+  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int pieces = W / N;
+  float g[kMaxPieces][N], ag[kMaxPieces][N], ab[kMaxPieces][N];
+#pragma unroll
+  for (int c = 0; c < kMaxPieces; ++c) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) { g[c][i] = 0.f; ag[c][i] = 0.f; ab[c][i] = 0.f; }
+    if (lane + 64 * c < pieces) Piece<E>::load(gamma + (lane + 64 * c) * N, g[c]);
+  }
+  for (int row = blockIdx.x * kLnWaves + wave; row < T; row += gridDim.x * kLnWaves) {
+    const float mu = mean[row], rs = rstd[row];
+    float xh[kMaxPieces][N], gy[kMaxPieces][N];
+    float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxPieces; ++c) {
+      const int pc = lane + 64 * c;
+      if (pc < pieces) {
+        float d[N];
+        Piece<E>::load(s + (size_t)row * W + pc * N, xh[c]);
+        Piece<E>::load(dy + (size_t)row * W + pc * N, d);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+          xh[c][i] = (xh[c][i] - mu) * rs;
+          ag[c][i] = fmaf(d[i], xh[c][i], ag[c][i]);
+          ab[c][i] += d[i];
+          gy[c][i] = d[i] * g[c][i];
+          c1 += gy[c][i];
+          c2 = fmaf(gy[c][i], xh[c][i], c2);
+        }
+      }
+    }
+    c1 = wsum(c1) / (float)W;
+    c2 = wsum(c2) / (float)W;
+#pragma unroll
+    for (int c = 0; c < kMaxPieces; ++c) {
+      const int pc = lane + 64 * c;
+      if (pc < pieces) {
+        float out[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) out[i] = rs * (gy[c][i] - c1 - xh[c][i] * c2);
+        Piece<E>::store(ds + (size_t)row * W + pc * N, out);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kMaxPieces; ++c) {
+    const int pc = lane + 64 * c;
+    if (pc < pieces) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        lds[(wave * 2 + 0) * W + pc * N + i] = ag[c][i];
+        lds[(wave * 2 + 1) * W + pc * N + i] = ab[c][i];
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 2 * W; idx += kLnThreads) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kLnWaves; ++w) t += lds[w * 2 * W + idx];
+    part[(size_t)blockIdx.x * 2 * W + idx] = t;
+  }
+}
+
+// dgamma[w], dbeta[w] = sum over the `nparts` partial rows, in order.
+__global__ __launch_bounds__(256) void add_layernorm_colsum_kernel(const float* __restrict__ part, int nparts, int W,
+                                                                   float* __restrict__ dgamma,
+                                                                   float* __restrict__ dbeta) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= 2 * W) return;
+  float t = 0.f;
+  for (int p = 0; p < nparts; ++p) t += part[(size_t)p * 2 * W + idx];
+  if (idx < W) dgamma[idx] = t; else dbeta[idx - W] = t;
+}
+
+int bwd_blocks(int T_cap) { return max(1, min((T_cap + kLnWaves - 1) / kLnWaves, kLayerNormMaxParts)); }
+
+}  // namespace
+
+mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
+                                   int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
+                                   float* rstd, hipStream_t stream) {
+  const int blocks = (T_cap + kLnWaves - 1) / kLnWaves;
+  if (dt == MB_BF16)
+    hipLaunchKernelGGL(add_layernorm_fwd_kernel<uint16_t>, dim3(blocks), dim3(kLnThreads), 0, stream,
+                       (const uint16_t*)x, (const uint16_t*)r, (const uint16_t*)gamma, (const uint16_t*)beta, T_cap,
+                       meta, W, eps, (uint16_t*)y, (uint16_t*)s, mean, rstd);
+  else
+    hipLaunchKernelGGL(add_layernorm_fwd_kernel<float>, dim3(blocks), dim3(kLnThreads), 0, stream, (const float*)x,
+                       (const float*)r, (const float*)gamma, (const float*)beta, T_cap, meta, W, eps, (float*)y,
+                       (float*)s, mean, rstd);
+  return check_launch("add_layernorm_fwd_kernel");
+}
+
+mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, const void* gamma, const float* mean,
+                                   const float* rstd, int T_cap, const int32_t* meta, int W, void* ds, float* dgamma,
+                                   float* dbeta, float* part, hipStream_t stream) {
+  if (T_cap == 0) {
+    // no rows (dy, s, gamma, ... may be NULL): nothing to read, the column sums are zeros
+    hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 255) / 256), dim3(256), 0, stream, part, 0, W,
+                       dgamma, dbeta);
+    return check_launch("add_layernorm_colsum_kernel");
+  }
+  const int blocks = bwd_blocks(T_cap);
+  const size_t smem = sizeof(float) * kLnWaves * 2 * (size_t)W;
+  if (dt == MB_BF16)
+    hipLaunchKernelGGL(add_layernorm_bwd_kernel<uint16_t>, dim3(blocks), dim3(kLnThreads), smem, stream,
+                       (const uint16_t*)dy, (const uint16_t*)s, (const uint16_t*)gamma, mean, rstd, T_cap, meta, W,
+                       (uint16_t*)ds, part);
+  else
+    hipLaunchKernelGGL(add_layernorm_bwd_kernel<float>, dim3(blocks), dim3(kLnThreads), smem, stream,
+                       (const float*)dy, (const float*)s, (const float*)gamma, mean, rstd, T_cap, meta, W,
+                       (float*)ds, part);
+  mb_status st = check_launch("add_layernorm_bwd_kernel");
+  if (st != MB_OK) return st;
+  hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 255) / 256), dim3(256), 0, stream, part, blocks, W,
+                     dgamma, dbeta);
+  return check_launch("add_layernorm_colsum_kernel");
+}
+
+}  // namespace mb
