@@ -223,6 +223,7 @@ def main():
         "paper_context": "MosaicBERT-Base: 79.6 GLUE in 1.13 h on 8xA100-80GB (end-to-end pretraining; not comparable)",
     }
 
+    out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev)}
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
     if args.copy_calibration:
@@ -238,6 +239,43 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(batch, f_fwd + f_bwd)
     print(json.dumps(out))
+
+
+def time_layernorm(mb, T, W, tdt, dev):
+    """Add & LayerNorm on the packed tokens of the same batch ([T, H*D]), outside the timed step: 50 launches
+    between two events.  Algorithmic bytes: forward reads x, r and writes s, y (4 T W e); backward reads dy, s
+    and writes ds (3 T W e)."""
+    import torch
+    e = 2 if tdt == torch.bfloat16 else 4
+    x = torch.randn(T, W, device=dev).to(tdt)
+    r = torch.randn(T, W, device=dev).to(tdt)
+    gamma = torch.ones(W, device=dev).to(tdt)
+    beta = torch.zeros(W, device=dev).to(tdt)
+    dy = torch.randn(T, W, device=dev).to(tdt)
+    y, s, ds = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    mean = torch.empty(T, dtype=torch.float32, device=dev)
+    rstd = torch.empty(T, dtype=torch.float32, device=dev)
+    dg = torch.empty(W, dtype=torch.float32, device=dev)
+    db = torch.empty(W, dtype=torch.float32, device=dev)
+    ws = torch.empty(mb.mb_add_layernorm_bwd_workspace_bytes(W), dtype=torch.uint8, device=dev)
+    fwd = lambda: mb.mb_add_layernorm_fwd(x, r, gamma, beta, 1e-5, y=y, s=s, mean=mean, rstd=rstd)
+    bwd = lambda: mb.mb_add_layernorm_bwd(dy, s, gamma, mean, rstd, ds=ds, dgamma=dg, dbeta=db, workspace=ws)
+    res = {}
+    for name, fn, nbytes in (("fwd", fwd, 4 * T * W * e + 8 * T), ("bwd", bwd, 3 * T * W * e + 8 * T)):
+        for _ in range(5):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(50):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / 50
+        res[name + "_us"] = round(us, 2)
+        res[name + "_GBs"] = round(nbytes / (us * 1e-6) * 1e-9, 1)
+        res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
+    res["shape"] = "T=%d W=%d" % (T, W)
+    return res
 
 
 def time_each_call(mb, lib, env):

@@ -13,7 +13,7 @@
 namespace mb {
 namespace {
 
-constexpr int kMaxPieces = 4;        // 16-byte pieces per lane: rows up to 64 * 4 * 16 bytes = 4 KB
+// 16-byte pieces per lane: 2 for rows up to 2 KB (fewer registers, four waves per SIMD), else 4 (up to 4 KB)
 constexpr int kLnThreads = 256;
 constexpr int kLnWaves = kLnThreads / 64;
 
@@ -61,7 +61,7 @@ template <> struct Piece<float> {
   static __device__ __forceinline__ float round(float x) { return x; }
 };
 
-template <typename E>
+template <typename E, int kMaxPieces>
 __global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
     const E* __restrict__ x, const E* __restrict__ r, const E* __restrict__ gamma, const E* __restrict__ beta,
     int T_cap, const int32_t* __restrict__ meta, int W, float eps, E* __restrict__ y, E* __restrict__ s,
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
 
 // Each wave walks rows  blockIdx*4 + wave, + 4*gridDim, ...: writes ds and keeps per-lane partial column
 // sums; the four waves of a block are then added in a fixed order and written to part[block][2][W].
-template <typename E>
+template <typename E, int kMaxPieces>
 __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
     const E* __restrict__ dy, const E* __restrict__ s, const E* __restrict__ gamma, const float* __restrict__ mean,
     const float* __restrict__ rstd, int T_cap, const int32_t* __restrict__ meta, int W, E* __restrict__ ds,
@@ -190,15 +190,30 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
   }
 }
 
-// dgamma[w], dbeta[w] = sum over the `nparts` partial rows, in order.
+// dgamma[w], dbeta[w] = sum over the `nparts` partial rows.  64 columns per block; the partial rows are
+// dealt to 4 waves x 8 independent accumulators (so that the loads overlap) and combined in a fixed order.
 __global__ __launch_bounds__(256) void add_layernorm_colsum_kernel(const float* __restrict__ part, int nparts, int W,
                                                                    float* __restrict__ dgamma,
                                                                    float* __restrict__ dbeta) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  if (idx >= 2 * W) return;
-  float t = 0.f;
-  for (int p = 0; p < nparts; ++p) t += part[(size_t)p * 2 * W + idx];
-  if (idx < W) dgamma[idx] = t; else dbeta[idx - W] = t;
+  __shared__ float red[4][64];
+  const int idx = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int slice = threadIdx.x >> 6;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (idx < 2 * W) {
+    int p = slice;
+    for (; p + 28 < nparts; p += 32) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc[u] += part[(size_t)(p + 4 * u) * 2 * W + idx];
+    }
+    for (; p < nparts; p += 4) acc[0] += part[(size_t)p * 2 * W + idx];
+  }
+  red[slice][threadIdx.x & 63] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+  __syncthreads();
+  if (slice == 0 && idx < 2 * W) {
+    const int l = threadIdx.x & 63;
+    const float t = (red[0][l] + red[1][l]) + (red[2][l] + red[3][l]);
+    if (idx < W) dgamma[idx] = t; else dbeta[idx - W] = t;
+  }
 }
 
 int bwd_blocks(int T_cap) { return max(1, min((T_cap + kLnWaves - 1) / kLnWaves, kLayerNormMaxParts)); }
@@ -209,14 +224,13 @@ mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, co
                                    int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
                                    float* rstd, hipStream_t stream) {
   const int blocks = (T_cap + kLnWaves - 1) / kLnWaves;
-  if (dt == MB_BF16)
-    hipLaunchKernelGGL(add_layernorm_fwd_kernel<uint16_t>, dim3(blocks), dim3(kLnThreads), 0, stream,
-                       (const uint16_t*)x, (const uint16_t*)r, (const uint16_t*)gamma, (const uint16_t*)beta, T_cap,
-                       meta, W, eps, (uint16_t*)y, (uint16_t*)s, mean, rstd);
-  else
-    hipLaunchKernelGGL(add_layernorm_fwd_kernel<float>, dim3(blocks), dim3(kLnThreads), 0, stream, (const float*)x,
-                       (const float*)r, (const float*)gamma, (const float*)beta, T_cap, meta, W, eps, (float*)y,
-                       (float*)s, mean, rstd);
+  const bool small = (size_t)W * elem_size(dt) <= 2048;
+#define MB_LN_FWD(E, P)                                                                                           \
+  hipLaunchKernelGGL((add_layernorm_fwd_kernel<E, P>), dim3(blocks), dim3(kLnThreads), 0, stream, (const E*)x,    \
+                     (const E*)r, (const E*)gamma, (const E*)beta, T_cap, meta, W, eps, (E*)y, (E*)s, mean, rstd)
+  if (dt == MB_BF16) { if (small) MB_LN_FWD(uint16_t, 2); else MB_LN_FWD(uint16_t, 4); }
+  else { if (small) MB_LN_FWD(float, 2); else MB_LN_FWD(float, 4); }
+#undef MB_LN_FWD
   return check_launch("add_layernorm_fwd_kernel");
 }
 
@@ -225,23 +239,22 @@ mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, c
                                    float* dbeta, float* part, hipStream_t stream) {
   if (T_cap == 0) {
     // no rows (dy, s, gamma, ... may be NULL): nothing to read, the column sums are zeros
-    hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 255) / 256), dim3(256), 0, stream, part, 0, W,
+    hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(256), 0, stream, part, 0, W,
                        dgamma, dbeta);
     return check_launch("add_layernorm_colsum_kernel");
   }
   const int blocks = bwd_blocks(T_cap);
   const size_t smem = sizeof(float) * kLnWaves * 2 * (size_t)W;
-  if (dt == MB_BF16)
-    hipLaunchKernelGGL(add_layernorm_bwd_kernel<uint16_t>, dim3(blocks), dim3(kLnThreads), smem, stream,
-                       (const uint16_t*)dy, (const uint16_t*)s, (const uint16_t*)gamma, mean, rstd, T_cap, meta, W,
-                       (uint16_t*)ds, part);
-  else
-    hipLaunchKernelGGL(add_layernorm_bwd_kernel<float>, dim3(blocks), dim3(kLnThreads), smem, stream,
-                       (const float*)dy, (const float*)s, (const float*)gamma, mean, rstd, T_cap, meta, W,
-                       (float*)ds, part);
+  const bool small = (size_t)W * elem_size(dt) <= 2048;
+#define MB_LN_BWD(E, P)                                                                                          \
+  hipLaunchKernelGGL((add_layernorm_bwd_kernel<E, P>), dim3(blocks), dim3(kLnThreads), smem, stream,             \
+                     (const E*)dy, (const E*)s, (const E*)gamma, mean, rstd, T_cap, meta, W, (E*)ds, part)
+  if (dt == MB_BF16) { if (small) MB_LN_BWD(uint16_t, 2); else MB_LN_BWD(uint16_t, 4); }
+  else { if (small) MB_LN_BWD(float, 2); else MB_LN_BWD(float, 4); }
+#undef MB_LN_BWD
   mb_status st = check_launch("add_layernorm_bwd_kernel");
   if (st != MB_OK) return st;
-  hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 255) / 256), dim3(256), 0, stream, part, blocks, W,
+  hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(256), 0, stream, part, blocks, W,
                      dgamma, dbeta);
   return check_launch("add_layernorm_colsum_kernel");
 }
