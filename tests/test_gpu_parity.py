@@ -56,7 +56,9 @@ def compare_attention(got, ref, mask, tol, lse_tol, label, abs_floor_ulps=False)
 
 # ------------------------------------------------------------------ index maps and row copies
 @pytest.mark.parametrize("seed,B,L,p", [(0, 4, 32, 0.5), (1, 7, 300, 0.9), (2, 1, 1, 1.0), (3, 5, 16, 0.0),
-                                        (4, 3, 1000, 1.0), (5, 300, 17, 0.3), (6, 2, 5000, 0.01), (7, 256, 128, 0.8)])
+                                        (4, 3, 1000, 1.0), (5, 300, 17, 0.3), (6, 2, 5000, 0.01), (7, 256, 128, 0.8),
+                                        (8, 600, 128, 0.7), (9, 3, 40000, 0.5), (10, 512, 128, 1.0), (11, 1, 65536, 0.9),
+                                        (12, 65536, 1, 0.5), (13, 1000, 65, 0.2), (14, 1, 63, 1.0)])
 def test_unpad_index_arbitrary_masks_bit_exact(mb, seed, B, L, p):
     print("unpad_index seed=%d B=%d L=%d p=%.2f" % (seed, B, L, p), flush=True)
     mask = wl.random_mask(seed, B, L, p)
