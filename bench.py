@@ -223,7 +223,8 @@ def main():
         "paper_context": "MosaicBERT-Base: 79.6 GLUE in 1.13 h on 8xA100-80GB (end-to-end pretraining; not comparable)",
     }
 
-    out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev)}
+    out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev),
+                        "padded_attention_comparison": time_padded_vs_varlen(mb, locals())}
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
     if args.copy_calibration:
@@ -275,6 +276,40 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_GBs"] = round(nbytes / (us * 1e-6) * 1e-9, 1)
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
     res["shape"] = "T=%d W=%d" % (T, W)
+    return res
+
+
+def time_padded_vs_varlen(mb, g):
+    """What removing padding saves in attention itself: the same kernels on the same batch, once over the
+    packed real tokens (cu_seqlens from the mask) and once over every position of the padded [B, L] batch
+    as the paper's own code ran attention (all B*L positions computed).  Forward + backward, 30 launches
+    each between two events; outputs of the padded run are scratch."""
+    import torch
+    B, L, H, D, cap = g["B"], g["L"], g["H"], g["D"], g["cap"]
+    dev = g["dev"]
+    qkv_packed, dout_packed = g["qkv"], g["dout"]
+    qkv_full = g["qkv_padded"].view(cap, 3, H, D)
+    do_full = g["do_padded"].view(cap, H, D)
+    cu_full = torch.arange(0, cap + 1, L, dtype=torch.int32, device=dev)
+    o, lse, dqkv, ws = g["o"], g["lse"], g["dqkv"], g["workspace"]
+    slopes, scale = g["slopes"], g["scale"]
+    res = {}
+    for name, x, do_, cu_ in (("varlen", qkv_packed, dout_packed, g["cu"]), ("padded", qkv_full, do_full, cu_full)):
+        def run():
+            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu_, L, slopes, scale, out=o, lse=lse)
+            mb.mb_alibi_attn_bwd(do_, x[:, 0], x[:, 1], x[:, 2], o, lse, cu_, L, slopes, scale,
+                                 dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
+        for _ in range(3):
+            run()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(30):
+            run()
+        b.record()
+        torch.cuda.synchronize()
+        res[name + "_fwd_bwd_us"] = round(a.elapsed_time(b) * 1e3 / 30, 2)
+    res["speedup_from_unpadding"] = round(res["padded_fwd_bwd_us"] / res["varlen_fwd_bwd_us"], 3)
+    res["fraction_of_positions_that_are_real"] = round(g["T_host"] / cap, 4)
     return res
 
 

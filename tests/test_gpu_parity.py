@@ -357,3 +357,32 @@ def test_all_sequences_empty_and_single_token_batches(mb):
     ref = run_oracle(c, mb.mb_alibi_slopes(1).double().numpy())
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "single token")
     assert np.array_equal(got["o"][0, 0], c["v"][0, 0].astype(np.float64))      # O = V for a length-1 sequence
+
+
+def test_bf16_tile_boundary_lengths(mb):
+    """Lengths on both sides of every tile boundary of the any-length kernels (32, 64, 128) in one batch."""
+    lengths = [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 2, 0]
+    c = wl.random_attention_case(71, lengths, 257, 2, 64, std=0.7, bf16=True, v_std=0.5)
+    slopes = mb.mb_alibi_slopes(2)
+    got = run_hip_path(mb, c, slopes, bf16=True)
+    check_index_maps(got, c["mask"])
+    ref = run_oracle(c, slopes.double().numpy())
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 tile boundaries")
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_bf16_random_shapes(mb, seed):
+    """Random batch sizes, head counts and lengths (both kernel families, chosen by the longest sequence)."""
+    rng = np.random.default_rng(1000 + seed)
+    B = int(rng.integers(1, 9))
+    H = int(rng.integers(1, 5))
+    L = int(rng.choice([48, 128, 200, 400]))
+    lengths = [int(x) for x in rng.integers(0, L + 1, size=B)]
+    lengths[int(rng.integers(B))] = L
+    print("random shapes seed=%d B=%d H=%d L=%d lengths=%s" % (seed, B, H, L, lengths), flush=True)
+    c = wl.random_attention_case(2000 + seed, lengths, L, H, 64, std=0.6, bf16=True, v_std=0.6)
+    slopes = mb.mb_alibi_slopes(H)
+    got = run_hip_path(mb, c, slopes, bf16=True)
+    check_index_maps(got, c["mask"])
+    ref = run_oracle(c, slopes.double().numpy())
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 random %d" % seed)
