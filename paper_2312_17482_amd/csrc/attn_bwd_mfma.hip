@@ -508,21 +508,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const uint16_t* qh = q + h * kD + st_col;
     const uint16_t* gh = dout + h * kD + st_col;
     const uint16_t* oh = o + h * kD + st_col;
+    // The backward is the last reader of the forward's activations: non-temporal loads keep this one-pass
+    // stream from evicting what other kernels of the step still need from L2 / the memory-side cache.
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
-        tk[it] = *reinterpret_cast<const u32x4*>(kh + gr[it] * ks);
-        tv[it] = *reinterpret_cast<const u32x4*>(vh + gr[it] * vs);
+        tk[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kh + gr[it] * ks));
+        tv[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + gr[it] * vs));
       }
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
       if (32 * it + st_row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(qh + gr[it] * qs);
-        tg[it] = *reinterpret_cast<const u32x4*>(gh + gr[it] * dos);
-        to[it] = *reinterpret_cast<const u32x4*>(oh + gr[it] * os);
+        tq[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qh + gr[it] * qs));
+        tg[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gh + gr[it] * dos));
+        to[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(oh + gr[it] * os));
       }
     }
   }

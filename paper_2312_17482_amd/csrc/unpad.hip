@@ -100,13 +100,24 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(const int32_t* __rest
 constexpr int kRowsPerBlock = 8;
 constexpr int kLanesPerRow = kThreads / kRowsPerBlock;  // 32
 
+// Cache policy: a row that is read here for the last time (the padded input of a gather, the packed
+// input of a scatter) is loaded non-temporally, and the padded output of a scatter is stored
+// non-temporally, so that these one-pass streams do not push the packed activations, which the attention
+// kernels are about to read, out of the L2 and the memory-side cache.  A gather's packed output is stored
+// normally for the same reason.
+typedef unsigned int nt_u32x4 __attribute__((ext_vector_type(4)));
+template <bool kNtLoad, bool kNtStore>
 __device__ __forceinline__ void copy_row(const uint4* __restrict__ src, uint4* __restrict__ dst, int units, int c) {
+  const nt_u32x4* s = reinterpret_cast<const nt_u32x4*>(src);
+  nt_u32x4* d = reinterpret_cast<nt_u32x4*>(dst);
+  auto ld = [&](int u) { return kNtLoad ? __builtin_nontemporal_load(s + u) : s[u]; };
+  auto st = [&](int u, nt_u32x4 v) { if (kNtStore) __builtin_nontemporal_store(v, d + u); else d[u] = v; };
   int u = c;
   for (; u + 3 * kLanesPerRow < units; u += 4 * kLanesPerRow) {
-    const uint4 a0 = src[u], a1 = src[u + kLanesPerRow], a2 = src[u + 2 * kLanesPerRow], a3 = src[u + 3 * kLanesPerRow];
-    dst[u] = a0; dst[u + kLanesPerRow] = a1; dst[u + 2 * kLanesPerRow] = a2; dst[u + 3 * kLanesPerRow] = a3;
+    const nt_u32x4 a0 = ld(u), a1 = ld(u + kLanesPerRow), a2 = ld(u + 2 * kLanesPerRow), a3 = ld(u + 3 * kLanesPerRow);
+    st(u, a0); st(u + kLanesPerRow, a1); st(u + 2 * kLanesPerRow, a2); st(u + 3 * kLanesPerRow, a3);
   }
-  for (; u < units; u += kLanesPerRow) dst[u] = src[u];
+  for (; u < units; u += kLanesPerRow) st(u, ld(u));
 }
 
 __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const uint4* __restrict__ padded,
@@ -117,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const uint4* __re
   const int t = blockIdx.x * kRowsPerBlock + (threadIdx.x / kLanesPerRow);
   if (t >= T) return;
   const int p = indices[t];
-  copy_row(padded + (size_t)p * units, packed + (size_t)t * units, units, threadIdx.x % kLanesPerRow);
+  copy_row<true, false>(padded + (size_t)p * units, packed + (size_t)t * units, units, threadIdx.x % kLanesPerRow);
 }
 
 // Block = 8 consecutive padded rows p0..p0+7.  Wave 0 finds t0 = first t with indices[t] >= p0 by a
@@ -159,10 +170,10 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
   uint4* dst = padded + (size_t)p * units;
   const int lane = threadIdx.x % kLanesPerRow;
   if (kept) {
-    if (kCopy) copy_row(packed + (size_t)(t0 + c) * units, dst, units, lane);
+    if (kCopy) copy_row<true, true>(packed + (size_t)(t0 + c) * units, dst, units, lane);
   } else {
-    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-    for (int u = lane; u < units; u += kLanesPerRow) dst[u] = z;
+    const nt_u32x4 z = {0u, 0u, 0u, 0u};
+    for (int u = lane; u < units; u += kLanesPerRow) __builtin_nontemporal_store(z, reinterpret_cast<nt_u32x4*>(dst) + u);
   }
 }
 
