@@ -2,8 +2,8 @@
 """Benchmark of the hot path on one MI355X: unpad -> ALiBi varlen attention fwd+bwd -> pad.
 
 One "step" is one pass of the whole path over one synthetic batch that is already resident in HBM:
-  mb_unpad_index(mask) -> mb_read_meta -> mb_unpad(fused QKV), mb_unpad(dO) -> mb_alibi_attn_fwd ->
-  mb_alibi_attn_bwd -> mb_pad(O), mb_pad(dQKV).
+  mb_unpad_index(mask) -> mb_unpad(fused QKV) -> mb_alibi_attn_fwd -> mb_unpad(dO) -> mb_alibi_attn_bwd ->
+  mb_pad(O), mb_pad(dQKV)    (no host synchronisation inside a step).
 Prints ONE JSON line.  `value` = attention flops on real tokens (14*H*D*sum(len^2): forward QK^T and PV,
 backward's five products including the recomputation of the scores) divided by the whole step time.
 """
@@ -112,24 +112,28 @@ def main():
         assert st == 0, mb.mb_last_error()
         # No host round trip: the token count stays on the device (meta); the attention calls get the
         # capacity B*L as their row count and L as the bound of the sequence length.
+        # (the upstream gradient is unpadded right before the backward needs it, so that the packed Q/K/V
+        # just written are still in cache when the forward reads them)
         mb.mb_unpad(qkv_padded, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
-        mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
         if record is not None:
             record[0].record(stream)
         mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse)
         if record is not None:
             record[1].record(stream)
+        mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
+        if record is not None:
+            record[2].record(stream)
         mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
                              dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace)
         if record is not None:
-            record[2].record(stream)
+            record[3].record(stream)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
         mb.mb_pad(dqkv.view(cap, 3 * H * D), indices, cap, meta, B, L, out=dqkv_padded)
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(events[i])
@@ -139,7 +143,7 @@ def main():
     assert T == T_host and max_seqlen == int(lengths.max())
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    bwd_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    bwd_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
 
     # The same path with the gather and the scatter done inside the attention kernels' own row loads and
     # stores (token_rows = indices): no packed copies at all; padding rows of the outputs are zeroed.

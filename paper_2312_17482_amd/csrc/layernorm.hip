@@ -191,27 +191,32 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
 }
 
 // dgamma[w], dbeta[w] = sum over the `nparts` partial rows.  64 columns per block; the partial rows are
-// dealt to 4 waves x 8 independent accumulators (so that the loads overlap) and combined in a fixed order.
-__global__ __launch_bounds__(256) void add_layernorm_colsum_kernel(const float* __restrict__ part, int nparts, int W,
-                                                                   float* __restrict__ dgamma,
-                                                                   float* __restrict__ dbeta) {
-  __shared__ float red[4][64];
-  const int idx = blockIdx.x * 64 + (threadIdx.x & 63);
+// dealt to 16 waves x 4 independent accumulators (so that many loads are in flight) and combined in a
+// fixed order.
+constexpr int kColsumSlices = 16;
+__global__ __launch_bounds__(64 * kColsumSlices) void add_layernorm_colsum_kernel(const float* __restrict__ part,
+                                                                                int nparts, int W,
+                                                                                float* __restrict__ dgamma,
+                                                                                float* __restrict__ dbeta) {
+  __shared__ float red[kColsumSlices][64];
+  const int l = threadIdx.x & 63;
+  const int idx = blockIdx.x * 64 + l;
   const int slice = threadIdx.x >> 6;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (idx < 2 * W) {
     int p = slice;
-    for (; p + 28 < nparts; p += 32) {
+    for (; p + 3 * kColsumSlices < nparts; p += 4 * kColsumSlices) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc[u] += part[(size_t)(p + 4 * u) * 2 * W + idx];
+      for (int u = 0; u < 4; ++u) acc[u] += part[(size_t)(p + kColsumSlices * u) * 2 * W + idx];
     }
-    for (; p < nparts; p += 4) acc[0] += part[(size_t)p * 2 * W + idx];
+    for (; p < nparts; p += kColsumSlices) acc[0] += part[(size_t)p * 2 * W + idx];
   }
-  red[slice][threadIdx.x & 63] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
+  red[slice][l] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   __syncthreads();
   if (slice == 0 && idx < 2 * W) {
-    const int l = threadIdx.x & 63;
-    const float t = (red[0][l] + red[1][l]) + (red[2][l] + red[3][l]);
+    float t = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < kColsumSlices; ++sl) t += red[sl][l];
     if (idx < W) dgamma[idx] = t; else dbeta[idx - W] = t;
   }
 }
@@ -239,7 +244,7 @@ mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, c
                                    float* dbeta, float* part, hipStream_t stream) {
   if (T_cap == 0) {
     // no rows (dy, s, gamma, ... may be NULL): nothing to read, the column sums are zeros
-    hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(256), 0, stream, part, 0, W,
+    hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(64 * kColsumSlices), 0, stream, part, 0, W,
                        dgamma, dbeta);
     return check_launch("add_layernorm_colsum_kernel");
   }
@@ -254,7 +259,7 @@ mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, c
 #undef MB_LN_BWD
   mb_status st = check_launch("add_layernorm_bwd_kernel");
   if (st != MB_OK) return st;
-  hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(256), 0, stream, part, blocks, W,
+  hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(64 * kColsumSlices), 0, stream, part, blocks, W,
                      dgamma, dbeta);
   return check_launch("add_layernorm_colsum_kernel");
 }
