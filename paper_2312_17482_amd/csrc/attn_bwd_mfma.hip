@@ -665,7 +665,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       const int row = 8 * it + orow;
       const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
       if (kw + row < n) {
-        *reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride) = w;
+        // written into the padded layout these rows are final results of the step: stream them out
+        if (kRows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride));
+        else *reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride) = w;
       }
     }
   };

@@ -133,8 +133,6 @@ __global__ __launch_bounds__(kThreads) void gather_rows_kernel(const uint4* __re
 
 // Block = 8 consecutive padded rows p0..p0+7.  Wave 0 finds t0 = first t with indices[t] >= p0 by a
 // 64-ary search (indices ascending); the rows of the block that are kept then sit at t0, t0+1, ...
-// kCopy = false: only the rows that are not listed in `indices` are written (with zeros).
-template <bool kCopy>
 __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __restrict__ packed,
                                                                 const int32_t* __restrict__ indices, int T_cap,
                                                                 const int32_t* __restrict__ meta, int rows_padded,
@@ -170,10 +168,54 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
   uint4* dst = padded + (size_t)p * units;
   const int lane = threadIdx.x % kLanesPerRow;
   if (kept) {
-    if (kCopy) copy_row<true, true>(packed + (size_t)(t0 + c) * units, dst, units, lane);
+    copy_row<true, true>(packed + (size_t)(t0 + c) * units, dst, units, lane);
   } else {
     const nt_u32x4 z = {0u, 0u, 0u, 0u};
     for (int u = lane; u < units; u += kLanesPerRow) __builtin_nontemporal_store(z, reinterpret_cast<nt_u32x4*>(dst) + u);
+  }
+}
+
+// Zero the rows that `indices` does not list.  Block = 64 consecutive padded rows p0..p0+63: wave 0 finds
+// t0 = first t with indices[t] >= p0 (64-ary search) and marks the listed rows of the block, which are
+// indices[t0], indices[t0+1], ... below p0+64; everything unmarked is padding and is zero-filled.
+constexpr int kZeroRows = 64;
+__global__ __launch_bounds__(kThreads) void zero_padding_kernel(const int32_t* __restrict__ indices, int T_cap,
+                                                                const int32_t* __restrict__ meta, int rows_padded,
+                                                                int units, uint4* __restrict__ padded) {
+  __shared__ int s_listed[kZeroRows];
+  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  const int p0 = blockIdx.x * kZeroRows;
+  if (threadIdx.x < kZeroRows) s_listed[threadIdx.x] = 0;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    int lo = 0, hi = T;
+    while (hi - lo > 64) {
+      const int step = (hi - lo + 63) / 64;
+      const long long pos = (long long)lo + (long long)(lane + 1) * step - 1;
+      const bool less = (pos < hi) && (indices[pos] < p0);
+      const int c = __popcll(__ballot(less));
+      const long long nlo = (long long)lo + (long long)c * step;
+      const long long nhi = nlo + step - 1;
+      lo = (int)nlo;
+      hi = (int)(nhi < hi ? nhi : hi);
+    }
+    const bool less = (lo + lane < hi) && (indices[lo + lane] < p0);
+    const int t0 = lo + __popcll(__ballot(less));
+    if (t0 + lane < T) {
+      const int v = indices[t0 + lane];   // ascending: the listed rows of this block come first
+      if (v < p0 + kZeroRows) s_listed[v - p0] = 1;
+    }
+  }
+  __syncthreads();
+  const int lane = threadIdx.x % kLanesPerRow;
+  const nt_u32x4 z = {0u, 0u, 0u, 0u};
+  for (int r = threadIdx.x / kLanesPerRow; r < kZeroRows; r += kRowsPerBlock) {
+    const int p = p0 + r;
+    if (p < rows_padded && !s_listed[r]) {
+      nt_u32x4* dst = reinterpret_cast<nt_u32x4*>(padded + (size_t)p * units);
+      for (int u = lane; u < units; u += kLanesPerRow) __builtin_nontemporal_store(z, dst + u);
+    }
   }
 }
 
@@ -202,17 +244,17 @@ mb_status launch_gather_rows(const void* padded, const int32_t* indices, int T_c
 mb_status launch_scatter_rows(const void* packed, const int32_t* indices, int T_cap, const int32_t* meta,
                               int rows_padded, int row_bytes, void* padded, hipStream_t stream) {
   const int blocks = (rows_padded + kRowsPerBlock - 1) / kRowsPerBlock;
-  hipLaunchKernelGGL(scatter_rows_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)packed,
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)packed,
                      indices, T_cap, meta, rows_padded, row_bytes / 16, (uint4*)padded);
   return check_launch("scatter_rows_kernel");
 }
 
 mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* meta, int rows_padded,
                               int row_bytes, void* padded, hipStream_t stream) {
-  const int blocks = (rows_padded + kRowsPerBlock - 1) / kRowsPerBlock;
-  hipLaunchKernelGGL(scatter_rows_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream, (const uint4*)nullptr,
-                     indices, T_cap, meta, rows_padded, row_bytes / 16, (uint4*)padded);
-  return check_launch("scatter_rows_kernel<zero only>");
+  const int blocks = (rows_padded + kZeroRows - 1) / kZeroRows;
+  hipLaunchKernelGGL(zero_padding_kernel, dim3(blocks), dim3(kThreads), 0, stream, indices, T_cap, meta,
+                     rows_padded, row_bytes / 16, (uint4*)padded);
+  return check_launch("zero_padding_kernel");
 }
 
 }  // namespace mb
