@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--workload", default="bert_base")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--detail", action="store_true", help="also time each call of the path separately")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="override the number of sequences (same recipe); not the benchmark configuration")
     ap.add_argument("--full-length", action="store_true",
                     help="every sequence gets max_len tokens (no padding): shows what the attention kernels reach "
                          "without ragged tiles; not the benchmark configuration")
@@ -66,7 +68,7 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    batch = wl.make_batch(args.workload, full_length=args.full_length)
+    batch = wl.make_batch(args.workload, batch=args.batch, full_length=args.full_length)
     w = batch["workload"]
     B, L, H, D = w.B, w.L, w.H, w.D
     bf16 = w.dtype == "bf16"
