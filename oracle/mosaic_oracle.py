@@ -24,6 +24,10 @@ it); positions are those of the padded row, which for suffix padding equal the
 positions inside the packed sequence; masks are int, nonzero = real token;
 indices are ascending flat positions b*L + l; logsumexp is the natural log.
 
+Beyond the attention path the file holds the two neighbouring sublayers of the
+encoder block in the same plain style: the residual add + LayerNorm with 2-byte
+storage ("Low Precision LayerNorm" paragraph) and the GeGLU feed-forward of Eq. 2.
+
 Every function here is pinned by tests/test_oracle_pins.py against closed
 forms, invariants, finite differences, brute force and a library routine.
 """
@@ -217,3 +221,49 @@ def add_layernorm_bwd(dy, s, gamma, eps):
     g = dy * np.asarray(gamma, dtype=np.float64)
     ds = rstd * (g - g.mean(axis=1, keepdims=True) - xhat * (g * xhat).mean(axis=1, keepdims=True))
     return ds, (dy * xhat).sum(axis=0), dy.sum(axis=0)
+
+
+# --------------------------------------------------------------------------- GeGLU feed-forward
+def gelu(z: np.ndarray) -> np.ndarray:
+    """Gaussian-error linear unit, the exact form z * Phi(z) with Phi the standard normal
+    distribution function, Phi(z) = (1 + erf(z / sqrt 2)) / 2 (section "Gated Linear Units": the
+    paper names GeLU and gives no formula; the exact form is the reading taken, not the tanh fit)."""
+    from scipy.special import erf
+    z = np.asarray(z, dtype=np.float64)
+    return 0.5 * z * (1.0 + erf(z / np.sqrt(2.0)))
+
+
+def gelu_grad(z: np.ndarray) -> np.ndarray:
+    """d/dz [z Phi(z)] = Phi(z) + z phi(z), phi the standard normal density."""
+    from scipy.special import erf
+    z = np.asarray(z, dtype=np.float64)
+    return 0.5 * (1.0 + erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
+
+
+def geglu_fwd(x, w1, v, w2):
+    """Eq. 2:  y = (GeLU(x W1) (*) x V) W2, no bias terms, float64.
+
+    x [T, hidden]; w1, v [inter, hidden] and w2 [hidden, inter] hold the TRANSPOSES of the paper's W1, V
+    and W2 (the [out_features, in_features] storage of a linear layer), so x W1 is x @ w1.T.
+    Returns (y [T, hidden], a [T, inter]) with a = GeLU(x W1) (*) x V, the tensor between the two
+    projections."""
+    x, w1, v, w2 = (np.asarray(t, dtype=np.float64) for t in (x, w1, v, w2))
+    h = x @ w1.T
+    g = x @ v.T
+    a = gelu(h) * g
+    return a @ w2.T, a
+
+
+def geglu_bwd(dy, x, w1, v, w2):
+    """Textbook derivative of geglu_fwd for the scalar loss sum(y * dy) (the paper prints none).
+    Returns (dx, dw1, dv, dw2) in the layouts of x, w1, v, w2."""
+    dy, x, w1, v, w2 = (np.asarray(t, dtype=np.float64) for t in (dy, x, w1, v, w2))
+    h = x @ w1.T
+    g = x @ v.T
+    a = gelu(h) * g
+    da = dy @ w2                    # [T, inter]
+    dw2 = dy.T @ a                  # [hidden, inter]
+    dh = da * g * gelu_grad(h)
+    dg = da * gelu(h)
+    dx = dh @ w1 + dg @ v
+    return dx, dh.T @ x, dg.T @ x, dw2

@@ -416,3 +416,100 @@ def test_layernorm_backward_pins():
     xhat0 = (s - s.mean(1, keepdims=True)) / np.sqrt(s.var(1, keepdims=True))
     assert np.allclose((ds0 * xhat0).sum(1), 0, atol=1e-11)
     assert np.allclose(db, dy.sum(0))
+
+
+# --------------------------------------------------------------------------- GeGLU feed-forward (Eq. 2)
+def test_gelu_pins():
+    import math
+    z = np.linspace(-6.0, 6.0, 241)
+    y = orc.gelu(z)
+    # closed values: GeLU(0) = 0; Phi(1) = 0.841344746068543 (standard normal table)
+    assert orc.gelu(np.array([0.0]))[0] == 0.0
+    assert abs(orc.gelu(np.array([1.0]))[0] - 0.841344746068543) < 1e-15
+    assert abs(orc.gelu(np.array([-1.0]))[0] + (1.0 - 0.841344746068543)) < 1e-15
+    # Phi(z) + Phi(-z) = 1  =>  GeLU(z) - GeLU(-z) = z
+    np.testing.assert_allclose(y - orc.gelu(-z), z, atol=1e-15)
+    # brute force: Phi(z) = 1/2 + integral_0^z phi(t) dt by composite Simpson on 2000 panels
+    def phi_int(zz):
+        n = 2000
+        t = np.linspace(0.0, zz, n + 1)
+        f = np.exp(-0.5 * t * t) / math.sqrt(2.0 * math.pi)
+        return 0.5 + (zz / n) / 3.0 * (f[0] + f[-1] + 4.0 * f[1:-1:2].sum() + 2.0 * f[2:-1:2].sum())
+    for zz in (-3.3, -1.7, -0.4, 0.25, 0.9, 2.2, 4.1):
+        assert abs(orc.gelu(np.array([zz]))[0] - zz * phi_int(zz)) < 1e-12
+    # another library's erf, and torch's exact gelu in float64
+    np.testing.assert_allclose(y, [0.5 * t * (1.0 + math.erf(t / math.sqrt(2.0))) for t in z], atol=1e-15)
+    np.testing.assert_allclose(y, torch.nn.functional.gelu(torch.from_numpy(z), approximate="none").numpy(), atol=1e-15)
+    # not the tanh fit: the two differ by up to ~5e-4 near |z| = 2
+    assert np.abs(y - torch.nn.functional.gelu(torch.from_numpy(z), approximate="tanh").numpy()).max() > 1e-4
+    # limits and derivative
+    assert abs(orc.gelu(np.array([12.0]))[0] - 12.0) < 1e-15 and abs(orc.gelu(np.array([-12.0]))[0]) < 1e-15
+    eps = 1e-6
+    np.testing.assert_allclose(orc.gelu_grad(z), (orc.gelu(z + eps) - orc.gelu(z - eps)) / (2 * eps), atol=1e-9)
+
+
+def _geglu_case(seed, T, hidden, inter):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, hidden))
+    w1 = rng.standard_normal((inter, hidden)) / np.sqrt(hidden)
+    v = rng.standard_normal((inter, hidden)) / np.sqrt(hidden)
+    w2 = rng.standard_normal((hidden, inter)) / np.sqrt(inter)
+    dy = rng.standard_normal((T, hidden))
+    return x, w1, v, w2, dy
+
+
+def test_geglu_forward_pins():
+    x, w1, v, w2, _ = _geglu_case(3, 7, 5, 11)
+    y, a = orc.geglu_fwd(x, w1, v, w2)
+    assert y.shape == (7, 5) and a.shape == (7, 11)
+    # element by element from the definition, with plain loops and math.erf
+    import math
+    for t in (0, 3, 6):
+        for j in (0, 4, 10):
+            h = sum(x[t, c] * w1[j, c] for c in range(5))
+            g = sum(x[t, c] * v[j, c] for c in range(5))
+            assert abs(a[t, j] - 0.5 * h * (1.0 + math.erf(h / math.sqrt(2.0))) * g) < 1e-14
+        for c in (0, 2, 4):
+            assert abs(y[t, c] - sum(a[t, j] * w2[c, j] for j in range(11))) < 1e-13
+    # library composition in float64 (linear layers store [out_features, in_features])
+    F = torch.nn.functional
+    tx, tw1, tv, tw2 = (torch.from_numpy(t) for t in (x, w1, v, w2))
+    ref = F.linear(F.gelu(F.linear(tx, tw1)) * F.linear(tx, tv), tw2)
+    np.testing.assert_allclose(y, ref.numpy(), atol=1e-13)
+    # the fused layout of the appendix on GLU implementations: one projection of twice the width, then a slice
+    both = F.linear(tx, torch.cat([tw1, tv], dim=0))
+    ref2 = F.linear(F.gelu(both[:, :11]) * both[:, 11:], tw2)
+    np.testing.assert_allclose(y, ref2.numpy(), atol=1e-13)
+    # special cases: zero gate matrix -> zero output; the gate is linear in V; rows are independent;
+    # swapping W1 and V changes the result (the nonlinearity sits on the W1 branch only)
+    assert np.all(orc.geglu_fwd(x, w1, 0 * v, w2)[0] == 0)
+    np.testing.assert_allclose(orc.geglu_fwd(x, w1, 3.0 * v, w2)[0], 3.0 * y, atol=1e-13)
+    np.testing.assert_allclose(orc.geglu_fwd(x[2:3], w1, v, w2)[0], y[2:3], atol=1e-14)
+    assert np.abs(orc.geglu_fwd(x, v, w1, w2)[0] - y).max() > 1e-2
+    # identity output projection and a gate that is constantly 1 reduce to GeLU of a linear layer
+    w2i = np.eye(11)
+    vi = np.zeros((11, 5)); xi = x.copy(); xi[:, 0] = 1.0; vi[:, 0] = 1.0
+    np.testing.assert_allclose(orc.geglu_fwd(xi, w1, vi, w2i)[0], orc.gelu(xi @ w1.T), atol=1e-14)
+
+
+def test_geglu_backward_pins():
+    x, w1, v, w2, dy = _geglu_case(5, 6, 4, 9)
+    dx, dw1, dv, dw2 = orc.geglu_bwd(dy, x, w1, v, w2)
+    # torch autograd in float64
+    F = torch.nn.functional
+    ts = [torch.from_numpy(t).clone().requires_grad_(True) for t in (x, w1, v, w2)]
+    out = F.linear(F.gelu(F.linear(ts[0], ts[1])) * F.linear(ts[0], ts[2]), ts[3])
+    (out * torch.from_numpy(dy)).sum().backward()
+    for mine, t in zip((dx, dw1, dv, dw2), ts):
+        np.testing.assert_allclose(mine, t.grad.numpy(), atol=1e-12)
+    # central finite differences of the scalar loss, a few entries of every argument
+    def loss(x_, w1_, v_, w2_):
+        return float((orc.geglu_fwd(x_, w1_, v_, w2_)[0] * dy).sum())
+    args = [x, w1, v, w2]
+    eps = 1e-6
+    for which, grad in enumerate((dx, dw1, dv, dw2)):
+        for idx in ((0, 0), (1, 2), (grad.shape[0] - 1, grad.shape[1] - 1)):
+            plus = [t.copy() for t in args]; minus = [t.copy() for t in args]
+            plus[which][idx] += eps; minus[which][idx] -= eps
+            fd = (loss(*plus) - loss(*minus)) / (2 * eps)
+            assert abs(fd - grad[idx]) < 1e-7 * max(1.0, abs(fd)), (which, idx, fd, grad[idx])
