@@ -203,6 +203,26 @@ MB_API mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void*
                                       void* ds, float* dgamma, float* dbeta, void* workspace,
                                       size_t workspace_bytes, void* stream);
 
+/*
+ * GeGLU feed-forward sublayer, forward (Eq. 2 of the paper:  y = (GeLU(x W1) (*) x V) W2,  GeLU(h) = h Phi(h)
+ * in its exact form, no bias terms), in the fused arrangement of the appendix on GLU implementations: the two
+ * input projections are one matrix of twice the width whose product is sliced in two.
+ *   x      dev, [T_cap, hidden], read.
+ *   w1v    dev, [2*inter, hidden], read: rows 0..inter-1 hold W1 transposed, rows inter..2*inter-1 hold V
+ *          transposed (the [out_features, in_features] storage of a linear layer, contiguous along hidden).
+ *   w2     dev, [hidden, inter], read: W2 transposed, same convention.
+ *   T_cap, meta_dev  rows [0, T) are processed, T = min(meta_dev[0], T_cap), or T_cap if meta_dev is NULL;
+ *          rows at and beyond T are neither read nor written.
+ *   act    dev, [T_cap, inter], written: GeLU(x W1) (*) x V rounded once to the storage type; it is the
+ *          operand of the second projection and what a backward pass needs.
+ *   y      dev, [T_cap, hidden], written.
+ * Products accumulate in fp32.  Supported: MB_BF16 with hidden a multiple of 256 and inter a multiple of 128
+ * (MB_ERR_UNSUPPORTED otherwise).  All pointers 16-byte aligned.  Nothing is allocated; work is enqueued on
+ * `stream`.
+ */
+MB_API mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta_dev,
+                              int hidden, int inter, mb_dtype dt, void* act, void* y, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ MB_F32, MB_BF16 = 0, 1
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
            "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
-           "mb_add_layernorm_bwd")
+           "mb_add_layernorm_bwd", "mb_geglu_fwd")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -61,6 +61,9 @@ _lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
 _lib.mb_add_layernorm_bwd.restype = c_int
 _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.mb_geglu_fwd.restype = c_int
+_lib.mb_geglu_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p,
+                              c_void_p]
 
 
 class MosaicAttnError(RuntimeError):
@@ -243,3 +246,18 @@ def mb_add_layernorm_bwd(dy, s, gamma, mean, rstd, T_cap=None, meta=None, ds=Non
                                      _dtype_code(s), _ptr(ds), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
                                      workspace.numel(), _stream()))
     return ds, dgamma, dbeta
+
+
+def mb_geglu_fwd(x, w1v, w2, T_cap=None, meta=None, act=None, y=None):
+    """x [rows, hidden]; w1v [2*inter, hidden] (W1 transposed over V transposed); w2 [hidden, inter] (W2
+    transposed).  Returns (y [rows, hidden], act [rows, inter])."""
+    assert x.dim() == 2 and x.is_contiguous() and w1v.is_contiguous() and w2.is_contiguous()
+    rows, hidden = x.shape
+    inter = w2.shape[1]
+    assert tuple(w1v.shape) == (2 * inter, hidden) and tuple(w2.shape) == (hidden, inter)
+    T_cap = rows if T_cap is None else T_cap
+    act = torch.empty((rows, inter), dtype=x.dtype, device=x.device) if act is None else act
+    y = torch.empty_like(x) if y is None else y
+    _check(_lib.mb_geglu_fwd(_ptr(x), _ptr(w1v), _ptr(w2), T_cap, _ptr(meta), hidden, inter, _dtype_code(x),
+                             _ptr(act), _ptr(y), _stream()))
+    return y, act

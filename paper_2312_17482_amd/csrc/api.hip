@@ -336,4 +336,26 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
                                  dv_row_stride, (float*)workspace, (hipStream_t)stream);
 }
 
+mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta_dev, int hidden,
+                       int inter, mb_dtype dt, void* act, void* y, void* stream) {
+  clear_error();
+  MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap must be >= 0 (got %d)", T_cap);
+  MB_REQUIRE(hidden > 0 && inter > 0, MB_ERR_INVALID_ARG, "hidden and inter must be positive (got %d, %d)", hidden,
+             inter);
+  MB_REQUIRE(dt == MB_BF16, MB_ERR_UNSUPPORTED, "the feed-forward kernels are bf16 only");
+  MB_REQUIRE(hidden % 256 == 0 && inter % 128 == 0, MB_ERR_UNSUPPORTED,
+             "hidden must be a multiple of 256 and inter a multiple of 128 (got %d, %d)", hidden, inter);
+  MB_REQUIRE((int64_t)T_cap * (int64_t)(inter > hidden ? inter : hidden) < ((int64_t)1 << 31) &&
+                 2 * (int64_t)inter * (int64_t)hidden < ((int64_t)1 << 31),
+             MB_ERR_UNSUPPORTED, "tensor of 2^31 elements or more (T_cap=%d hidden=%d inter=%d)", T_cap, hidden, inter);
+  if (T_cap == 0) return MB_OK;
+  MB_CHECK_PTR(x);
+  MB_CHECK_PTR(w1v);
+  MB_CHECK_PTR(w2);
+  MB_CHECK_PTR(act);
+  MB_CHECK_PTR(y);
+  return launch_geglu_fwd(x, w1v, w2, T_cap, meta_dev, hidden, inter, act, y, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -64,6 +64,10 @@ mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* 
 
 // Add & LayerNorm.  The backward writes one partial row of column sums per workgroup, at most this many.
 static constexpr int kLayerNormMaxParts = 1024;
+// GeGLU feed-forward, forward (bf16; hidden a multiple of 256, inter a multiple of 128).
+mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta,
+                           int hidden, int inter, void* act, void* y, hipStream_t stream);
+
 mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
                                    int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
                                    float* rstd, hipStream_t stream);

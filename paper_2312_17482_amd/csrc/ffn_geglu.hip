@@ -1,0 +1,194 @@
+// GeGLU feed-forward of the encoder block (Eq. 2 of the paper):  y = (GeLU(x W1) (*) x V) W2,
+// forward, bf16 storage, fp32 accumulation on the matrix cores.
+//
+// Two launches of one tiled GEMM kernel, both of the form  out[t, n] = sum_k X[t, k] * Wt[n, k]
+// (token rows and weight rows are both contiguous along k, the storage of a linear layer):
+//   1. gated:  the weight is the fused [2*inter, hidden] matrix of the appendix on GLU implementations
+//      (rows 0..inter-1 = W1^T, rows inter.. = V^T).  A workgroup computes, for 256 tokens, 128 columns
+//      of x W1 and THE SAME 128 columns of x V, so the slice and the product GeLU(.) (*) (.) happen on
+//      the accumulators: neither projection is ever written to memory.
+//   2. plain:  y = a W2 with the [hidden, inter] matrix W2^T.
+//
+// Tiling: 256 tokens x 256 weight rows per workgroup of 4 waves (2 x 2, each 128 x 128 = 16 accumulator
+// tiles of v_mfma_f32_32x32x16_bf16), k in steps of 64 through two LDS stages (next stage is written
+// while the current one is consumed: one barrier per step), the stage after that in flight in registers.
+// The products are formed transposed (weight rows along accumulator rows, tokens along lanes), so a
+// lane owns runs of 4 consecutive output columns of one token; the tile is turned into full 128-byte
+// row segments through a wave-private LDS slab before it is stored.
+#include "common.h"
+#include "mfma_util.h"
+
+namespace mb {
+namespace {
+
+constexpr int kBM = 256;                              // tokens per workgroup
+constexpr int kBN = 256;                              // weight rows per workgroup
+constexpr int kBK = 64;                               // k per stage
+constexpr int kPitch = 72;                            // LDS row pitch, elements (144 B: conflict-free 16-byte reads)
+constexpr int kStage = (kBM + kBN) * kPitch;          // elements per stage (73728 B)
+constexpr int kGroupM = 4;                            // token panels walked together (L2 reuse of the weight tiles)
+
+// GeLU(h) = h * Phi(h), exact form.
+__device__ __forceinline__ float gelu_exact(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
+
+template <bool kGated>
+__global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
+                                                          const uint16_t* __restrict__ W, int ldw, int K,
+                                                          int n_tiles, int gate_row, int T_cap,
+                                                          const int32_t* __restrict__ meta,
+                                                          uint16_t* __restrict__ out, int ldo) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kStage];
+
+  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  const int m_tiles = (T_cap + kBM - 1) / kBM;
+
+  // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs; give every XCD a
+  // contiguous run of tiles, walked kGroupM token panels at a time, so that the tiles resident on one
+  // XCD share their token panels and weight tiles in that XCD's L2.
+  const int total = gridDim.x, per = total >> 3;
+  int lin = blockIdx.x;
+  if (lin < (per << 3)) lin = (lin & 7) * per + (lin >> 3);
+  const int group = lin / (kGroupM * n_tiles);
+  const int first_m = group * kGroupM;
+  const int gsize = min(m_tiles - first_m, kGroupM);
+  const int rem = lin - group * (kGroupM * n_tiles);
+  const int tile_m = first_m + rem % gsize;
+  const int tile_n = rem / gsize;
+  const int m0 = tile_m * kBM;
+  if (m0 >= T) return;
+  constexpr int kOutCols = kGated ? kBN / 2 : kBN;    // output columns per workgroup
+  const int n0 = tile_n * kOutCols;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // Global -> LDS staging: a row of a stage is 128 bytes = 8 lanes x 16 bytes; 32 rows per pass.
+  const int lrow = tid >> 3, lchunk = (tid & 7) * 8;
+  // (element offsets fit 32 bits: the host checks rows * row length < 2^31)
+  uint32_t xsrc[8], wsrc[8];
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const int r = 32 * p + lrow;
+    xsrc[p] = (uint32_t)min(m0 + r, T - 1) * (uint32_t)ldx + lchunk;
+    const int wr = kGated ? (r < 128 ? n0 + r : gate_row + n0 + (r - 128)) : n0 + r;
+    wsrc[p] = (uint32_t)wr * (uint32_t)ldw + lchunk;
+  }
+  u32x4 stage[16];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      stage[p] = *reinterpret_cast<const u32x4*>(X + (xsrc[p] + k0));
+      stage[8 + p] = *reinterpret_cast<const u32x4*>(W + (wsrc[p] + k0));
+    }
+  };
+  auto deposit = [&](uint16_t* buf) {
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+      *reinterpret_cast<u32x4*>(&buf[(32 * p + lrow) * kPitch + lchunk]) = stage[p];
+  };
+
+  // Fragment rows of this wave inside a stage: tokens at rows 0..255, weight rows at 256..511.
+  // Gated: accumulator rows nb = 0,1 are columns of x W1, nb = 2,3 the same columns of x V.
+  int xoff[4], woff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    xoff[i] = (wm * 128 + i * 32 + c) * kPitch + g * 8;
+    const int wr = kGated ? (i >> 1) * 128 + wn * 64 + (i & 1) * 32 : wn * 128 + i * 32;
+    woff[i] = (kBM + wr + c) * kPitch + g * 8;
+  }
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
+
+  const int nk = K / kBK;
+  fetch(0);
+  deposit(smem);
+  if (nk > 1) fetch(kBK);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const uint16_t* cur = smem + (kt & 1) * kStage;
+    // (every wave left the other stage at the barrier that ended the previous step)
+    if (kt + 1 < nk) deposit(smem + ((kt + 1) & 1) * kStage);
+    if (kt + 2 < nk) fetch((kt + 2) * kBK);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 wf[4], xf[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        wf[i] = lds_read8(cur + woff[i] + kk * 16);
+        xf[i] = lds_read8(cur + xoff[i] + kk * 16);
+      }
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma32(wf[nb], xf[mb], acc[nb][mb]);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue.  The stage that the last step did not read is free: one 128-token x 64-column slab per wave.
+  uint16_t* slab = smem + (nk & 1) * kStage + wave * (128 * kPitch);
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+  const int row_base = m0 + wm * 128;
+  constexpr int kHalves = kGated ? 1 : 2;
+#pragma unroll
+  for (int half = 0; half < kHalves; ++half) {
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float r[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (kGated) r[i] = gelu_exact(acc[nb][mb][4 * j + i]) * acc[nb + 2][mb][4 * j + i];
+            else r[i] = acc[2 * half + nb][mb][4 * j + i];
+          }
+          u32x2 w;
+          w[0] = pack_bf16(r[0], r[1]);
+          w[1] = pack_bf16(r[2], r[3]);
+          *reinterpret_cast<u32x2*>(&slab[(mb * 32 + c) * kPitch + nb * 32 + 8 * j + 4 * g]) = w;
+        }
+      }
+    }
+    // (same wave wrote and reads the slab: LDS operations of one wave complete in order)
+    const int col = n0 + (kGated ? wn * 64 : wn * 128 + half * 64) + ocol;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int row = 8 * it + orow;
+      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      if (row_base + row < T) *reinterpret_cast<u32x4*>(out + (int64_t)(row_base + row) * ldo + col) = w;
+    }
+  }
+}
+
+}  // namespace
+
+mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta,
+                           int hidden, int inter, void* act, void* y, hipStream_t stream) {
+  if (T_cap == 0) return MB_OK;
+  const int m_tiles = (T_cap + kBM - 1) / kBM;
+  {
+    const int n_tiles = inter / (kBN / 2);
+    ffn_gemm_kernel<true><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
+        T_cap, meta, static_cast<uint16_t*>(act), inter);
+  }
+  {
+    const int n_tiles = hidden / kBN;
+    ffn_gemm_kernel<false><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, T_cap,
+        meta, static_cast<uint16_t*>(y), hidden);
+  }
+  return check_launch("ffn_gemm_kernel");
+}
+
+}  // namespace mb

@@ -122,6 +122,18 @@ def random_attention_case(seed: int, lengths, L: int, H: int, D: int, std: float
     return out
 
 
+def random_ffn_case(seed: int, T: int, hidden: int, inter: int, w_std: float = 0.02) -> dict:
+    """Inputs of the feed-forward sublayer, rounded to bf16: x ~ N(0,1) (what a LayerNorm hands over),
+    weights ~ N(0, w_std^2) in [out_features, in_features] storage (0.02 = the usual BERT initialisation;
+    the paper states none), w1v = W1 transposed stacked over V transposed, dy ~ N(0,1)."""
+    rng = np.random.default_rng(seed)
+    x = round_to_bf16(rng.standard_normal((T, hidden), dtype=np.float32))
+    w1v = round_to_bf16(rng.standard_normal((2 * inter, hidden), dtype=np.float32) * np.float32(w_std))
+    w2 = round_to_bf16(rng.standard_normal((hidden, inter), dtype=np.float32) * np.float32(w_std))
+    dy = round_to_bf16(rng.standard_normal((T, hidden), dtype=np.float32))
+    return {"x": x, "w1v": w1v, "w2": w2, "dy": dy, "hidden": hidden, "inter": inter}
+
+
 def random_mask(seed: int, B: int, L: int, keep_prob: float) -> np.ndarray:
     """Arbitrary 0/1 mask (holes allowed) for the index-map tests."""
     rng = np.random.default_rng(seed)

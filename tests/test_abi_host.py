@@ -163,3 +163,18 @@ def test_layernorm_rejects_bad_arguments():
     assert need == 1024 * 2 * 768 * 4 and mb.mb_add_layernorm_bwd_workspace_bytes(0) == 0
     assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, A, A, A, need - 1, None) == mb.MB_ERR_WORKSPACE
     assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, None, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+
+
+def test_geglu_rejects_bad_arguments():
+    f = lib.mb_geglu_fwd
+    assert f(A, A, A, 16, None, 768, 3072, mb.MB_F32, A, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, 16, None, 768, 3072, 7, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, -1, None, 768, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, 16, None, 0, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, 16, None, 700, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, 16, None, 768, 3000, mb.MB_BF16, A, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, 1 << 20, None, 768, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_UNSUPPORTED     # 2^31 elements
+    assert f(None, A, A, 16, None, 768, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, 16, None, 768, 3072, mb.MB_BF16, A, None, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A + 8, A, A, 16, None, 768, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(None, None, None, 0, None, 768, 3072, mb.MB_BF16, None, None, None) == mb.MB_OK

@@ -1,0 +1,99 @@
+"""GPU parity of the GeGLU feed-forward (forward) against the CPU oracle, through the C ABI.
+
+Tolerances (bf16 storage, fp32 accumulation): for the stored activation a = GeLU(x W1) (*) x V and for y,
+max-abs <= 2e-2 and relative Frobenius <= 1e-2, and in addition max-abs <= 2^-6 * max|ref| so that cases
+with small outputs are held to the same relative standard.  One case with O(1) weights has |a| up to ~10,
+where a correctly rounded bf16 value is already off by 2^-9 relative: there the absolute bound is
+max(2e-2, 2^-7 * max|ref|)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2312_17482_amd import workloads as wl
+from tests.helpers import err_stats
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mb():
+    assert torch.cuda.is_available()
+    from paper_2312_17482_amd import binding
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).cuda()
+
+
+def check(name, got, ref, wide=False):
+    ma, rf = err_stats(got.double().cpu().numpy(), ref)
+    top = float(np.abs(ref).max())
+    bound = max(2e-2, 2.0 ** -7 * top) if wide else min(2e-2, max(2.0 ** -6 * top, 1e-30))
+    assert ma <= bound and rf <= 1e-2, "%s max_abs=%.3e (bound %.3e) rel_fro=%.3e" % (name, ma, bound, rf)
+
+
+def run_case(mb, seed, T, hidden, inter, w_std=0.02, T_cap=None, wide=False):
+    case = wl.random_ffn_case(seed, T if T_cap is None else T_cap, hidden, inter, w_std)
+    x, w1v, w2 = case["x"], case["w1v"], case["w2"]
+    y_ref, a_ref = orc.geglu_fwd(x[:T], w1v[:inter], w1v[inter:], w2)
+    rows = x.shape[0]
+    guard = 2
+    act = torch.full((rows + guard, inter), 9.0, dtype=torch.bfloat16, device="cuda")
+    y = torch.full((rows + guard, hidden), 9.0, dtype=torch.bfloat16, device="cuda")
+    meta = None if T_cap is None else torch.tensor([T, 0], dtype=torch.int32, device="cuda")
+    mb.mb_geglu_fwd(dev(x), dev(w1v), dev(w2), meta=meta, act=act[:rows], y=y[:rows])
+    torch.cuda.synchronize()
+    assert torch.all(act[T:] == 9.0) and torch.all(y[T:] == 9.0), "rows at or beyond T were written"
+    check("act", act[:T], a_ref, wide)
+    check("y", y[:T], y_ref, wide)
+    return act, y
+
+
+@pytest.mark.parametrize("T,hidden,inter", [(1, 256, 128), (37, 256, 384), (256, 256, 128), (257, 512, 256),
+                                            (700, 768, 3072), (1300, 1024, 4096), (2049, 256, 640)])
+def test_geglu_forward_parity(mb, T, hidden, inter):
+    print("geglu T=%d hidden=%d inter=%d" % (T, hidden, inter), flush=True)
+    run_case(mb, 11, T, hidden, inter)
+
+
+def test_geglu_forward_unit_scale_weights(mb):
+    print("geglu unit-scale weights", flush=True)
+    run_case(mb, 12, 600, 768, 3072, w_std=1.0 / np.sqrt(768.0), wide=True)
+
+
+def test_geglu_forward_device_side_row_count(mb):
+    print("geglu capacity mode", flush=True)
+    run_case(mb, 13, 1111, 768, 3072, T_cap=1536)
+    run_case(mb, 14, 256, 256, 128, T_cap=1024)      # whole workgroups beyond T
+
+
+def test_geglu_forward_full_size_and_repeatable(mb):
+    """The feed-forward of the benchmark batch: 26963 packed tokens, hidden 768, intermediate 3072."""
+    print("geglu full size", flush=True)
+    case = wl.random_ffn_case(15, 26963, 768, 3072)
+    y_ref, a_ref = orc.geglu_fwd(case["x"], case["w1v"][:3072], case["w1v"][3072:], case["w2"])
+    xd, wd, w2d = dev(case["x"]), dev(case["w1v"]), dev(case["w2"])
+    y, act = mb.mb_geglu_fwd(xd, wd, w2d)
+    y2, act2 = mb.mb_geglu_fwd(xd, wd, w2d)
+    torch.cuda.synchronize()
+    check("act", act, a_ref)
+    check("y", y, y_ref)
+    assert torch.equal(y, y2) and torch.equal(act, act2)
+
+
+def test_geglu_empty_input(mb):
+    x = torch.empty((0, 768), dtype=torch.bfloat16, device="cuda")
+    w1v = torch.zeros((6144, 768), dtype=torch.bfloat16, device="cuda")
+    w2 = torch.zeros((768, 3072), dtype=torch.bfloat16, device="cuda")
+    y, act = mb.mb_geglu_fwd(x, w1v, w2)
+    assert y.shape == (0, 768) and act.shape == (0, 3072)
+    # T = 0 on the device with a non-zero capacity: nothing is written
+    xx = torch.zeros((512, 768), dtype=torch.bfloat16, device="cuda")
+    yy = torch.full((512, 768), 9.0, dtype=torch.bfloat16, device="cuda")
+    aa = torch.full((512, 3072), 9.0, dtype=torch.bfloat16, device="cuda")
+    meta = torch.zeros(2, dtype=torch.int32, device="cuda")
+    mb.mb_geglu_fwd(xx, w1v, w2, meta=meta, act=aa, y=yy)
+    torch.cuda.synchronize()
+    assert torch.all(yy == 9.0) and torch.all(aa == 9.0)
