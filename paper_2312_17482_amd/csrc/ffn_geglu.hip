@@ -18,6 +18,10 @@
 #include "common.h"
 #include "mfma_util.h"
 
+#ifndef FFN_DIAG
+#define FFN_DIAG 0
+#endif
+
 namespace mb {
 namespace {
 
@@ -34,12 +38,13 @@ __device__ __forceinline__ float gelu_exact(float h) { return 0.5f * h * (1.0f +
 template <bool kGated>
 __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                           const uint16_t* __restrict__ W, int ldw, int K,
-                                                          int n_tiles, int gate_row, int T_cap,
+                                                          int n_tiles, int gate_row, int w_rows, int T_cap,
                                                           const int32_t* __restrict__ meta,
                                                           uint16_t* __restrict__ out, int ldo) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kStage];
 
-  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  // (readfirstlane: tells the compiler the value is wave-uniform, so descriptors built from it stay scalar)
+  const int T = __builtin_amdgcn_readfirstlane(meta ? min(meta[0], T_cap) : T_cap);
   const int m_tiles = (T_cap + kBM - 1) / kBM;
 
   // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs; give every XCD a
@@ -52,8 +57,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   const int first_m = group * kGroupM;
   const int gsize = min(m_tiles - first_m, kGroupM);
   const int rem = lin - group * (kGroupM * n_tiles);
-  const int tile_m = first_m + rem % gsize;
-  const int tile_n = rem / gsize;
+  // (the divisions run on the vector unit; readfirstlane moves the wave-uniform results back to scalars)
+  const int tile_m = __builtin_amdgcn_readfirstlane(first_m + rem % gsize);
+  const int tile_n = __builtin_amdgcn_readfirstlane(rem / gsize);
   const int m0 = tile_m * kBM;
   if (m0 >= T) return;
   constexpr int kOutCols = kGated ? kBN / 2 : kBN;    // output columns per workgroup
@@ -65,27 +71,36 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
 
   // Global -> LDS staging: a row of a stage is 128 bytes = 8 lanes x 16 bytes; 32 rows per pass.
   const int lrow = tid >> 3, lchunk = (tid & 7) * 8;
-  // (element offsets fit 32 bits: the host checks rows * row length < 2^31)
-  uint32_t xsrc[8], wsrc[8];
-#pragma unroll
-  for (int p = 0; p < 8; ++p) {
-    const int r = 32 * p + lrow;
-    xsrc[p] = (uint32_t)min(m0 + r, T - 1) * (uint32_t)ldx + lchunk;
-    const int wr = kGated ? (r < 128 ? n0 + r : gate_row + n0 + (r - 128)) : n0 + r;
-    wsrc[p] = (uint32_t)wr * (uint32_t)ldw + lchunk;
-  }
-  u32x4 stage[16];
-  auto fetch = [&](int k0) {
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      stage[p] = *reinterpret_cast<const u32x4*>(X + (xsrc[p] + k0));
-      stage[8 + p] = *reinterpret_cast<const u32x4*>(W + (wsrc[p] + k0));
-    }
+  // Buffer loads: address = descriptor base + scalar offset + one per-lane offset, so the 16 loads of a
+  // step need no vector address arithmetic.  Token rows get one descriptor per pass whose extent ends at
+  // row T: rows at or beyond T read as zero instead of touching memory that may not exist.  (Byte
+  // offsets fit 32 bits: the host checks rows * row length < 2^31 elements.)
+  constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format (gfx9 family)
+  const uint32_t xlane = ((uint32_t)lrow * (uint32_t)ldx + lchunk) * 2u;
+  const uint32_t wlane = ((uint32_t)lrow * (uint32_t)ldw + lchunk) * 2u;
+  const __amdgpu_buffer_rsrc_t wrs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(W), 0, w_rows * ldw * 2, kRsrcFlags);
+  // Two register sets: while one k step is computed, the next one goes from registers to LDS and the two
+  // after it are in flight from memory (a load has two whole steps to arrive).
+  u32x4 st0[16], st1[16];
+  auto fetch_one = [&](u32x4 (&st)[16], int p, int k0) {
+    // (descriptor and offsets are scalar arithmetic on wave-uniform values)
+    const int first = m0 + 32 * p;
+    const int rows = __builtin_amdgcn_readfirstlane(max(min(T - first, 32), 0));   // (clamp is a vector op)
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(X) + (int64_t)first * ldx, 0, rows * ldx * 2, kRsrcFlags);
+    const int wr = kGated ? (p < 4 ? n0 + 32 * p : gate_row + n0 + 32 * (p - 4)) : n0 + 32 * p;
+    st[p] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, k0 * 2, 0);
+    st[8 + p] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane, (wr * ldw + k0) * 2, 0);
   };
-  auto deposit = [&](uint16_t* buf) {
+  auto fetch = [&](u32x4 (&st)[16], int k0) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) fetch_one(st, p, k0);
+  };
+  auto deposit = [&](const u32x4 (&st)[16], uint16_t* buf) {
 #pragma unroll
     for (int p = 0; p < 16; ++p)
-      *reinterpret_cast<u32x4*>(&buf[(32 * p + lrow) * kPitch + lchunk]) = stage[p];
+      *reinterpret_cast<u32x4*>(&buf[(32 * p + lrow) * kPitch + lchunk]) = st[p];
   };
 
   // Fragment rows of this wave inside a stage: tokens at rows 0..255, weight rows at 256..511.
@@ -106,35 +121,66 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
-  const int nk = K / kBK;
-  fetch(0);
-  deposit(smem);
-  if (nk > 1) fetch(kBK);
+  const int nk = K / kBK;                       // even (the host checks K % 128 == 0)
+  fetch(st0, 0);
+  deposit(st0, smem);
+  fetch(st1, kBK);
+  fetch(st0, min(2, nk - 1) * kBK);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const uint16_t* cur = smem + (kt & 1) * kStage;
-    // (every wave left the other stage at the barrier that ended the previous step)
-    if (kt + 1 < nk) deposit(smem + ((kt + 1) & 1) * kStage);
-    if (kt + 2 < nk) fetch((kt + 2) * kBK);
+  // One k step = 4 sub-steps of 16 matrix instructions (k = 16 each) on stage `cur`.  Issue order is
+  // written out by hand and fenced (with one wave per SIMD nothing but the order hides latencies):
+  // every group of 4 matrix instructions is preceded by 2 LDS reads of the NEXT sub-step's fragments
+  // (double-buffered), and in sub-step 0 by 4 LDS writes that move register set `st` (tile kt + 1) to
+  // stage `nxt`, in sub-step 1 by 4 global loads that refill `st` with tile kt + 3.  The workgroup
+  // barrier sits before sub-step 3: by then this wave has read all of `cur` and written its share of
+  // `nxt`, so sub-step 3 already reads the first fragments of `nxt`, and the next step may overwrite
+  // `cur`.  No branches: the last steps fetch a clamped, redundant tile and deposit it where nobody reads.
+  bf16x8 wf[2][4], xf[2][4];
+  auto read_pair = [&](const uint16_t* stage_ptr, int kk, int buf, int i) {     // i = 0..3: two of the 8 fragments
+    if (i < 2) {
+      wf[buf][2 * i] = lds_read8(stage_ptr + woff[2 * i] + kk * 16);
+      wf[buf][2 * i + 1] = lds_read8(stage_ptr + woff[2 * i + 1] + kk * 16);
+    } else {
+      xf[buf][2 * (i - 2)] = lds_read8(stage_ptr + xoff[2 * (i - 2)] + kk * 16);
+      xf[buf][2 * (i - 2) + 1] = lds_read8(stage_ptr + xoff[2 * (i - 2) + 1] + kk * 16);
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) read_pair(smem, 0, 0, i);
+  auto step = [&](const uint16_t* cur, uint16_t* nxt, u32x4 (&st)[16], int k_fetch) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 wf[4], xf[4];
+      if (kk == 3) __syncthreads();
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        wf[i] = lds_read8(cur + woff[i] + kk * 16);
-        xf[i] = lds_read8(cur + xoff[i] + kk * 16);
+      for (int q = 0; q < 4; ++q) {
+        // x fragments of the next sub-step first (all four are needed by its first group), then w
+        if (kk < 3) read_pair(cur, kk + 1, (kk + 1) & 1, (q + 2) & 3);
+        else read_pair(nxt, 0, 0, (q + 2) & 3);
+        if (kk == 0 && FFN_DIAG < 2) {
+#pragma unroll
+          for (int p = 4 * q; p < 4 * q + 4; ++p)
+            *reinterpret_cast<u32x4*>(&nxt[(32 * p + lrow) * kPitch + lchunk]) = st[p];
+        }
+        if (kk == 1 && FFN_DIAG < 1) {
+#pragma unroll
+          for (int p = 2 * q; p < 2 * q + 2; ++p) fetch_one(st, p, k_fetch);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
+        __builtin_amdgcn_sched_barrier(0);
       }
-#pragma unroll
-      for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma32(wf[nb], xf[mb], acc[nb][mb]);
     }
-    __syncthreads();
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    step(smem, smem + kStage, st1, min(kt + 3, nk - 1) * kBK);
+    step(smem + kStage, smem, st0, min(kt + 4, nk - 1) * kBK);
   }
+  __syncthreads();
 
   // Epilogue.  The stage that the last step did not read is free: one 128-token x 64-column slab per wave.
-  uint16_t* slab = smem + (nk & 1) * kStage + wave * (128 * kPitch);
+  uint16_t* slab = smem + wave * (128 * kPitch);
   const int orow = lane >> 3, ocol = (lane & 7) * 8;
   const int row_base = m0 + wm * 128;
   constexpr int kHalves = kGated ? 1 : 2;
@@ -180,12 +226,12 @@ mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T
     const int n_tiles = inter / (kBN / 2);
     ffn_gemm_kernel<true><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
         static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
-        T_cap, meta, static_cast<uint16_t*>(act), inter);
+        2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter);
   }
   {
     const int n_tiles = hidden / kBN;
     ffn_gemm_kernel<false><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
-        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, T_cap,
+        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden, T_cap,
         meta, static_cast<uint16_t*>(y), hidden);
   }
   return check_launch("ffn_gemm_kernel");
