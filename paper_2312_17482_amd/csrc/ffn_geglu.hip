@@ -9,38 +9,57 @@
 //      the accumulators: neither projection is ever written to memory.
 //   2. plain:  y = a W2 with the [hidden, inter] matrix W2^T.
 //
-// Tiling: 256 tokens x 256 weight rows per workgroup of 4 waves (2 x 2, each 128 x 128 = 16 accumulator
-// tiles of v_mfma_f32_32x32x16_bf16), k in steps of 64 through two LDS stages (next stage is written
-// while the current one is consumed: one barrier per step), the stage after that in flight in registers.
+// Tiling: 256 tokens x 256 (or 192) weight rows per workgroup of 4 waves (2 x 2, each 128 x 128 or
+// 128 x 96 = 16 or 12 accumulator tiles of v_mfma_f32_32x32x16_bf16), k in steps of 64 through two LDS
+// stages (next stage is written while the current one is consumed: one barrier per step), the two steps
+// after that in flight in registers.  The narrower tile exists for the second projection, whose few
+// column tiles otherwise leave the last round of workgroups mostly empty.
 // The products are formed transposed (weight rows along accumulator rows, tokens along lanes), so a
 // lane owns runs of 4 consecutive output columns of one token; the tile is turned into full 128-byte
 // row segments through a wave-private LDS slab before it is stored.
 #include "common.h"
 #include "mfma_util.h"
 
-#ifndef FFN_DIAG
-#define FFN_DIAG 0
-#endif
 
 namespace mb {
 namespace {
 
 constexpr int kBM = 256;                              // tokens per workgroup
-constexpr int kBN = 256;                              // weight rows per workgroup
 constexpr int kBK = 64;                               // k per stage
 constexpr int kPitch = 72;                            // LDS row pitch, elements (144 B: conflict-free 16-byte reads)
-constexpr int kStage = (kBM + kBN) * kPitch;          // elements per stage (73728 B)
 constexpr int kGroupM = 4;                            // token panels walked together (L2 reuse of the weight tiles)
 
-// GeLU(h) = h * Phi(h), exact form.
-__device__ __forceinline__ float gelu_exact(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
+// GeLU(h) = h * Phi(h), the exact (error-function) form, with Phi evaluated by the classic five-term
+// rational approximation of erfc (Abramowitz & Stegun 7.1.26, absolute error below 1.5e-7):
+//   x = |h| / sqrt 2,  t = 1 / (1 + p x),  u = (1/2) (a1 t + ... + a5 t^5) exp(-x^2) = Phi(-|h|),
+//   Phi(h) = u for h < 0 and 1 - u otherwise.
+// About 17 vector instructions per value, two of them transcendental; the result is rounded to bf16
+// (relative 2^-9) right after, so the approximation error is invisible.
+__device__ __forceinline__ float gelu_exact(float h) {
+  const float x = fabsf(h) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  poly = fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = fmaf(poly, t, 0.5f * 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(h * h * (-0.5f * kLog2e));
+  const float u = poly * t * e;                       // Phi(-|h|), in (0, 1/2]
+  const float phi = 0.5f + copysignf(0.5f - u, h);
+  return h * phi;
+}
 
-template <bool kGated>
+template <bool kGated, int kNB>   // kNB: 32-row weight blocks per wave (4 or 3); workgroup = 64 * kNB weight rows
 __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                           const uint16_t* __restrict__ W, int ldw, int K,
                                                           int n_tiles, int gate_row, int w_rows, int T_cap,
                                                           const int32_t* __restrict__ meta,
                                                           uint16_t* __restrict__ out, int ldo) {
+  static_assert(!kGated || kNB == 4, "the gated epilogue pairs weight blocks 0,1 with 2,3");
+  constexpr int kBN = 64 * kNB;                     // weight rows per workgroup
+  constexpr int kStage = (kBM + kBN) * kPitch;      // elements per LDS stage
+  constexpr int kLoads = 8 + 2 * kNB;               // 16-byte loads per thread and k step (32 rows per load)
+  constexpr int kSlots = 4 * kNB;                   // matrix instructions per sub-step
+  constexpr int kFrags = 4 + kNB;                   // fragments per sub-step
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kStage];
 
   // (readfirstlane: tells the compiler the value is wave-uniform, so descriptors built from it stay scalar)
@@ -69,10 +88,10 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   const int c = lane & 31, g = lane >> 5;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // Global -> LDS staging: a row of a stage is 128 bytes = 8 lanes x 16 bytes; 32 rows per pass.
+  // Global -> LDS staging: a row of a stage is 128 bytes = 8 lanes x 16 bytes; 32 rows per load.
   const int lrow = tid >> 3, lchunk = (tid & 7) * 8;
-  // Buffer loads: address = descriptor base + scalar offset + one per-lane offset, so the 16 loads of a
-  // step need no vector address arithmetic.  Token rows get one descriptor per pass whose extent ends at
+  // Buffer loads: address = descriptor base + scalar offset + one per-lane offset, so the loads of a
+  // step need no vector address arithmetic.  Token rows get one descriptor per load whose extent ends at
   // row T: rows at or beyond T read as zero instead of touching memory that may not exist.  (Byte
   // offsets fit 32 bits: the host checks rows * row length < 2^31 elements.)
   constexpr int kRsrcFlags = 0x00020000;        // raw buffer, 32-bit data format (gfx9 family)
@@ -80,96 +99,98 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   const uint32_t wlane = ((uint32_t)lrow * (uint32_t)ldw + lchunk) * 2u;
   const __amdgpu_buffer_rsrc_t wrs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(W), 0, w_rows * ldw * 2, kRsrcFlags);
+  // Load i of a step: i < 8 token rows 32 i .., else weight rows 32 (i - 8) .. of the tile (stage row 32 i).
+  // (descriptor and offsets are scalar arithmetic on wave-uniform values)
+  auto fetch_one = [&](u32x4 (&st)[kLoads], int i, int k0) {
+    if (i < 8) {
+      const int first = m0 + 32 * i;
+      const int rows = __builtin_amdgcn_readfirstlane(max(min(T - first, 32), 0));   // (the clamp is a vector op)
+      const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(X) + (int64_t)first * ldx, 0, rows * ldx * 2, kRsrcFlags);
+      st[i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, k0 * 2, 0);
+    } else {
+      const int p = i - 8;
+      const int wr = kGated ? (p < 4 ? n0 + 32 * p : gate_row + n0 + 32 * (p - 4)) : n0 + 32 * p;
+      st[i] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane, (wr * ldw + k0) * 2, 0);
+    }
+  };
+  auto deposit_one = [&](const u32x4 (&st)[kLoads], int i, uint16_t* buf) {
+    *reinterpret_cast<u32x4*>(&buf[(32 * i + lrow) * kPitch + lchunk]) = st[i];
+  };
   // Two register sets: while one k step is computed, the next one goes from registers to LDS and the two
   // after it are in flight from memory (a load has two whole steps to arrive).
-  u32x4 st0[16], st1[16];
-  auto fetch_one = [&](u32x4 (&st)[16], int p, int k0) {
-    // (descriptor and offsets are scalar arithmetic on wave-uniform values)
-    const int first = m0 + 32 * p;
-    const int rows = __builtin_amdgcn_readfirstlane(max(min(T - first, 32), 0));   // (clamp is a vector op)
-    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(X) + (int64_t)first * ldx, 0, rows * ldx * 2, kRsrcFlags);
-    const int wr = kGated ? (p < 4 ? n0 + 32 * p : gate_row + n0 + 32 * (p - 4)) : n0 + 32 * p;
-    st[p] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xlane, k0 * 2, 0);
-    st[8 + p] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane, (wr * ldw + k0) * 2, 0);
-  };
-  auto fetch = [&](u32x4 (&st)[16], int k0) {
-#pragma unroll
-    for (int p = 0; p < 8; ++p) fetch_one(st, p, k0);
-  };
-  auto deposit = [&](const u32x4 (&st)[16], uint16_t* buf) {
-#pragma unroll
-    for (int p = 0; p < 16; ++p)
-      *reinterpret_cast<u32x4*>(&buf[(32 * p + lrow) * kPitch + lchunk]) = st[p];
-  };
+  u32x4 st0[kLoads], st1[kLoads];
 
-  // Fragment rows of this wave inside a stage: tokens at rows 0..255, weight rows at 256..511.
+  // Fragment rows of this wave inside a stage: tokens at rows 0..255, weight rows from 256 on.
   // Gated: accumulator rows nb = 0,1 are columns of x W1, nb = 2,3 the same columns of x V.
-  int xoff[4], woff[4];
+  int xoff[4], woff[kNB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    xoff[i] = (wm * 128 + i * 32 + c) * kPitch + g * 8;
-    const int wr = kGated ? (i >> 1) * 128 + wn * 64 + (i & 1) * 32 : wn * 128 + i * 32;
+  for (int i = 0; i < 4; ++i) xoff[i] = (wm * 128 + i * 32 + c) * kPitch + g * 8;
+#pragma unroll
+  for (int i = 0; i < kNB; ++i) {
+    const int wr = kGated ? (i >> 1) * 128 + wn * 64 + (i & 1) * 32 : wn * (32 * kNB) + i * 32;
     woff[i] = (kBM + wr + c) * kPitch + g * 8;
   }
 
-  f32x16 acc[4][4];
+  f32x16 acc[kNB][4];
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb)
+  for (int nb = 0; nb < kNB; ++nb)
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
   const int nk = K / kBK;                       // even (the host checks K % 128 == 0)
-  fetch(st0, 0);
-  deposit(st0, smem);
-  fetch(st1, kBK);
-  fetch(st0, min(2, nk - 1) * kBK);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) fetch_one(st0, i, 0);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) deposit_one(st0, i, smem);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) fetch_one(st1, i, kBK);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) fetch_one(st0, i, min(2, nk - 1) * kBK);
   __syncthreads();
 
-  // One k step = 4 sub-steps of 16 matrix instructions (k = 16 each) on stage `cur`.  Issue order is
-  // written out by hand and fenced (with one wave per SIMD nothing but the order hides latencies):
-  // every group of 4 matrix instructions is preceded by 2 LDS reads of the NEXT sub-step's fragments
-  // (double-buffered), and in sub-step 0 by 4 LDS writes that move register set `st` (tile kt + 1) to
-  // stage `nxt`, in sub-step 1 by 4 global loads that refill `st` with tile kt + 3.  The workgroup
-  // barrier sits before sub-step 3: by then this wave has read all of `cur` and written its share of
-  // `nxt`, so sub-step 3 already reads the first fragments of `nxt`, and the next step may overwrite
-  // `cur`.  No branches: the last steps fetch a clamped, redundant tile and deposit it where nobody reads.
-  bf16x8 wf[2][4], xf[2][4];
-  auto read_pair = [&](const uint16_t* stage_ptr, int kk, int buf, int i) {     // i = 0..3: two of the 8 fragments
-    if (i < 2) {
-      wf[buf][2 * i] = lds_read8(stage_ptr + woff[2 * i] + kk * 16);
-      wf[buf][2 * i + 1] = lds_read8(stage_ptr + woff[2 * i + 1] + kk * 16);
-    } else {
-      xf[buf][2 * (i - 2)] = lds_read8(stage_ptr + xoff[2 * (i - 2)] + kk * 16);
-      xf[buf][2 * (i - 2) + 1] = lds_read8(stage_ptr + xoff[2 * (i - 2) + 1] + kk * 16);
-    }
+  // One k step = 4 sub-steps of 4 kNB matrix instructions (k = 16 each) on stage `cur`.  Issue order is
+  // written out by hand and fenced (with one wave per SIMD nothing but the order hides latencies): in
+  // front of every matrix instruction go at most three memory instructions, so that their issue hides
+  // under the previous matrix instruction: one LDS read of the NEXT sub-step's fragments
+  // (double-buffered) in each of the first slots; in sub-step 0 the LDS writes that move register set
+  // `st` (tile kt + 1) to stage `nxt`; in sub-step 1 the global loads that refill `st` with tile
+  // kt + 3.  The workgroup barrier sits before sub-step 3: by then this wave has read all of `cur` and
+  // written its share of `nxt`, so sub-step 3 already reads the first fragments of `nxt`, and the next
+  // step may overwrite `cur`.  No branches: the last steps fetch a clamped, redundant tile and deposit
+  // it where nobody reads.
+  bf16x8 wf[2][kNB], xf[2][4];
+  // Fragment i of sub-step kk: i = 0..3 token fragments, then the weight fragments.
+  auto read_frag = [&](const uint16_t* stage_ptr, int kk, int buf, int i) {
+    if (i < 4) xf[buf][i] = lds_read8(stage_ptr + xoff[i] + kk * 16);
+    else wf[buf][i - 4] = lds_read8(stage_ptr + woff[i - 4] + kk * 16);
   };
 #pragma unroll
-  for (int i = 0; i < 4; ++i) read_pair(smem, 0, 0, i);
-  auto step = [&](const uint16_t* cur, uint16_t* nxt, u32x4 (&st)[16], int k_fetch) {
+  for (int i = 0; i < kFrags; ++i) read_frag(smem, 0, 0, i);
+  auto step = [&](const uint16_t* cur, uint16_t* nxt, u32x4 (&st)[kLoads], int k_fetch) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       if (kk == 3) __syncthreads();
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        // x fragments of the next sub-step first (all four are needed by its first group), then w
-        if (kk < 3) read_pair(cur, kk + 1, (kk + 1) & 1, (q + 2) & 3);
-        else read_pair(nxt, 0, 0, (q + 2) & 3);
-        if (kk == 0 && FFN_DIAG < 2) {
+      for (int q = 0; q < kNB; ++q) {
 #pragma unroll
-          for (int p = 4 * q; p < 4 * q + 4; ++p)
-            *reinterpret_cast<u32x4*>(&nxt[(32 * p + lrow) * kPitch + lchunk]) = st[p];
+        for (int mb = 0; mb < 4; ++mb) {
+          const int slot = 4 * q + mb;
+          if (slot < kFrags) {
+            if (kk < 3) read_frag(cur, kk + 1, (kk + 1) & 1, slot);
+            else read_frag(nxt, 0, 0, slot);
+          }
+#pragma unroll
+          for (int i = slot; i < kLoads; i += kSlots) {
+            if (kk == 0) deposit_one(st, i, nxt);
+            if (kk == 1) fetch_one(st, i, k_fetch);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        if (kk == 1 && FFN_DIAG < 1) {
-#pragma unroll
-          for (int p = 2 * q; p < 2 * q + 2; ++p) fetch_one(st, p, k_fetch);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
   };
@@ -179,39 +200,54 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   }
   __syncthreads();
 
-  // Epilogue.  The stage that the last step did not read is free: one 128-token x 64-column slab per wave.
+  // Epilogue: through a wave-private slab of 128 tokens x 64 columns (both stages are free now), two
+  // 32-column accumulator blocks at a time (the last pass of an odd kNB has one).
   uint16_t* slab = smem + wave * (128 * kPitch);
-  const int orow = lane >> 3, ocol = (lane & 7) * 8;
   const int row_base = m0 + wm * 128;
-  constexpr int kHalves = kGated ? 1 : 2;
+  constexpr int kOutBlocks = kGated ? 2 : kNB;      // 32-column output blocks per wave
 #pragma unroll
-  for (int half = 0; half < kHalves; ++half) {
+  for (int b0 = 0; b0 < kOutBlocks; b0 += 2) {
+    constexpr int kTwo = 2;
+    const int nblk = (kOutBlocks - b0) < kTwo ? (kOutBlocks - b0) : kTwo;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
+      if (nb < nblk) {
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb) {
+        for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          float r[4];
+          for (int j = 0; j < 4; ++j) {
+            float r[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if (kGated) r[i] = gelu_exact(acc[nb][mb][4 * j + i]) * acc[nb + 2][mb][4 * j + i];
-            else r[i] = acc[2 * half + nb][mb][4 * j + i];
+            for (int i = 0; i < 4; ++i) {
+              if (kGated) r[i] = gelu_exact(acc[nb][mb][4 * j + i]) * acc[nb + 2][mb][4 * j + i];
+              else r[i] = acc[b0 + nb][mb][4 * j + i];
+            }
+            u32x2 w;
+            w[0] = pack_bf16(r[0], r[1]);
+            w[1] = pack_bf16(r[2], r[3]);
+            *reinterpret_cast<u32x2*>(&slab[(mb * 32 + c) * kPitch + nb * 32 + 8 * j + 4 * g]) = w;
           }
-          u32x2 w;
-          w[0] = pack_bf16(r[0], r[1]);
-          w[1] = pack_bf16(r[2], r[3]);
-          *reinterpret_cast<u32x2*>(&slab[(mb * 32 + c) * kPitch + nb * 32 + 8 * j + 4 * g]) = w;
         }
       }
     }
     // (same wave wrote and reads the slab: LDS operations of one wave complete in order)
-    const int col = n0 + (kGated ? wn * 64 : wn * 128 + half * 64) + ocol;
+    const int col0 = n0 + wn * (32 * kOutBlocks) + b0 * 32;
+    if (nblk == 2) {                // rows of 64 columns = 128 bytes = 8 lanes
+      const int orow = lane >> 3, ocol = (lane & 7) * 8;
 #pragma unroll
-    for (int it = 0; it < 16; ++it) {
-      const int row = 8 * it + orow;
-      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
-      if (row_base + row < T) *reinterpret_cast<u32x4*>(out + (int64_t)(row_base + row) * ldo + col) = w;
+      for (int it = 0; it < 16; ++it) {
+        const int row = 8 * it + orow;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+        if (row_base + row < T) *reinterpret_cast<u32x4*>(out + (int64_t)(row_base + row) * ldo + col0 + ocol) = w;
+      }
+    } else {                        // rows of 32 columns = 64 bytes = 4 lanes
+      const int orow = lane >> 2, ocol = (lane & 3) * 8;
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = 16 * it + orow;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+        if (row_base + row < T) *reinterpret_cast<u32x4*>(out + (int64_t)(row_base + row) * ldo + col0 + ocol) = w;
+      }
     }
   }
 }
@@ -223,16 +259,28 @@ mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T
   if (T_cap == 0) return MB_OK;
   const int m_tiles = (T_cap + kBM - 1) / kBM;
   {
-    const int n_tiles = inter / (kBN / 2);
-    ffn_gemm_kernel<true><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+    const int n_tiles = inter / 128;
+    ffn_gemm_kernel<true, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
         static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
         2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter);
   }
-  {
-    const int n_tiles = hidden / kBN;
-    ffn_gemm_kernel<false><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
-        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden, T_cap,
-        meta, static_cast<uint16_t*>(y), hidden);
+  // Second projection: few column tiles.  Pick the tile width (256 or 192 weight rows) that wastes less of
+  // the last round of workgroups on the 256 compute units.
+  const auto cost = [&](int bn) {
+    const int tiles = m_tiles * (hidden / bn);
+    return (double)((tiles + 255) / 256) * bn;
+  };
+  const bool narrow = hidden % 192 == 0 && (hidden % 256 != 0 || cost(192) < cost(256));
+  if (narrow) {
+    const int n_tiles = hidden / 192;
+    ffn_gemm_kernel<false, 3><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden,
+        T_cap, meta, static_cast<uint16_t*>(y), hidden);
+  } else {
+    const int n_tiles = hidden / 256;
+    ffn_gemm_kernel<false, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden,
+        T_cap, meta, static_cast<uint16_t*>(y), hidden);
   }
   return check_launch("ffn_gemm_kernel");
 }
