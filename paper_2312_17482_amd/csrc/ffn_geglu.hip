@@ -20,6 +20,10 @@
 #include "common.h"
 #include "mfma_util.h"
 
+#ifndef FFN_DIAG
+#define FFN_DIAG 0
+#endif
+
 
 namespace mb {
 namespace {
@@ -32,20 +36,19 @@ constexpr int kGroupM = 4;                            // token panels walked tog
 // GeLU(h) = h * Phi(h), the exact (error-function) form, with Phi evaluated by the classic five-term
 // rational approximation of erfc (Abramowitz & Stegun 7.1.26, absolute error below 1.5e-7):
 //   x = |h| / sqrt 2,  t = 1 / (1 + p x),  u = (1/2) (a1 t + ... + a5 t^5) exp(-x^2) = Phi(-|h|),
-//   Phi(h) = u for h < 0 and 1 - u otherwise.
-// About 17 vector instructions per value, two of them transcendental; the result is rounded to bf16
-// (relative 2^-9) right after, so the approximation error is invisible.
+//   Phi(h) = u for h < 0 and 1 - u otherwise,  hence  h Phi(h) = max(h, 0) - |h| u  for either sign.
+// 12 vector instructions and two transcendentals per value; the result is rounded to bf16 (relative
+// 2^-9) right after, so the approximation error is invisible.
 __device__ __forceinline__ float gelu_exact(float h) {
-  const float x = fabsf(h) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+  const float ah = fabsf(h);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, ah, 1.0f));
   float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
   poly = fmaf(poly, t, 0.5f * 1.421413741f);
   poly = fmaf(poly, t, 0.5f * -0.284496736f);
   poly = fmaf(poly, t, 0.5f * 0.254829592f);
   const float e = __builtin_amdgcn_exp2f(h * h * (-0.5f * kLog2e));
   const float u = poly * t * e;                       // Phi(-|h|), in (0, 1/2]
-  const float phi = 0.5f + copysignf(0.5f - u, h);
-  return h * phi;
+  return fmaf(-ah, u, fmaxf(h, 0.0f));
 }
 
 template <bool kGated, int kNB>   // kNB: 32-row weight blocks per wave (4 or 3); workgroup = 64 * kNB weight rows
@@ -184,8 +187,15 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
           }
 #pragma unroll
           for (int i = slot; i < kLoads; i += kSlots) {
+#if FFN_DIAG == 0
             if (kk == 0) deposit_one(st, i, nxt);
             if (kk == 1) fetch_one(st, i, k_fetch);
+#elif FFN_DIAG == 1   /* LDS writes of stale registers, no loads */
+            if (kk == 0) deposit_one(st, i, nxt);
+#elif FFN_DIAG == 3   /* loads, consumed without an LDS write */
+            if (kk == 0) asm volatile("" ::"v"(st[i]));
+            if (kk == 1) fetch_one(st, i, k_fetch);
+#endif
           }
           __builtin_amdgcn_sched_barrier(0);
           acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
