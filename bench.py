@@ -231,6 +231,8 @@ def main():
 
     out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev),
                         "padded_attention_comparison": time_padded_vs_varlen(mb, locals())}
+    if bf16 and (H * D) % 256 == 0:
+        out["next_rows"]["geglu_ffn_fwd_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
     if args.copy_calibration:
@@ -283,6 +285,31 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
     res["shape"] = "T=%d W=%d" % (T, W)
     return res
+
+
+def time_geglu(mb, T, hidden, inter, dev):
+    """GeGLU feed-forward, forward, on the packed tokens of the same batch ([T, hidden] -> [T, inter] ->
+    [T, hidden]), outside the timed step: 20 launches between two events.  Flops: 2 T hidden 2 inter for the
+    fused first projection + 2 T inter hidden for the second, against the dense bf16 matrix-core peak."""
+    import torch
+    x = torch.randn(T, hidden, device=dev).to(torch.bfloat16)
+    w1v = (torch.randn(2 * inter, hidden, device=dev) * 0.02).to(torch.bfloat16)
+    w2 = (torch.randn(hidden, inter, device=dev) * 0.02).to(torch.bfloat16)
+    act = torch.empty((T, inter), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((T, hidden), dtype=torch.bfloat16, device=dev)
+    for _ in range(3):
+        mb.mb_geglu_fwd(x, w1v, w2, act=act, y=y)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(20):
+        mb.mb_geglu_fwd(x, w1v, w2, act=act, y=y)
+    b.record()
+    torch.cuda.synchronize()
+    us = a.elapsed_time(b) * 1e3 / 20
+    flops = 2.0 * T * hidden * 2 * inter + 2.0 * T * inter * hidden
+    return {"us": round(us, 1), "tflops": round(flops / us * 1e-6, 1),
+            "frac_of_bf16_mfma_peak": round(flops / us * 1e-6 / PEAK_BF16_TFLOPS, 4),
+            "shape": "T=%d hidden=%d inter=%d" % (T, hidden, inter)}
 
 
 def time_padded_vs_varlen(mb, g):

@@ -20,9 +20,6 @@
 #include "common.h"
 #include "mfma_util.h"
 
-#ifndef FFN_DIAG
-#define FFN_DIAG 0
-#endif
 
 
 namespace mb {
@@ -67,12 +64,15 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
 
   // (readfirstlane: tells the compiler the value is wave-uniform, so descriptors built from it stay scalar)
   const int T = __builtin_amdgcn_readfirstlane(meta ? min(meta[0], T_cap) : T_cap);
-  const int m_tiles = (T_cap + kBM - 1) / kBM;
+  // (the grid is sized for T_cap rows; the tile map uses the token panels that hold tokens, so that the
+  // idle workgroups are the last ones and not the share of one XCD)
+  const int m_tiles = (T + kBM - 1) / kBM;
+  if ((int)blockIdx.x >= m_tiles * n_tiles) return;
 
   // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs; give every XCD a
   // contiguous run of tiles, walked kGroupM token panels at a time, so that the tiles resident on one
   // XCD share their token panels and weight tiles in that XCD's L2.
-  const int total = gridDim.x, per = total >> 3;
+  const int total = m_tiles * n_tiles, per = total >> 3;
   int lin = blockIdx.x;
   if (lin < (per << 3)) lin = (lin & 7) * per + (lin >> 3);
   const int group = lin / (kGroupM * n_tiles);
@@ -144,12 +144,13 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
       for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
   const int nk = K / kBK;                       // even (the host checks K % 128 == 0)
+  // (the first two k steps are requested together, so that only one memory latency is exposed)
 #pragma unroll
   for (int i = 0; i < kLoads; ++i) fetch_one(st0, i, 0);
 #pragma unroll
-  for (int i = 0; i < kLoads; ++i) deposit_one(st0, i, smem);
-#pragma unroll
   for (int i = 0; i < kLoads; ++i) fetch_one(st1, i, kBK);
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) deposit_one(st0, i, smem);
 #pragma unroll
   for (int i = 0; i < kLoads; ++i) fetch_one(st0, i, min(2, nk - 1) * kBK);
   __syncthreads();
@@ -187,15 +188,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
           }
 #pragma unroll
           for (int i = slot; i < kLoads; i += kSlots) {
-#if FFN_DIAG == 0
             if (kk == 0) deposit_one(st, i, nxt);
             if (kk == 1) fetch_one(st, i, k_fetch);
-#elif FFN_DIAG == 1   /* LDS writes of stale registers, no loads */
-            if (kk == 0) deposit_one(st, i, nxt);
-#elif FFN_DIAG == 3   /* loads, consumed without an LDS write */
-            if (kk == 0) asm volatile("" ::"v"(st[i]));
-            if (kk == 1) fetch_one(st, i, k_fetch);
-#endif
           }
           __builtin_amdgcn_sched_barrier(0);
           acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
