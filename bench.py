@@ -289,27 +289,54 @@ def time_layernorm(mb, T, W, tdt, dev):
 
 def time_geglu(mb, T, hidden, inter, dev):
     """GeGLU feed-forward, forward, on the packed tokens of the same batch ([T, hidden] -> [T, inter] ->
-    [T, hidden]), outside the timed step: 20 launches between two events.  Flops: 2 T hidden 2 inter for the
-    fused first projection + 2 T inter hidden for the second, against the dense bf16 matrix-core peak."""
+    [T, hidden]), outside the timed step: 20 launches of each arrangement between two events.
+    fused = mb_geglu_fwd (the activation runs on the accumulators of the first projection); the two
+    unfused arrangements of the paper's appendix on GLU implementations are built from the same GEMM
+    kernel: `sliced` = one double-width projection stored and sliced, `separate` = two projections; both
+    then run the activation as a pass of its own.  Flops: 2 T hidden 2 inter + 2 T inter hidden."""
     import torch
-    x = torch.randn(T, hidden, device=dev).to(torch.bfloat16)
-    w1v = (torch.randn(2 * inter, hidden, device=dev) * 0.02).to(torch.bfloat16)
-    w2 = (torch.randn(hidden, inter, device=dev) * 0.02).to(torch.bfloat16)
-    act = torch.empty((T, inter), dtype=torch.bfloat16, device=dev)
-    y = torch.empty((T, hidden), dtype=torch.bfloat16, device=dev)
-    for _ in range(3):
+    bf = torch.bfloat16
+    x = torch.randn(T, hidden, device=dev).to(bf)
+    w1v = (torch.randn(2 * inter, hidden, device=dev) * 0.02).to(bf)
+    w1, v = w1v[:inter].contiguous(), w1v[inter:].contiguous()
+    w2 = (torch.randn(hidden, inter, device=dev) * 0.02).to(bf)
+    act = torch.empty((T, inter), dtype=bf, device=dev)
+    y = torch.empty((T, hidden), dtype=bf, device=dev)
+    hg = torch.empty((T, 2 * inter), dtype=bf, device=dev)
+    h, g = torch.empty((T, inter), dtype=bf, device=dev), torch.empty((T, inter), dtype=bf, device=dev)
+
+    def fused():
         mb.mb_geglu_fwd(x, w1v, w2, act=act, y=y)
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(20):
-        mb.mb_geglu_fwd(x, w1v, w2, act=act, y=y)
-    b.record()
-    torch.cuda.synchronize()
-    us = a.elapsed_time(b) * 1e3 / 20
+
+    def sliced():
+        mb.mb_linear_fwd(x, w1v, y=hg)
+        mb.mb_gelu_gate(hg[:, :inter], hg[:, inter:], act=act)
+        mb.mb_linear_fwd(act, w2, y=y)
+
+    def separate():
+        mb.mb_linear_fwd(x, w1, y=h)
+        mb.mb_linear_fwd(x, v, y=g)
+        mb.mb_gelu_gate(h, g, act=act)
+        mb.mb_linear_fwd(act, w2, y=y)
+
     flops = 2.0 * T * hidden * 2 * inter + 2.0 * T * inter * hidden
-    return {"us": round(us, 1), "tflops": round(flops / us * 1e-6, 1),
-            "frac_of_bf16_mfma_peak": round(flops / us * 1e-6 / PEAK_BF16_TFLOPS, 4),
-            "shape": "T=%d hidden=%d inter=%d" % (T, hidden, inter)}
+    res = {"shape": "T=%d hidden=%d inter=%d" % (T, hidden, inter)}
+    for name, fn in (("fused", fused), ("sliced", sliced), ("separate", separate)):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / 20
+        res[name + "_us"] = round(us, 1)
+        res[name + "_tflops"] = round(flops / us * 1e-6, 1)
+    res["frac_of_bf16_mfma_peak"] = round(res["fused_tflops"] / PEAK_BF16_TFLOPS, 4)
+    res["unfused_slowdown"] = {"sliced": round(res["sliced_us"] / res["fused_us"], 3),
+                               "separate": round(res["separate_us"] / res["fused_us"], 3)}
+    return res
 
 
 def time_padded_vs_varlen(mb, g):

@@ -223,6 +223,25 @@ MB_API mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void*
 MB_API mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta_dev,
                               int hidden, int inter, mb_dtype dt, void* act, void* y, void* stream);
 
+/*
+ * The pieces of the UNFUSED arrangements of the same sublayer (appendix on GLU implementations: two separate
+ * input projections, or one of twice the width whose product is stored and sliced), for comparison with
+ * mb_geglu_fwd, which never stores the projections:
+ *
+ * mb_linear_fwd:  y = x W for a bias-free linear layer.
+ *   x   dev, [T_cap, n_in], read.      wt  dev, [n_out, n_in], read: W transposed.      y  dev, [T_cap, n_out], written.
+ *   Supported: MB_BF16, n_in a multiple of 128, n_out a multiple of 256 or of 192 (MB_ERR_UNSUPPORTED otherwise).
+ * mb_gelu_gate:   act = GeLU(h) (*) gate, elementwise, exact-form GeLU.
+ *   h, gate  dev, [T_cap, inter] blocks with a common row stride `row_stride` (elements): two separate buffers
+ *            (row_stride = inter) or the two halves of one [T_cap, 2*inter] buffer (gate = h + inter, row_stride =
+ *            2*inter).  act  dev, [T_cap, inter] contiguous, written.  inter and row_stride multiples of 8.
+ * Rows [0, T), T = min(meta_dev[0], T_cap) or T_cap if meta_dev is NULL; pointers 16-byte aligned.
+ */
+MB_API mb_status mb_linear_fwd(const void* x, const void* wt, int T_cap, const int32_t* meta_dev, int n_in, int n_out,
+                               mb_dtype dt, void* y, void* stream);
+MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_stride, int T_cap, const int32_t* meta_dev,
+                              int inter, mb_dtype dt, void* act, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -240,6 +240,16 @@ def gelu_grad(z: np.ndarray) -> np.ndarray:
     return 0.5 * (1.0 + erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
 
 
+def linear_fwd(x, wt):
+    """Bias-free linear layer y = x W with wt = W transposed ([out_features, in_features]); float64."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(wt, dtype=np.float64).T
+
+
+def gelu_gate(h, g):
+    """GeLU(h) (*) g, elementwise: the activation of Eq. 2 between the projections."""
+    return gelu(h) * np.asarray(g, dtype=np.float64)
+
+
 def geglu_fwd(x, w1, v, w2):
     """Eq. 2:  y = (GeLU(x W1) (*) x V) W2, no bias terms, float64.
 

@@ -24,7 +24,7 @@ MB_F32, MB_BF16 = 0, 1
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
            "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
-           "mb_add_layernorm_bwd", "mb_geglu_fwd")
+           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_linear_fwd", "mb_gelu_gate")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -61,6 +61,10 @@ _lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
 _lib.mb_add_layernorm_bwd.restype = c_int
 _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.mb_linear_fwd.restype = c_int
+_lib.mb_linear_fwd.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]
+_lib.mb_gelu_gate.restype = c_int
+_lib.mb_gelu_gate.argtypes = [c_void_p, c_void_p, c_int64, c_int, c_void_p, c_int, c_int, c_void_p, c_void_p]
 _lib.mb_geglu_fwd.restype = c_int
 _lib.mb_geglu_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p,
                               c_void_p]
@@ -261,3 +265,27 @@ def mb_geglu_fwd(x, w1v, w2, T_cap=None, meta=None, act=None, y=None):
     _check(_lib.mb_geglu_fwd(_ptr(x), _ptr(w1v), _ptr(w2), T_cap, _ptr(meta), hidden, inter, _dtype_code(x),
                              _ptr(act), _ptr(y), _stream()))
     return y, act
+
+
+def mb_linear_fwd(x, wt, T_cap=None, meta=None, y=None):
+    """y = x @ wt.T for x [rows, n_in], wt [n_out, n_in]."""
+    assert x.dim() == 2 and x.is_contiguous() and wt.is_contiguous() and wt.shape[1] == x.shape[1]
+    rows, n_in = x.shape
+    n_out = wt.shape[0]
+    T_cap = rows if T_cap is None else T_cap
+    y = torch.empty((rows, n_out), dtype=x.dtype, device=x.device) if y is None else y
+    _check(_lib.mb_linear_fwd(_ptr(x), _ptr(wt), T_cap, _ptr(meta), n_in, n_out, _dtype_code(x), _ptr(y), _stream()))
+    return y
+
+
+def mb_gelu_gate(h, gate, T_cap=None, meta=None, act=None):
+    """act = GeLU(h) * gate; h and gate are [rows, inter] views with the same row stride (two buffers, or
+    the halves of one [rows, 2*inter] buffer)."""
+    assert h.dim() == 2 and h.shape == gate.shape and h.stride(1) == 1 and gate.stride(1) == 1
+    assert h.stride(0) == gate.stride(0)
+    rows, inter = h.shape
+    T_cap = rows if T_cap is None else T_cap
+    act = torch.empty((rows, inter), dtype=h.dtype, device=h.device) if act is None else act
+    _check(_lib.mb_gelu_gate(_ptr(h), _ptr(gate), h.stride(0), T_cap, _ptr(meta), inter, _dtype_code(h), _ptr(act),
+                             _stream()))
+    return act

@@ -358,4 +358,40 @@ mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap
   return launch_geglu_fwd(x, w1v, w2, T_cap, meta_dev, hidden, inter, act, y, (hipStream_t)stream);
 }
 
+mb_status mb_linear_fwd(const void* x, const void* wt, int T_cap, const int32_t* meta_dev, int n_in, int n_out,
+                        mb_dtype dt, void* y, void* stream) {
+  clear_error();
+  MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap must be >= 0 (got %d)", T_cap);
+  MB_REQUIRE(n_in > 0 && n_out > 0, MB_ERR_INVALID_ARG, "n_in and n_out must be positive (got %d, %d)", n_in, n_out);
+  MB_REQUIRE(dt == MB_BF16, MB_ERR_UNSUPPORTED, "the feed-forward kernels are bf16 only");
+  MB_REQUIRE(n_in % 128 == 0 && (n_out % 256 == 0 || n_out % 192 == 0), MB_ERR_UNSUPPORTED,
+             "n_in must be a multiple of 128 and n_out a multiple of 256 or 192 (got %d, %d)", n_in, n_out);
+  MB_REQUIRE((int64_t)T_cap * (int64_t)(n_in > n_out ? n_in : n_out) < ((int64_t)1 << 31) &&
+                 (int64_t)n_in * (int64_t)n_out < ((int64_t)1 << 31),
+             MB_ERR_UNSUPPORTED, "tensor of 2^31 elements or more (T_cap=%d n_in=%d n_out=%d)", T_cap, n_in, n_out);
+  if (T_cap == 0) return MB_OK;
+  MB_CHECK_PTR(x);
+  MB_CHECK_PTR(wt);
+  MB_CHECK_PTR(y);
+  return launch_linear_fwd(x, wt, T_cap, meta_dev, n_in, n_out, y, (hipStream_t)stream);
+}
+
+mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_stride, int T_cap, const int32_t* meta_dev,
+                       int inter, mb_dtype dt, void* act, void* stream) {
+  clear_error();
+  MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap must be >= 0 (got %d)", T_cap);
+  MB_REQUIRE(inter > 0, MB_ERR_INVALID_ARG, "inter must be positive (got %d)", inter);
+  MB_REQUIRE(dt == MB_BF16, MB_ERR_UNSUPPORTED, "the feed-forward kernels are bf16 only");
+  MB_REQUIRE(inter % 8 == 0 && row_stride % 8 == 0 && row_stride >= inter, MB_ERR_INVALID_ARG,
+             "inter and row_stride must be multiples of 8 with row_stride >= inter (got %d, %lld)", inter,
+             (long long)row_stride);
+  if (T_cap == 0) return MB_OK;
+  MB_CHECK_PTR(h);
+  MB_CHECK_PTR(gate);
+  MB_CHECK_PTR(act);
+  return launch_gelu_gate(h, gate, row_stride, T_cap, meta_dev, inter, act, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -67,6 +67,12 @@ static constexpr int kLayerNormMaxParts = 1024;
 // GeGLU feed-forward, forward (bf16; hidden a multiple of 256, inter a multiple of 128).
 mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta,
                            int hidden, int inter, void* act, void* y, hipStream_t stream);
+// The pieces of the unfused arrangements: a bias-free projection y = x wt^T (n_in a multiple of 128, n_out a
+// multiple of 256 or of 192) and the activation pass act = GeLU(h) (*) gate over rows of stride ld.
+mb_status launch_linear_fwd(const void* x, const void* wt, int T_cap, const int32_t* meta, int n_in, int n_out,
+                            void* y, hipStream_t stream);
+mb_status launch_gelu_gate(const void* h, const void* gate, int64_t ld, int T_cap, const int32_t* meta, int inter,
+                           void* act, hipStream_t stream);
 
 mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
                                    int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,

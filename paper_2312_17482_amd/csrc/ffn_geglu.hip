@@ -256,37 +256,85 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   }
 }
 
+// a = GeLU(h) (*) g, elementwise over [T, inter]: the separate activation pass of the unfused arrangements
+// (the fused path above never runs it).  One 16-byte piece of h and of g per thread; HBM-bound.
+__global__ __launch_bounds__(256) void gelu_gate_kernel(const uint16_t* __restrict__ h,
+                                                        const uint16_t* __restrict__ gate, int64_t ld, int T_cap,
+                                                        const int32_t* __restrict__ meta, int inter,
+                                                        uint16_t* __restrict__ act) {
+  const int T = meta ? min(meta[0], T_cap) : T_cap;
+  const int pieces = inter >> 3;
+  const int64_t total = (int64_t)T * pieces;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = idx / pieces;
+    const int col = (int)(idx - row * pieces) * 8;
+    const u32x4 hv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(h + row * ld + col));
+    const u32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gate + row * ld + col));
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float h0 = __uint_as_float(hv[i] << 16), h1 = __uint_as_float(hv[i] & 0xffff0000u);
+      const float g0 = __uint_as_float(gv[i] << 16), g1 = __uint_as_float(gv[i] & 0xffff0000u);
+      r[i] = pack_bf16(gelu_exact(h0) * g0, gelu_exact(h1) * g1);
+    }
+    *reinterpret_cast<u32x4*>(act + row * (int64_t)inter + col) = r;
+  }
+}
+
 }  // namespace
+
+// out[t, n] = sum_k x[t, k] * wt[n, k] with the plain epilogue; the tile width (256 or 192 weight rows) is the
+// one that wastes less of the last round of workgroups on the 256 compute units.
+static void launch_plain(const void* x, const void* wt, int T_cap, const int32_t* meta, int n_in, int n_out, void* y,
+                         hipStream_t stream) {
+  const int m_tiles = (T_cap + kBM - 1) / kBM;
+  const auto cost = [&](int bn) {
+    const int tiles = m_tiles * (n_out / bn);
+    return (double)((tiles + 255) / 256) * bn;
+  };
+  const bool narrow = n_out % 192 == 0 && (n_out % 256 != 0 || cost(192) < cost(256));
+  if (narrow) {
+    const int n_tiles = n_out / 192;
+    ffn_gemm_kernel<false, 3><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(x), n_in, static_cast<const uint16_t*>(wt), n_in, n_in, n_tiles, 0, n_out, T_cap,
+        meta, static_cast<uint16_t*>(y), n_out);
+  } else {
+    const int n_tiles = n_out / 256;
+    ffn_gemm_kernel<false, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(x), n_in, static_cast<const uint16_t*>(wt), n_in, n_in, n_tiles, 0, n_out, T_cap,
+        meta, static_cast<uint16_t*>(y), n_out);
+  }
+}
 
 mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta,
                            int hidden, int inter, void* act, void* y, hipStream_t stream) {
   if (T_cap == 0) return MB_OK;
   const int m_tiles = (T_cap + kBM - 1) / kBM;
-  {
-    const int n_tiles = inter / 128;
-    ffn_gemm_kernel<true, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
-        static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
-        2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter);
-  }
-  // Second projection: few column tiles.  Pick the tile width (256 or 192 weight rows) that wastes less of
-  // the last round of workgroups on the 256 compute units.
-  const auto cost = [&](int bn) {
-    const int tiles = m_tiles * (hidden / bn);
-    return (double)((tiles + 255) / 256) * bn;
-  };
-  const bool narrow = hidden % 192 == 0 && (hidden % 256 != 0 || cost(192) < cost(256));
-  if (narrow) {
-    const int n_tiles = hidden / 192;
-    ffn_gemm_kernel<false, 3><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
-        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden,
-        T_cap, meta, static_cast<uint16_t*>(y), hidden);
-  } else {
-    const int n_tiles = hidden / 256;
-    ffn_gemm_kernel<false, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
-        static_cast<const uint16_t*>(act), inter, static_cast<const uint16_t*>(w2), inter, inter, n_tiles, 0, hidden,
-        T_cap, meta, static_cast<uint16_t*>(y), hidden);
-  }
+  const int n_tiles = inter / 128;
+  ffn_gemm_kernel<true, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+      static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
+      2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter);
+  launch_plain(act, w2, T_cap, meta, inter, hidden, y, stream);
   return check_launch("ffn_gemm_kernel");
+}
+
+mb_status launch_linear_fwd(const void* x, const void* wt, int T_cap, const int32_t* meta, int n_in, int n_out,
+                            void* y, hipStream_t stream) {
+  if (T_cap == 0) return MB_OK;
+  launch_plain(x, wt, T_cap, meta, n_in, n_out, y, stream);
+  return check_launch("ffn_gemm_kernel");
+}
+
+mb_status launch_gelu_gate(const void* h, const void* gate, int64_t ld, int T_cap, const int32_t* meta, int inter,
+                           void* act, hipStream_t stream) {
+  if (T_cap == 0) return MB_OK;
+  const int64_t pieces = (int64_t)T_cap * (inter >> 3);
+  const int blocks = (int)((pieces + 255) / 256 < 8192 ? (pieces + 255) / 256 : 8192);
+  gelu_gate_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(static_cast<const uint16_t*>(h),
+                                                           static_cast<const uint16_t*>(gate), ld, T_cap, meta, inter,
+                                                           static_cast<uint16_t*>(act));
+  return check_launch("gelu_gate_kernel");
 }
 
 }  // namespace mb

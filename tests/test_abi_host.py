@@ -178,3 +178,19 @@ def test_geglu_rejects_bad_arguments():
     assert f(A, A, A, 16, None, 768, 3072, mb.MB_BF16, A, None, None) == mb.MB_ERR_INVALID_ARG
     assert f(A + 8, A, A, 16, None, 768, 3072, mb.MB_BF16, A, A, None) == mb.MB_ERR_INVALID_ARG
     assert f(None, None, None, 0, None, 768, 3072, mb.MB_BF16, None, None, None) == mb.MB_OK
+
+
+def test_linear_and_gelu_gate_reject_bad_arguments():
+    f = lib.mb_linear_fwd
+    assert f(A, A, 16, None, 768, 3072, mb.MB_F32, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, 16, None, 700, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, 16, None, 768, 3000, mb.MB_BF16, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, -2, None, 768, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, None, 16, None, 768, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert f(None, None, 0, None, 768, 3072, mb.MB_BF16, None, None) == mb.MB_OK
+    g = lib.mb_gelu_gate
+    assert g(A, A, 3072, 16, None, 3072, mb.MB_F32, A, None) == mb.MB_ERR_UNSUPPORTED
+    assert g(A, A, 3070, 16, None, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert g(A, A, 3072, 16, None, 3076, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert g(A, A + 2, 3072, 16, None, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
+    assert g(None, None, 3072, 0, None, 3072, mb.MB_BF16, None, None) == mb.MB_OK

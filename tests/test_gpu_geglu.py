@@ -97,3 +97,60 @@ def test_geglu_empty_input(mb):
     mb.mb_geglu_fwd(xx, w1v, w2, meta=meta, act=aa, y=yy)
     torch.cuda.synchronize()
     assert torch.all(yy == 9.0) and torch.all(aa == 9.0)
+
+
+@pytest.mark.parametrize("T,n_in,n_out", [(300, 768, 6144), (513, 3072, 768), (64, 128, 192), (1000, 256, 1024),
+                                          (257, 640, 384)])
+def test_linear_forward_parity(mb, T, n_in, n_out):
+    print("linear T=%d n_in=%d n_out=%d" % (T, n_in, n_out), flush=True)
+    rng = np.random.default_rng(21)
+    x = wl.round_to_bf16(rng.standard_normal((T, n_in), dtype=np.float32))
+    wt = wl.round_to_bf16(rng.standard_normal((n_out, n_in), dtype=np.float32) / np.float32(np.sqrt(n_in)))
+    y = torch.full((T + 2, n_out), 9.0, dtype=torch.bfloat16, device="cuda")
+    mb.mb_linear_fwd(dev(x), dev(wt), y=y[:T])
+    torch.cuda.synchronize()
+    assert torch.all(y[T:] == 9.0)
+    check("y", y[:T], orc.linear_fwd(x, wt), wide=True)
+
+
+def test_gelu_gate_parity_and_unfused_arrangements(mb):
+    """The activation pass alone, and the two unfused arrangements of the appendix on GLU implementations
+    (two projections; one double-width projection, sliced) against the oracle and against the fused call."""
+    print("gelu gate / unfused arrangements", flush=True)
+    T, hidden, inter = 900, 768, 3072
+    case = wl.random_ffn_case(22, T, hidden, inter)
+    x, w1v, w2 = case["x"], case["w1v"], case["w2"]
+    y_ref, a_ref = orc.geglu_fwd(x, w1v[:inter], w1v[inter:], w2)
+    xd, wd, w2d = dev(x), dev(w1v), dev(w2)
+    # activation pass on given h, g (wide range, both signs)
+    rng = np.random.default_rng(23)
+    h = wl.round_to_bf16(rng.standard_normal((T, inter), dtype=np.float32) * 2.5)
+    g = wl.round_to_bf16(rng.standard_normal((T, inter), dtype=np.float32))
+    act = mb.mb_gelu_gate(dev(h), dev(g))
+    check("gelu_gate", act, orc.gelu_gate(h, g), wide=True)
+    # (C) one double-width projection, stored and sliced
+    hg = mb.mb_linear_fwd(xd, wd)
+    act_c = mb.mb_gelu_gate(hg[:, :inter], hg[:, inter:])
+    y_c = mb.mb_linear_fwd(act_c, w2d)
+    # (B) two separate projections
+    h_b = mb.mb_linear_fwd(xd, wd[:inter].contiguous())
+    g_b = mb.mb_linear_fwd(xd, wd[inter:].contiguous())
+    act_b = mb.mb_gelu_gate(h_b, g_b)
+    y_b = mb.mb_linear_fwd(act_b, w2d)
+    y_f, act_f = mb.mb_geglu_fwd(xd, wd, w2d)
+    torch.cuda.synchronize()
+    # (the unfused arrangements store x W1 and x V in bf16 before the activation: one more rounding per
+    # factor than the fused call, hence the bound that scales with the largest value for them)
+    for name, a_, y_, wide in (("sliced", act_c, y_c, True), ("separate", act_b, y_b, True), ("fused", act_f, y_f, False)):
+        check("act " + name, a_, a_ref, wide)
+        check("y " + name, y_, y_ref, wide)
+    assert torch.equal(act_b, act_c) and torch.equal(y_b, y_c)     # same arithmetic, different buffers
+    # capacity mode of the pieces
+    meta = torch.tensor([500, 0], dtype=torch.int32, device="cuda")
+    yy = torch.full((T, inter), 9.0, dtype=torch.bfloat16, device="cuda")
+    mb.mb_linear_fwd(xd, wd[:inter].contiguous(), meta=meta, y=yy)
+    aa = torch.full((T, inter), 9.0, dtype=torch.bfloat16, device="cuda")
+    mb.mb_gelu_gate(hg[:, :inter], hg[:, inter:], meta=meta, act=aa)
+    torch.cuda.synchronize()
+    assert torch.all(yy[500:] == 9.0) and torch.equal(yy[:500], h_b[:500])
+    assert torch.all(aa[500:] == 9.0) and torch.equal(aa[:500], act_c[:500])

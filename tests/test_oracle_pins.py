@@ -492,6 +492,24 @@ def test_geglu_forward_pins():
     np.testing.assert_allclose(orc.geglu_fwd(xi, w1, vi, w2i)[0], orc.gelu(xi @ w1.T), atol=1e-14)
 
 
+def test_unfused_pieces_compose_to_geglu():
+    """The three arrangements of the appendix on GLU implementations are the same function: two separate
+    projections, one double-width projection that is sliced, and Eq. 2 as written."""
+    x, w1, v, w2, _ = _geglu_case(9, 6, 4, 10)
+    y, a = orc.geglu_fwd(x, w1, v, w2)
+    h, g = orc.linear_fwd(x, w1), orc.linear_fwd(x, v)
+    # linear_fwd element by element
+    for t, j in ((0, 0), (5, 9), (3, 4)):
+        assert abs(h[t, j] - sum(x[t, c] * w1[j, c] for c in range(4))) < 1e-14
+    np.testing.assert_allclose(orc.gelu_gate(h, g), a, atol=1e-14)
+    np.testing.assert_allclose(orc.linear_fwd(orc.gelu_gate(h, g), w2), y, atol=1e-13)
+    hg = orc.linear_fwd(x, np.concatenate([w1, v], axis=0))
+    np.testing.assert_allclose(orc.linear_fwd(orc.gelu_gate(hg[:, :10], hg[:, 10:]), w2), y, atol=1e-13)
+    # gelu_gate is GeLU on the first argument only
+    np.testing.assert_allclose(orc.gelu_gate(h, np.ones_like(h)), orc.gelu(h), atol=0)
+    assert np.abs(orc.gelu_gate(g, h) - a).max() > 1e-3
+
+
 def test_geglu_backward_pins():
     x, w1, v, w2, dy = _geglu_case(5, 6, 4, 9)
     dx, dw1, dv, dw2 = orc.geglu_bwd(dy, x, w1, v, w2)
