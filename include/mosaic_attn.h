@@ -242,6 +242,18 @@ MB_API mb_status mb_linear_fwd(const void* x, const void* wt, int T_cap, const i
 MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_stride, int T_cap, const int32_t* meta_dev,
                               int inter, mb_dtype dt, void* act, void* stream);
 
+/*
+ * Ceiling probe for callers that measure (bench.py): enqueues one launch of a kernel that saturates one unit
+ * and does nothing else, and reports the work of that launch; the caller times it.  Not an operation of the
+ * paper: it exists so that the roofs kernels are priced against are measured on the machine at hand.
+ *   kind   0: v_mfma_f32_32x32x16_bf16, independent accumulators (work = flops)
+ *          1: fp32 fused multiply-add on the vector unit (work = flops)
+ *          2: fp32 exponential on the vector unit (work = exponentials)
+ *   iters  rounds per lane (> 0).      out  dev, one float, scratch (never written in practice).
+ *   work_per_launch  host, written.
+ */
+MB_API mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

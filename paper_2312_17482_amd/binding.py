@@ -24,7 +24,7 @@ MB_F32, MB_BF16 = 0, 1
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
            "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
-           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_linear_fwd", "mb_gelu_gate")
+           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -61,6 +61,8 @@ _lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
 _lib.mb_add_layernorm_bwd.restype = c_int
 _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.mb_probe_ceiling.restype = c_int
+_lib.mb_probe_ceiling.argtypes = [c_int, c_int, c_void_p, c_void_p, c_void_p]
 _lib.mb_linear_fwd.restype = c_int
 _lib.mb_linear_fwd.argtypes = [c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]
 _lib.mb_gelu_gate.restype = c_int
@@ -289,3 +291,10 @@ def mb_gelu_gate(h, gate, T_cap=None, meta=None, act=None):
     _check(_lib.mb_gelu_gate(_ptr(h), _ptr(gate), h.stride(0), T_cap, _ptr(meta), inter, _dtype_code(h), _ptr(act),
                              _stream()))
     return act
+
+
+def mb_probe_ceiling(kind: int, iters: int, out) -> float:
+    """Enqueues one probe launch (0: bf16 MFMA, 1: fp32 FMA, 2: fp32 exp); returns its work (flops or exps)."""
+    work = ctypes.c_double(0.0)
+    _check(_lib.mb_probe_ceiling(kind, iters, _ptr(out), ctypes.byref(work), _stream()))
+    return work.value

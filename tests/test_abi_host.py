@@ -194,3 +194,11 @@ def test_linear_and_gelu_gate_reject_bad_arguments():
     assert g(A, A, 3072, 16, None, 3076, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
     assert g(A, A + 2, 3072, 16, None, 3072, mb.MB_BF16, A, None) == mb.MB_ERR_INVALID_ARG
     assert g(None, None, 3072, 0, None, 3072, mb.MB_BF16, None, None) == mb.MB_OK
+
+
+def test_probe_rejects_bad_arguments():
+    w = ctypes.c_double(0.0)
+    assert lib.mb_probe_ceiling(3, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_ceiling(0, 0, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_ceiling(0, 10, None, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_ceiling(0, 10, A, None, None) == mb.MB_ERR_INVALID_ARG
