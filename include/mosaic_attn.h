@@ -223,6 +223,28 @@ MB_API mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void*
 MB_API mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta_dev,
                               int hidden, int inter, mb_dtype dt, void* act, void* y, void* stream);
 
+/* Bytes of device workspace mb_geglu_bwd needs (0 on arguments it would reject). */
+MB_API size_t mb_geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter, mb_dtype dt);
+
+/*
+ * Backward of mb_geglu_fwd for the scalar loss sum(y * dy) (the textbook derivative of Eq. 2; the paper prints
+ * none).  With h = x W1, g = x V (recomputed here, the forward does not store them), a = GeLU(h) (*) g:
+ *   dA = dy W2^T,   dh = dA (*) g (*) GeLU'(h),   dg = dA (*) GeLU(h),   GeLU'(h) = Phi(h) + h phi(h),
+ *   dx = dh W1^T + dg V^T,   dW2 = a^T dy,   dW1 = x^T dh,   dV = x^T dg.
+ *   dy   dev, [T_cap, hidden], read.        x, w1v, w2   as in mb_geglu_fwd, read.
+ *   act  dev, [T_cap, inter], read: the activation the forward stored.
+ *   dx   dev, [T_cap, hidden], written (rows [0, T) only).
+ *   dw1v dev, [2*inter, hidden] float, written: gradient of w1v in its own (transposed) layout, dW1^T over dV^T.
+ *   dw2  dev, [hidden, inter] float, written: gradient of w2 in its own layout (dW2^T).
+ *   workspace  dev, 256-byte aligned, at least mb_geglu_bwd_workspace_bytes bytes, scratch.
+ * Weight gradients are fp32 sums over the T token rows taken in a fixed order (deterministic); with T = 0 they
+ * are zeros.  dh and dg pass through bf16 on their way into the products.  Supported: MB_BF16 with hidden and
+ * inter multiples of 256.
+ */
+MB_API mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act,
+                              int T_cap, const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx,
+                              float* dw1v, float* dw2, void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * The pieces of the UNFUSED arrangements of the same sublayer (appendix on GLU implementations: two separate
  * input projections, or one of twice the width whose product is stored and sliced), for comparison with

@@ -24,7 +24,7 @@ MB_F32, MB_BF16 = 0, 1
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
            "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
-           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling")
+           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -61,6 +61,11 @@ _lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
 _lib.mb_add_layernorm_bwd.restype = c_int
 _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.mb_geglu_bwd_workspace_bytes.restype = c_size_t
+_lib.mb_geglu_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
+_lib.mb_geglu_bwd.restype = c_int
+_lib.mb_geglu_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int,
+                              c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
 _lib.mb_probe_ceiling.restype = c_int
 _lib.mb_probe_ceiling.argtypes = [c_int, c_int, c_void_p, c_void_p, c_void_p]
 _lib.mb_linear_fwd.restype = c_int
@@ -298,3 +303,24 @@ def mb_probe_ceiling(kind: int, iters: int, out) -> float:
     work = ctypes.c_double(0.0)
     _check(_lib.mb_probe_ceiling(kind, iters, _ptr(out), ctypes.byref(work), _stream()))
     return work.value
+
+
+def mb_geglu_bwd_workspace_bytes(T_cap: int, hidden: int, inter: int, dtype_code: int = MB_BF16) -> int:
+    return int(_lib.mb_geglu_bwd_workspace_bytes(T_cap, hidden, inter, dtype_code))
+
+
+def mb_geglu_bwd(dy, x, w1v, w2, act, T_cap=None, meta=None, dx=None, dw1v=None, dw2=None, workspace=None):
+    """Returns (dx [rows, hidden], dw1v [2*inter, hidden] float32, dw2 [hidden, inter] float32)."""
+    rows, hidden = x.shape
+    inter = w2.shape[1]
+    T_cap = rows if T_cap is None else T_cap
+    dx = torch.empty_like(x) if dx is None else dx
+    dw1v = torch.empty((2 * inter, hidden), dtype=torch.float32, device=x.device) if dw1v is None else dw1v
+    dw2 = torch.empty((hidden, inter), dtype=torch.float32, device=x.device) if dw2 is None else dw2
+    if workspace is None:
+        workspace = torch.empty(max(mb_geglu_bwd_workspace_bytes(T_cap, hidden, inter, _dtype_code(x)), 256),
+                                dtype=torch.uint8, device=x.device)
+    _check(_lib.mb_geglu_bwd(_ptr(dy), _ptr(x), _ptr(w1v), _ptr(w2), _ptr(act), T_cap, _ptr(meta), hidden, inter,
+                             _dtype_code(x), _ptr(dx), _ptr(dw1v), _ptr(dw2), _ptr(workspace), workspace.numel(),
+                             _stream()))
+    return dx, dw1v, dw2

@@ -403,4 +403,49 @@ mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_lau
   return launch_probe(kind, iters, out, work_per_launch, (hipStream_t)stream);
 }
 
+static mb_status check_geglu_bwd(int T_cap, int hidden, int inter, mb_dtype dt) {
+  MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
+  MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap must be >= 0 (got %d)", T_cap);
+  MB_REQUIRE(hidden > 0 && inter > 0, MB_ERR_INVALID_ARG, "hidden and inter must be positive (got %d, %d)", hidden,
+             inter);
+  MB_REQUIRE(dt == MB_BF16, MB_ERR_UNSUPPORTED, "the feed-forward kernels are bf16 only");
+  MB_REQUIRE(hidden % 256 == 0 && inter % 256 == 0, MB_ERR_UNSUPPORTED,
+             "hidden and inter must be multiples of 256 (got %d, %d)", hidden, inter);
+  MB_REQUIRE((int64_t)T_cap * 2 * (int64_t)inter < ((int64_t)1 << 31) &&
+                 2 * (int64_t)inter * (int64_t)hidden < ((int64_t)1 << 31) &&
+                 (int64_t)T_cap * (int64_t)hidden < ((int64_t)1 << 31),
+             MB_ERR_UNSUPPORTED, "tensor of 2^31 elements or more (T_cap=%d hidden=%d inter=%d)", T_cap, hidden, inter);
+  return MB_OK;
+}
+
+size_t mb_geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter, mb_dtype dt) {
+  if (check_geglu_bwd(T_cap, hidden, inter, dt) != MB_OK) return 0;
+  return geglu_bwd_workspace_bytes(T_cap, hidden, inter);
+}
+
+mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act, int T_cap,
+                       const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx, float* dw1v, float* dw2,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  clear_error();
+  mb_status st = check_geglu_bwd(T_cap, hidden, inter, dt);
+  if (st != MB_OK) return st;
+  MB_CHECK_PTR(w1v);
+  MB_CHECK_PTR(w2);
+  MB_CHECK_PTR(dw1v);
+  MB_CHECK_PTR(dw2);
+  const size_t need = geglu_bwd_workspace_bytes(T_cap, hidden, inter);
+  MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
+             "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, MB_ERR_INVALID_ARG,
+             "workspace is not 256-byte aligned");
+  if (T_cap > 0) {
+    MB_CHECK_PTR(dy);
+    MB_CHECK_PTR(x);
+    MB_CHECK_PTR(act);
+    MB_CHECK_PTR(dx);
+  }
+  return launch_geglu_bwd(dy, x, w1v, w2, act, T_cap, meta_dev, hidden, inter, dx, dw1v, dw2, workspace,
+                          (hipStream_t)stream);
+}
+
 }  // extern "C"

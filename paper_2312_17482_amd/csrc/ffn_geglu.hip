@@ -48,13 +48,36 @@ __device__ __forceinline__ float gelu_exact(float h) {
   return fmaf(-ah, u, fmaxf(h, 0.0f));
 }
 
-template <bool kGated, int kNB>   // kNB: 32-row weight blocks per wave (4 or 3); workgroup = 64 * kNB weight rows
+// GeLU and its derivative Phi(h) + h phi(h) from the same intermediates (phi = the normal density).
+__device__ __forceinline__ void gelu_and_grad(float h, float& val, float& grad) {
+  const float ah = fabsf(h);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, ah, 1.0f));
+  float poly = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  poly = fmaf(poly, t, 0.5f * 1.421413741f);
+  poly = fmaf(poly, t, 0.5f * -0.284496736f);
+  poly = fmaf(poly, t, 0.5f * 0.254829592f);
+  const float e = __builtin_amdgcn_exp2f(h * h * (-0.5f * kLog2e));   // exp(-h^2 / 2)
+  const float u = poly * t * e;                                      // Phi(-|h|)
+  val = fmaf(-ah, u, fmaxf(h, 0.0f));
+  const float phi_cdf = h < 0.f ? u : 1.0f - u;
+  grad = fmaf(h * 0.3989422804014327f, e, phi_cdf);
+}
+
+// Epilogues of the GEMM kernel.
+constexpr int kPlain = 0;      // out = product
+constexpr int kGatedFwd = 1;   // out = GeLU(x W1) (*) x V on the accumulators (weight = W1^T over V^T)
+constexpr int kGateBwd = 2;    // the product is dA; with h | g read from `aux`: out = dA g GeLU'(h) | dA GeLU(h)
+
+template <int kMode, int kNB>   // kNB: 32-row weight blocks per wave (4 or 3); workgroup = 64 * kNB weight rows
 __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __restrict__ X, int ldx,
                                                           const uint16_t* __restrict__ W, int ldw, int K,
                                                           int n_tiles, int gate_row, int w_rows, int T_cap,
                                                           const int32_t* __restrict__ meta,
-                                                          uint16_t* __restrict__ out, int ldo) {
+                                                          uint16_t* __restrict__ out, int ldo,
+                                                          const uint16_t* __restrict__ aux, int gate_col) {
+  constexpr bool kGated = kMode == kGatedFwd;
   static_assert(!kGated || kNB == 4, "the gated epilogue pairs weight blocks 0,1 with 2,3");
+  static_assert(kMode != kGateBwd || kNB == 4, "the gate-backward epilogue is written for 64-column passes");
   constexpr int kBN = 64 * kNB;                     // weight rows per workgroup
   constexpr int kStage = (kBM + kBN) * kPitch;      // elements per LDS stage
   constexpr int kLoads = 8 + 2 * kNB;               // 16-byte loads per thread and k step (32 rows per load)
@@ -242,7 +265,30 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
       for (int it = 0; it < 16; ++it) {
         const int row = 8 * it + orow;
         const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
-        if (row_base + row < T) *reinterpret_cast<u32x4*>(out + (int64_t)(row_base + row) * ldo + col0 + ocol) = w;
+        if (row_base + row < T) {
+          const int64_t at = (int64_t)(row_base + row) * ldo + col0 + ocol;
+          if (kMode == kGateBwd) {
+            // w holds 8 values of dA; h and g of the same positions come from aux (columns col and
+            // gate_col + col of a row); dh and dg go to the same two places of out
+            const u32x4 hv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at));
+            const u32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at + gate_col));
+            u32x4 dh, dg;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              float v0, d0, v1, d1;
+              gelu_and_grad(__uint_as_float(hv[i] << 16), v0, d0);
+              gelu_and_grad(__uint_as_float(hv[i] & 0xffff0000u), v1, d1);
+              const float a0 = __uint_as_float(w[i] << 16), a1 = __uint_as_float(w[i] & 0xffff0000u);
+              const float g0 = __uint_as_float(gv[i] << 16), g1 = __uint_as_float(gv[i] & 0xffff0000u);
+              dh[i] = pack_bf16(a0 * g0 * d0, a1 * g1 * d1);
+              dg[i] = pack_bf16(a0 * v0, a1 * v1);
+            }
+            *reinterpret_cast<u32x4*>(out + at) = dh;
+            *reinterpret_cast<u32x4*>(out + at + gate_col) = dg;
+          } else {
+            *reinterpret_cast<u32x4*>(out + at) = w;
+          }
+        }
       }
     } else {                        // rows of 32 columns = 64 bytes = 4 lanes
       const int orow = lane >> 2, ocol = (lane & 3) * 8;
@@ -282,6 +328,154 @@ __global__ __launch_bounds__(256) void gelu_gate_kernel(const uint16_t* __restri
   }
 }
 
+// ------------------------------------------------------------------------------------------------ weight gradients
+// partial[split][m, n] = sum over the split's tokens t of P[t, m] * Q[t, n]: both operands are stored
+// token-major, so the contraction runs over ROWS.  Rows of 256 columns go to LDS as they are and the
+// matrix-core operands (8 consecutive tokens of one column per lane) come out of transposing LDS reads
+// (ds_read_b64_tr_b16).  The accumulator has m along registers and n along lanes, so a store instruction
+// writes 128 contiguous bytes of two output rows: fp32 partial tiles need no staging.  Tokens are split
+// over `splits` workgroups per tile (there are only M/256 x N/256 tiles); a second kernel adds the
+// partial tiles in a fixed order, so the result is deterministic.
+constexpr int kWgPitch = 272;                       // LDS row pitch of a 256-column token row, elements (544 B)
+constexpr int kWgRows = 64;                         // tokens per k step
+constexpr int kWgStage = 2 * kWgRows * kWgPitch;    // P rows + Q rows
+
+__global__ __launch_bounds__(256, 1) void ffn_wgrad_kernel(const uint16_t* __restrict__ P, int ldp,
+                                                           const uint16_t* __restrict__ Q, int ldq, int n_tiles,
+                                                           int tiles, int splits, int T_cap,
+                                                           const int32_t* __restrict__ meta,
+                                                           float* __restrict__ partial, int M, int N) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kWgStage];
+  const int T = __builtin_amdgcn_readfirstlane(meta ? min(meta[0], T_cap) : T_cap);
+  const int tile = blockIdx.x % tiles, split = blockIdx.x / tiles;
+  const int m0 = __builtin_amdgcn_readfirstlane(tile / n_tiles) * 256;
+  const int n0 = __builtin_amdgcn_readfirstlane(tile % n_tiles) * 256;
+  const int steps_total = (T + kWgRows - 1) / kWgRows;
+  const int per = (steps_total + splits - 1) / splits;
+  const int s_begin = split * per;
+  const int nsteps = max(min(s_begin + per, steps_total) - s_begin, 0);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, g = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lrow = tid >> 5, lchunk = (tid & 31) * 8;   // a row of 256 columns = 32 lanes x 16 bytes; 8 rows per pass
+  constexpr int kRsrcFlags = 0x00020000;
+  const uint32_t plane = ((uint32_t)lrow * (uint32_t)ldp + lchunk) * 2u;
+  const uint32_t qlane = ((uint32_t)lrow * (uint32_t)ldq + lchunk) * 2u;
+  u32x4 st[16];
+  // Load i of a step (i < 8: rows 8 i .. of P, else of Q).  The descriptor ends with the last token row,
+  // so the rows past T of the last step read as zeros and add nothing.
+  auto fetch_one = [&](int i, int t0) {
+    const int p = i & 7;
+    const int first = t0 + 8 * p;
+    const int rows = __builtin_amdgcn_readfirstlane(max(min(T - first, 8), 0));
+    if (i < 8) {
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(P) + (int64_t)first * ldp + m0, 0, rows > 0 ? ((rows - 1) * ldp + 256) * 2 : 0,
+          kRsrcFlags);
+      st[i] = __builtin_amdgcn_raw_buffer_load_b128(r, plane, 0, 0);
+    } else {
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(Q) + (int64_t)first * ldq + n0, 0, rows > 0 ? ((rows - 1) * ldq + 256) * 2 : 0,
+          kRsrcFlags);
+      st[i] = __builtin_amdgcn_raw_buffer_load_b128(r, qlane, 0, 0);
+    }
+  };
+  auto deposit = [&](uint16_t* buf) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = (i < 8 ? 0 : kWgRows) + 8 * (i & 7) + lrow;
+      *reinterpret_cast<u32x4*>(&buf[row * kWgPitch + lchunk]) = st[i];
+    }
+  };
+
+  f32x16 acc[4][4];   // [m block][n block]
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  const int tr_i = lane & 15, tr_q = lane >> 4;
+  const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
+  const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
+  const int poff = tr_row * kWgPitch + wm * 128 + tr_col;
+  const int qoff = (kWgRows + tr_row) * kWgPitch + wn * 128 + tr_col;
+
+  if (nsteps > 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) fetch_one(i, s_begin * kWgRows);
+    deposit(smem);
+    if (nsteps > 1) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) fetch_one(i, (s_begin + 1) * kWgRows);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nsteps; ++kt) {
+      const uint16_t* cur = smem + (kt & 1) * kWgStage;
+      // (every wave left the other stage at the barrier that ended the previous step)
+      if (kt + 1 < nsteps) deposit(smem + ((kt + 1) & 1) * kWgStage);
+      if (kt + 2 < nsteps) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) fetch_one(i, (s_begin + kt + 2) * kWgRows);
+      }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 pf[4], qf[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const uint16_t* pp = cur + poff + 16 * kk * kWgPitch + 32 * b;
+          const uint16_t* qq = cur + qoff + 16 * kk * kWgPitch + 32 * b;
+          pf[b] = join_tr(lds_read_tr4(pp), lds_read_tr4(pp + 8 * kWgPitch));
+          qf[b] = join_tr(lds_read_tr4(qq), lds_read_tr4(qq + 8 * kWgPitch));
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) acc[a][b] = mfma32(pf[a], qf[b], acc[a][b]);
+      }
+      __syncthreads();
+    }
+  }
+  // fp32 partial tile: register v of block (a, b) is row 8 (v / 4) + 4 g + v % 4, lane c is the column
+  float* dst = partial + (int64_t)split * M * N + (int64_t)(m0 + wm * 128) * N + n0 + wn * 128 + c;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        dst[(int64_t)(a * 32 + 8 * (v >> 2) + 4 * g + (v & 3)) * N + b * 32] = acc[a][b][v];
+}
+
+// out[i] = sum over splits of partial[s][i], in order.
+__global__ __launch_bounds__(256) void ffn_wgrad_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                               int64_t count4, float* __restrict__ out) {
+  const float4* src = reinterpret_cast<const float4*>(partial);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count4; i += (int64_t)gridDim.x * blockDim.x) {
+    float4 a = src[i];
+    for (int s = 1; s < splits; ++s) {
+      const float4 b = src[(int64_t)s * count4 + i];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    reinterpret_cast<float4*>(out)[i] = a;
+  }
+}
+
+// out[c][r] = in[r][c] for a [R, C] bf16 matrix (R, C multiples of 64): 64 x 64 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_kernel(const uint16_t* __restrict__ in, int R, int C,
+                                                        uint16_t* __restrict__ out) {
+  __shared__ uint16_t tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tile[4 * i + ty][tx] = in[(int64_t)(r0 + 4 * i + ty) * C + c0 + tx];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) out[(int64_t)(c0 + 4 * i + ty) * R + r0 + tx] = tile[tx][4 * i + ty];
+}
+
 }  // namespace
 
 // out[t, n] = sum_k x[t, k] * wt[n, k] with the plain epilogue; the tile width (256 or 192 weight rows) is the
@@ -296,14 +490,14 @@ static void launch_plain(const void* x, const void* wt, int T_cap, const int32_t
   const bool narrow = n_out % 192 == 0 && (n_out % 256 != 0 || cost(192) < cost(256));
   if (narrow) {
     const int n_tiles = n_out / 192;
-    ffn_gemm_kernel<false, 3><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+    ffn_gemm_kernel<kPlain, 3><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
         static_cast<const uint16_t*>(x), n_in, static_cast<const uint16_t*>(wt), n_in, n_in, n_tiles, 0, n_out, T_cap,
-        meta, static_cast<uint16_t*>(y), n_out);
+        meta, static_cast<uint16_t*>(y), n_out, nullptr, 0);
   } else {
     const int n_tiles = n_out / 256;
-    ffn_gemm_kernel<false, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+    ffn_gemm_kernel<kPlain, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
         static_cast<const uint16_t*>(x), n_in, static_cast<const uint16_t*>(wt), n_in, n_in, n_tiles, 0, n_out, T_cap,
-        meta, static_cast<uint16_t*>(y), n_out);
+        meta, static_cast<uint16_t*>(y), n_out, nullptr, 0);
   }
 }
 
@@ -312,9 +506,9 @@ mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T
   if (T_cap == 0) return MB_OK;
   const int m_tiles = (T_cap + kBM - 1) / kBM;
   const int n_tiles = inter / 128;
-  ffn_gemm_kernel<true, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
+  ffn_gemm_kernel<kGatedFwd, 4><<<dim3(m_tiles * n_tiles), dim3(256), 0, stream>>>(
       static_cast<const uint16_t*>(x), hidden, static_cast<const uint16_t*>(w1v), hidden, hidden, n_tiles, inter,
-      2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter);
+      2 * inter, T_cap, meta, static_cast<uint16_t*>(act), inter, nullptr, 0);
   launch_plain(act, w2, T_cap, meta, inter, hidden, y, stream);
   return check_launch("ffn_gemm_kernel");
 }
@@ -335,6 +529,68 @@ mb_status launch_gelu_gate(const void* h, const void* gate, int64_t ld, int T_ca
                                                            static_cast<const uint16_t*>(gate), ld, T_cap, meta, inter,
                                                            static_cast<uint16_t*>(act));
   return check_launch("gelu_gate_kernel");
+}
+
+// Workspace of the backward: h|g recomputed, dh|dg, the two transposed weight matrices, the partial
+// weight-gradient tiles.
+static constexpr int kWgradSplits = 7;
+static size_t bwd_ws_layout(int T_cap, int hidden, int inter, size_t off[5]) {
+  size_t at = 0;
+  const size_t rows = (size_t)T_cap * 2 * inter * 2;
+  off[0] = at; at += align_up(rows, 256);                                   // hg   [T_cap, 2 inter] bf16
+  off[1] = at; at += align_up(rows, 256);                                   // dhg  [T_cap, 2 inter] bf16
+  off[2] = at; at += align_up((size_t)inter * hidden * 2, 256);             // w2 transposed [inter, hidden]
+  off[3] = at; at += align_up((size_t)2 * inter * hidden * 2, 256);         // w1v transposed [hidden, 2 inter]
+  off[4] = at; at += align_up((size_t)kWgradSplits * 2 * inter * hidden * 4, 256);   // partial tiles, fp32
+  return at;
+}
+
+size_t geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter) {
+  size_t off[5];
+  return bwd_ws_layout(T_cap, hidden, inter, off);
+}
+
+static void launch_wgrad(const void* p, int ldp, const void* q, int ldq, int M, int N, int T_cap, const int32_t* meta,
+                         float* partial, float* out, hipStream_t stream) {
+  const int n_tiles = N / 256, tiles = (M / 256) * n_tiles;
+  ffn_wgrad_kernel<<<dim3(tiles * kWgradSplits), dim3(256), 0, stream>>>(
+      static_cast<const uint16_t*>(p), ldp, static_cast<const uint16_t*>(q), ldq, n_tiles, tiles, kWgradSplits, T_cap,
+      meta, partial, M, N);
+  const int64_t count4 = (int64_t)M * N / 4;
+  ffn_wgrad_reduce_kernel<<<dim3(1024), dim3(256), 0, stream>>>(partial, kWgradSplits, count4, out);
+}
+
+mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act, int T_cap,
+                           const int32_t* meta, int hidden, int inter, void* dx, float* dw1v, float* dw2,
+                           void* workspace, hipStream_t stream) {
+  size_t off[5];
+  bwd_ws_layout(T_cap, hidden, inter, off);
+  char* ws = static_cast<char*>(workspace);
+  uint16_t* hg = reinterpret_cast<uint16_t*>(ws + off[0]);
+  uint16_t* dhg = reinterpret_cast<uint16_t*>(ws + off[1]);
+  uint16_t* w2t = reinterpret_cast<uint16_t*>(ws + off[2]);
+  uint16_t* w1vt = reinterpret_cast<uint16_t*>(ws + off[3]);
+  float* partial = reinterpret_cast<float*>(ws + off[4]);
+  // the weight matrices the data gradients contract over their OTHER index
+  transpose_kernel<<<dim3(inter / 64, hidden / 64), dim3(256), 0, stream>>>(static_cast<const uint16_t*>(w2), hidden,
+                                                                           inter, w2t);
+  transpose_kernel<<<dim3(hidden / 64, 2 * inter / 64), dim3(256), 0, stream>>>(static_cast<const uint16_t*>(w1v),
+                                                                               2 * inter, hidden, w1vt);
+  if (T_cap > 0) {
+    const int m_tiles = (T_cap + kBM - 1) / kBM;
+    // h | g = x (W1 | V) again (recomputed, not stored by the forward)
+    launch_plain(x, w1v, T_cap, meta, hidden, 2 * inter, hg, stream);
+    // dA = dy W2^T, and on its way out  dh = dA g GeLU'(h),  dg = dA GeLU(h)
+    ffn_gemm_kernel<kGateBwd, 4><<<dim3(m_tiles * (inter / 256)), dim3(256), 0, stream>>>(
+        static_cast<const uint16_t*>(dy), hidden, w2t, hidden, hidden, inter / 256, 0, inter, T_cap, meta, dhg,
+        2 * inter, hg, inter);
+    // dx = dh W1^T + dg V^T = (dh | dg) (W1 | V)^T
+    launch_plain(dhg, w1vt, T_cap, meta, 2 * inter, hidden, dx, stream);
+  }
+  // dW2^T[c, j] = sum_t dy[t, c] act[t, j];   d(W1|V)^T[j, c] = sum_t (dh|dg)[t, j] x[t, c]
+  launch_wgrad(dy, hidden, act, inter, hidden, inter, T_cap, meta, partial, dw2, stream);
+  launch_wgrad(dhg, 2 * inter, x, hidden, 2 * inter, hidden, T_cap, meta, partial, dw1v, stream);
+  return check_launch("geglu backward");
 }
 
 }  // namespace mb

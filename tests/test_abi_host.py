@@ -202,3 +202,17 @@ def test_probe_rejects_bad_arguments():
     assert lib.mb_probe_ceiling(0, 0, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, None, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, A, None, None) == mb.MB_ERR_INVALID_ARG
+
+
+def test_geglu_bwd_rejects_bad_arguments():
+    f = lib.mb_geglu_bwd
+    need = mb.mb_geglu_bwd_workspace_bytes(512, 768, 3072)
+    assert need > 2 * 512 * 6144 * 2 and need % 256 == 0
+    assert mb.mb_geglu_bwd_workspace_bytes(512, 768, 3000) == 0
+    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need - 1, None) == mb.MB_ERR_WORKSPACE
+    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, None, need, None) == mb.MB_ERR_WORKSPACE
+    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A + 16, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, A, A, 512, None, 768, 3200, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_F32, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, None, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(None, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_INVALID_ARG

@@ -154,3 +154,60 @@ def test_gelu_gate_parity_and_unfused_arrangements(mb):
     torch.cuda.synchronize()
     assert torch.all(yy[500:] == 9.0) and torch.equal(yy[:500], h_b[:500])
     assert torch.all(aa[500:] == 9.0) and torch.equal(aa[:500], act_c[:500])
+
+
+def check_f32(name, got, ref):
+    ma, rf = err_stats(got.double().cpu().numpy(), ref)
+    top = float(np.abs(ref).max())
+    assert rf <= 1e-2 and ma <= 2.0 ** -6 * top, "%s max_abs=%.3e (max|ref| %.3e) rel_fro=%.3e" % (name, ma, top, rf)
+
+
+@pytest.mark.parametrize("T,hidden,inter,w_std", [(300, 256, 256, 0.05), (1000, 768, 3072, 0.02), (65, 512, 768, 0.04),
+                                                  (2500, 768, 3072, 0.02)])
+def test_geglu_backward_parity(mb, T, hidden, inter, w_std):
+    """dx (bf16) and the fp32 weight gradients against the oracle's textbook derivative.  Weight gradients are
+    sums over T tokens of products of bf16-rounded factors: relative Frobenius <= 1e-2, max-abs <= 2^-6 max|ref|."""
+    print("geglu backward T=%d hidden=%d inter=%d" % (T, hidden, inter), flush=True)
+    case = wl.random_ffn_case(31, T, hidden, inter, w_std)
+    x, w1v, w2, dy = case["x"], case["w1v"], case["w2"], case["dy"]
+    dx_ref, dw1_ref, dv_ref, dw2_ref = orc.geglu_bwd(dy, x, w1v[:inter], w1v[inter:], w2)
+    xd, wd, w2d, dyd = dev(x), dev(w1v), dev(w2), dev(dy)
+    y, act = mb.mb_geglu_fwd(xd, wd, w2d)
+    guard = 2
+    dx = torch.full((T + guard, hidden), 9.0, dtype=torch.bfloat16, device="cuda")
+    _, dw1v, dw2 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act, dx=dx[:T])
+    torch.cuda.synchronize()
+    assert torch.all(dx[T:] == 9.0)
+    check("dx", dx[:T], dx_ref, wide=True)
+    check_f32("dw1", dw1v[:inter], dw1_ref)
+    check_f32("dv", dw1v[inter:], dv_ref)
+    check_f32("dw2", dw2, dw2_ref)
+    # run-to-run identical (fixed summation order)
+    dx2, dw1v2, dw22 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act)
+    torch.cuda.synchronize()
+    assert torch.equal(dx2, dx[:T]) and torch.equal(dw1v2, dw1v) and torch.equal(dw22, dw2)
+
+
+def test_geglu_backward_device_side_row_count_and_empty(mb):
+    print("geglu backward capacity mode", flush=True)
+    T_cap, T, hidden, inter = 1024, 333, 256, 512
+    case = wl.random_ffn_case(32, T_cap, hidden, inter, 0.05)
+    x, w1v, w2, dy = case["x"], case["w1v"], case["w2"], case["dy"]
+    dx_ref, dw1_ref, dv_ref, dw2_ref = orc.geglu_bwd(dy[:T], x[:T], w1v[:inter], w1v[inter:], w2)
+    xd, wd, w2d, dyd = dev(x), dev(w1v), dev(w2), dev(dy)
+    meta = torch.tensor([T, 0], dtype=torch.int32, device="cuda")
+    y, act = mb.mb_geglu_fwd(xd, wd, w2d, meta=meta)
+    dx = torch.full((T_cap, hidden), 9.0, dtype=torch.bfloat16, device="cuda")
+    _, dw1v, dw2 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act, meta=meta, dx=dx)
+    torch.cuda.synchronize()
+    assert torch.all(dx[T:] == 9.0)
+    check("dx", dx[:T], dx_ref, wide=True)
+    check_f32("dw1", dw1v[:inter], dw1_ref)
+    check_f32("dv", dw1v[inter:], dv_ref)
+    check_f32("dw2", dw2, dw2_ref)
+    # no tokens at all: weight gradients are zeros, dx untouched
+    meta0 = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dx0 = torch.full((T_cap, hidden), 9.0, dtype=torch.bfloat16, device="cuda")
+    _, dw1v0, dw20 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act, meta=meta0, dx=dx0)
+    torch.cuda.synchronize()
+    assert torch.all(dx0 == 9.0) and torch.all(dw1v0 == 0) and torch.all(dw20 == 0)
