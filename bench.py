@@ -235,7 +235,7 @@ def main():
     out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev),
                         "padded_attention_comparison": time_padded_vs_varlen(mb, locals())}
     if bf16 and (H * D) % 256 == 0:
-        out["next_rows"]["geglu_ffn_fwd_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
+        out["next_rows"]["geglu_ffn_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
     if args.ceilings:
@@ -378,6 +378,27 @@ def time_geglu(mb, T, hidden, inter, dev):
         us = a.elapsed_time(b) * 1e3 / 20
         res[name + "_us"] = round(us, 1)
         res[name + "_tflops"] = round(flops / us * 1e-6, 1)
+    # backward: data gradient and fp32 weight gradients; flops 2 T hidden inter x (dA 1 + dx 2 + dW2 1 + dW1V 2),
+    # plus 2 more units when x W1 | x V are computed again (fused forward) instead of handed over (sliced forward)
+    dyt = torch.randn(T, hidden, device=dev).to(bf)
+    dx = torch.empty_like(x)
+    dw1v = torch.empty((2 * inter, hidden), dtype=torch.float32, device=dev)
+    dw2 = torch.empty((hidden, inter), dtype=torch.float32, device=dev)
+    ws = torch.empty(mb.mb_geglu_bwd_workspace_bytes(T, hidden, inter), dtype=torch.uint8, device=dev)
+    mb.mb_linear_fwd(x, w1v, y=hg)
+    unit = 2.0 * T * hidden * inter
+    for name, saved, units in (("bwd_recompute", None, 8.0), ("bwd_stored_projections", hg, 6.0)):
+        for _ in range(2):
+            mb.mb_geglu_bwd(dyt, x, w1v, w2, act, hg=saved, dx=dx, dw1v=dw1v, dw2=dw2, workspace=ws)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            mb.mb_geglu_bwd(dyt, x, w1v, w2, act, hg=saved, dx=dx, dw1v=dw1v, dw2=dw2, workspace=ws)
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / 10
+        res[name + "_us"] = round(us, 1)
+        res[name + "_tflops"] = round(units * unit / us * 1e-6, 1)
     res["frac_of_bf16_mfma_peak"] = round(res["fused_tflops"] / PEAK_BF16_TFLOPS, 4)
     res["unfused_slowdown"] = {"sliced": round(res["sliced_us"] / res["fused_us"], 3),
                                "separate": round(res["separate_us"] / res["fused_us"], 3)}

@@ -228,11 +228,13 @@ MB_API size_t mb_geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter, mb_
 
 /*
  * Backward of mb_geglu_fwd for the scalar loss sum(y * dy) (the textbook derivative of Eq. 2; the paper prints
- * none).  With h = x W1, g = x V (recomputed here, the forward does not store them), a = GeLU(h) (*) g:
+ * none).  With h = x W1, g = x V, a = GeLU(h) (*) g:
  *   dA = dy W2^T,   dh = dA (*) g (*) GeLU'(h),   dg = dA (*) GeLU(h),   GeLU'(h) = Phi(h) + h phi(h),
  *   dx = dh W1^T + dg V^T,   dW2 = a^T dy,   dW1 = x^T dh,   dV = x^T dg.
  *   dy   dev, [T_cap, hidden], read.        x, w1v, w2   as in mb_geglu_fwd, read.
  *   act  dev, [T_cap, inter], read: the activation the forward stored.
+ *   hg   dev, [T_cap, 2*inter] or NULL, read: x W1 | x V as the unfused forward (mb_linear_fwd with w1v) stores
+ *        them; NULL (the fused forward keeps neither) makes this call compute them again.
  *   dx   dev, [T_cap, hidden], written (rows [0, T) only).
  *   dw1v dev, [2*inter, hidden] float, written: gradient of w1v in its own (transposed) layout, dW1^T over dV^T.
  *   dw2  dev, [hidden, inter] float, written: gradient of w2 in its own layout (dW2^T).
@@ -242,7 +244,7 @@ MB_API size_t mb_geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter, mb_
  * inter multiples of 256.
  */
 MB_API mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act,
-                              int T_cap, const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx,
+                              const void* hg, int T_cap, const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx,
                               float* dw1v, float* dw2, void* workspace, size_t workspace_bytes, void* stream);
 
 /*

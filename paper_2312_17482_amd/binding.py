@@ -64,7 +64,7 @@ _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_
 _lib.mb_geglu_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_geglu_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
 _lib.mb_geglu_bwd.restype = c_int
-_lib.mb_geglu_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int,
+_lib.mb_geglu_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int,
                               c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
 _lib.mb_probe_ceiling.restype = c_int
 _lib.mb_probe_ceiling.argtypes = [c_int, c_int, c_void_p, c_void_p, c_void_p]
@@ -309,8 +309,10 @@ def mb_geglu_bwd_workspace_bytes(T_cap: int, hidden: int, inter: int, dtype_code
     return int(_lib.mb_geglu_bwd_workspace_bytes(T_cap, hidden, inter, dtype_code))
 
 
-def mb_geglu_bwd(dy, x, w1v, w2, act, T_cap=None, meta=None, dx=None, dw1v=None, dw2=None, workspace=None):
-    """Returns (dx [rows, hidden], dw1v [2*inter, hidden] float32, dw2 [hidden, inter] float32)."""
+def mb_geglu_bwd(dy, x, w1v, w2, act, hg=None, T_cap=None, meta=None, dx=None, dw1v=None, dw2=None, workspace=None):
+    """Returns (dx [rows, hidden], dw1v [2*inter, hidden] float32, dw2 [hidden, inter] float32).  hg: the stored
+    [rows, 2*inter] projections of the unfused forward, or None to have them computed again."""
+    assert hg is None or hg.is_contiguous()
     rows, hidden = x.shape
     inter = w2.shape[1]
     T_cap = rows if T_cap is None else T_cap
@@ -320,7 +322,7 @@ def mb_geglu_bwd(dy, x, w1v, w2, act, T_cap=None, meta=None, dx=None, dw1v=None,
     if workspace is None:
         workspace = torch.empty(max(mb_geglu_bwd_workspace_bytes(T_cap, hidden, inter, _dtype_code(x)), 256),
                                 dtype=torch.uint8, device=x.device)
-    _check(_lib.mb_geglu_bwd(_ptr(dy), _ptr(x), _ptr(w1v), _ptr(w2), _ptr(act), T_cap, _ptr(meta), hidden, inter,
+    _check(_lib.mb_geglu_bwd(_ptr(dy), _ptr(x), _ptr(w1v), _ptr(w2), _ptr(act), _ptr(hg), T_cap, _ptr(meta), hidden, inter,
                              _dtype_code(x), _ptr(dx), _ptr(dw1v), _ptr(dw2), _ptr(workspace), workspace.numel(),
                              _stream()))
     return dx, dw1v, dw2

@@ -423,8 +423,8 @@ size_t mb_geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter, mb_dtype d
   return geglu_bwd_workspace_bytes(T_cap, hidden, inter);
 }
 
-mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act, int T_cap,
-                       const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx, float* dw1v, float* dw2,
+mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act,
+                       const void* hg, int T_cap, const int32_t* meta_dev, int hidden, int inter, mb_dtype dt, void* dx, float* dw1v, float* dw2,
                        void* workspace, size_t workspace_bytes, void* stream) {
   clear_error();
   mb_status st = check_geglu_bwd(T_cap, hidden, inter, dt);
@@ -443,8 +443,9 @@ mb_status mb_geglu_bwd(const void* dy, const void* x, const void* w1v, const voi
     MB_CHECK_PTR(x);
     MB_CHECK_PTR(act);
     MB_CHECK_PTR(dx);
+    if (hg != nullptr) MB_REQUIRE(aligned16(hg), MB_ERR_INVALID_ARG, "hg is not 16-byte aligned");
   }
-  return launch_geglu_bwd(dy, x, w1v, w2, act, T_cap, meta_dev, hidden, inter, dx, dw1v, dw2, workspace,
+  return launch_geglu_bwd(dy, x, w1v, w2, act, hg, T_cap, meta_dev, hidden, inter, dx, dw1v, dw2, workspace,
                           (hipStream_t)stream);
 }
 

@@ -73,9 +73,9 @@ mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T
 // Backward of the feed-forward (hidden and inter multiples of 256): data gradient dx (bf16) and the fp32
 // gradients of the stored (transposed) weight matrices; `workspace` holds geglu_bwd_workspace_bytes bytes.
 size_t geglu_bwd_workspace_bytes(int T_cap, int hidden, int inter);
-mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act, int T_cap,
-                           const int32_t* meta, int hidden, int inter, void* dx, float* dw1v, float* dw2,
-                           void* workspace, hipStream_t stream);
+mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act,
+                           const void* hg_saved, int T_cap, const int32_t* meta, int hidden, int inter, void* dx,
+                           float* dw1v, float* dw2, void* workspace, hipStream_t stream);
 // The pieces of the unfused arrangements: a bias-free projection y = x wt^T (n_in a multiple of 128, n_out a
 // multiple of 256 or of 192) and the activation pass act = GeLU(h) (*) gate over rows of stride ld.
 mb_status launch_linear_fwd(const void* x, const void* wt, int T_cap, const int32_t* meta, int n_in, int n_out,

@@ -236,6 +236,24 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
   for (int b0 = 0; b0 < kOutBlocks; b0 += 2) {
     constexpr int kTwo = 2;
     const int nblk = (kOutBlocks - b0) < kTwo ? (kOutBlocks - b0) : kTwo;
+    // Gate backward: the h and g values this lane will combine with dA are requested before the
+    // accumulators go through the slab, so that they arrive meanwhile (the staging registers of the k
+    // loop are free now).
+    u32x4 hpre[kMode == kGateBwd ? 16 : 1], gpre[kMode == kGateBwd ? 16 : 1];
+    if (kMode == kGateBwd) {
+      const int orow = lane >> 3, ocol = (lane & 7) * 8;
+      const int colp = n0 + wn * (32 * kOutBlocks) + b0 * 32 + ocol;
+#pragma unroll
+      for (int it = 0; it < 16; ++it) {
+        const int row = row_base + 8 * it + orow;
+        hpre[it] = gpre[it] = u32x4{0u, 0u, 0u, 0u};
+        if (row < T) {
+          const int64_t at = (int64_t)row * ldo + colp;
+          hpre[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at));
+          gpre[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at + gate_col));
+        }
+      }
+    }
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
       if (nb < nblk) {
@@ -268,10 +286,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_kernel(const uint16_t* __rest
         if (row_base + row < T) {
           const int64_t at = (int64_t)(row_base + row) * ldo + col0 + ocol;
           if (kMode == kGateBwd) {
-            // w holds 8 values of dA; h and g of the same positions come from aux (columns col and
+            // w holds 8 values of dA; h and g of the same positions came from aux (columns col and
             // gate_col + col of a row); dh and dg go to the same two places of out
-            const u32x4 hv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at));
-            const u32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(aux + at + gate_col));
+            const u32x4 hv = hpre[kMode == kGateBwd ? it : 0], gv = gpre[kMode == kGateBwd ? it : 0];
             u32x4 dh, dg;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -350,10 +367,12 @@ __global__ __launch_bounds__(256, 1) void ffn_wgrad_kernel(const uint16_t* __res
   const int tile = blockIdx.x % tiles, split = blockIdx.x / tiles;
   const int m0 = __builtin_amdgcn_readfirstlane(tile / n_tiles) * 256;
   const int n0 = __builtin_amdgcn_readfirstlane(tile % n_tiles) * 256;
+  // k steps of this split: the same even number for every split (the k loop alternates two register
+  // sets); steps past the last token read zeros and add nothing
   const int steps_total = (T + kWgRows - 1) / kWgRows;
-  const int per = (steps_total + splits - 1) / splits;
+  const int per = (((steps_total + splits - 1) / splits) + 1) & ~1;
   const int s_begin = split * per;
-  const int nsteps = max(min(s_begin + per, steps_total) - s_begin, 0);
+  const int nsteps = s_begin < steps_total ? per : 0;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
@@ -362,10 +381,9 @@ __global__ __launch_bounds__(256, 1) void ffn_wgrad_kernel(const uint16_t* __res
   constexpr int kRsrcFlags = 0x00020000;
   const uint32_t plane = ((uint32_t)lrow * (uint32_t)ldp + lchunk) * 2u;
   const uint32_t qlane = ((uint32_t)lrow * (uint32_t)ldq + lchunk) * 2u;
-  u32x4 st[16];
   // Load i of a step (i < 8: rows 8 i .. of P, else of Q).  The descriptor ends with the last token row,
-  // so the rows past T of the last step read as zeros and add nothing.
-  auto fetch_one = [&](int i, int t0) {
+  // so the rows past T read as zeros and add nothing.
+  auto fetch_one = [&](u32x4 (&st)[16], int i, int t0) {
     const int p = i & 7;
     const int first = t0 + 8 * p;
     const int rows = __builtin_amdgcn_readfirstlane(max(min(T - first, 8), 0));
@@ -381,13 +399,11 @@ __global__ __launch_bounds__(256, 1) void ffn_wgrad_kernel(const uint16_t* __res
       st[i] = __builtin_amdgcn_raw_buffer_load_b128(r, qlane, 0, 0);
     }
   };
-  auto deposit = [&](uint16_t* buf) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = (i < 8 ? 0 : kWgRows) + 8 * (i & 7) + lrow;
-      *reinterpret_cast<u32x4*>(&buf[row * kWgPitch + lchunk]) = st[i];
-    }
+  uint16_t* const dep[2] = {smem + lrow * kWgPitch + lchunk, smem + kWgStage + lrow * kWgPitch + lchunk};
+  auto deposit_one = [&](const u32x4 (&st)[16], int i, int stage) {
+    *reinterpret_cast<u32x4*>(dep[stage] + ((i < 8 ? 0 : kWgRows) + 8 * (i & 7)) * kWgPitch) = st[i];
   };
+  u32x4 st0[16], st1[16];
 
   f32x16 acc[4][4];   // [m block][n block]
 #pragma unroll
@@ -404,38 +420,57 @@ __global__ __launch_bounds__(256, 1) void ffn_wgrad_kernel(const uint16_t* __res
   const int qoff = (kWgRows + tr_row) * kWgPitch + wn * 128 + tr_col;
 
   if (nsteps > 0) {
+    const int t_first = s_begin * kWgRows;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) fetch_one(i, s_begin * kWgRows);
-    deposit(smem);
-    if (nsteps > 1) {
+    for (int i = 0; i < 16; ++i) fetch_one(st0, i, t_first);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) fetch_one(i, (s_begin + 1) * kWgRows);
-    }
+    for (int i = 0; i < 16; ++i) fetch_one(st1, i, t_first + kWgRows);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) deposit_one(st0, i, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) fetch_one(st0, i, t_first + 2 * kWgRows);
     __syncthreads();
-    for (int kt = 0; kt < nsteps; ++kt) {
-      const uint16_t* cur = smem + (kt & 1) * kWgStage;
-      // (every wave left the other stage at the barrier that ended the previous step)
-      if (kt + 1 < nsteps) deposit(smem + ((kt + 1) & 1) * kWgStage);
-      if (kt + 2 < nsteps) {
+
+    // Same hand-ordered k step as the projection kernel: per sub-step 16 matrix instructions, each
+    // preceded by at most two memory instructions (fragment reads of the next sub-step, double-buffered;
+    // LDS writes of the next step in sub-step 0; global loads of the step after next in sub-step 1), the
+    // barrier before sub-step 3.
+    bf16x8 pf[2][4], qf[2][4];
+    auto read_frag = [&](const uint16_t* stage_ptr, int kk, int buf, int i) {   // i = 0..3 P blocks, 4..7 Q blocks
+      const uint16_t* p = stage_ptr + (i < 4 ? poff : qoff) + 16 * kk * kWgPitch + 32 * (i & 3);
+      const bf16x8 f = join_tr(lds_read_tr4(p), lds_read_tr4(p + 8 * kWgPitch));
+      if (i < 4) pf[buf][i] = f;
+      else qf[buf][i - 4] = f;
+    };
 #pragma unroll
-        for (int i = 0; i < 16; ++i) fetch_one(i, (s_begin + kt + 2) * kWgRows);
-      }
+    for (int i = 0; i < 8; ++i) read_frag(smem, 0, 0, i);
+    auto step = [&](int cur_stage, u32x4 (&st)[16], int t_fetch) {
+      const uint16_t* cur = smem + cur_stage * kWgStage;
+      const uint16_t* nxt = smem + (cur_stage ^ 1) * kWgStage;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 pf[4], qf[4];
+        if (kk == 3) __syncthreads();
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const uint16_t* pp = cur + poff + 16 * kk * kWgPitch + 32 * b;
-          const uint16_t* qq = cur + qoff + 16 * kk * kWgPitch + 32 * b;
-          pf[b] = join_tr(lds_read_tr4(pp), lds_read_tr4(pp + 8 * kWgPitch));
-          qf[b] = join_tr(lds_read_tr4(qq), lds_read_tr4(qq + 8 * kWgPitch));
+        for (int a = 0; a < 4; ++a) {
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const int slot = 4 * a + b;
+            if (slot < 8) {
+              if (kk < 3) read_frag(cur, kk + 1, (kk + 1) & 1, slot);
+              else read_frag(nxt, 0, 0, slot);
+            }
+            if (kk == 0) deposit_one(st, slot, cur_stage ^ 1);
+            if (kk == 1) fetch_one(st, slot, t_fetch);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[a][b] = mfma32(pf[kk & 1][a], qf[kk & 1][b], acc[a][b]);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         }
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) acc[a][b] = mfma32(pf[a], qf[b], acc[a][b]);
       }
-      __syncthreads();
+    };
+    for (int kt = 0; kt < nsteps; kt += 2) {
+      step(0, st1, t_first + (kt + 3) * kWgRows);
+      step(1, st0, t_first + (kt + 4) * kWgRows);
     }
   }
   // fp32 partial tile: register v of block (a, b) is row 8 (v / 4) + 4 g + v % 4, lane c is the column
@@ -560,13 +595,13 @@ static void launch_wgrad(const void* p, int ldp, const void* q, int ldq, int M, 
   ffn_wgrad_reduce_kernel<<<dim3(1024), dim3(256), 0, stream>>>(partial, kWgradSplits, count4, out);
 }
 
-mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act, int T_cap,
-                           const int32_t* meta, int hidden, int inter, void* dx, float* dw1v, float* dw2,
-                           void* workspace, hipStream_t stream) {
+mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const void* w2, const void* act,
+                           const void* hg_saved, int T_cap, const int32_t* meta, int hidden, int inter, void* dx,
+                           float* dw1v, float* dw2, void* workspace, hipStream_t stream) {
   size_t off[5];
   bwd_ws_layout(T_cap, hidden, inter, off);
   char* ws = static_cast<char*>(workspace);
-  uint16_t* hg = reinterpret_cast<uint16_t*>(ws + off[0]);
+  const uint16_t* hg = hg_saved ? static_cast<const uint16_t*>(hg_saved) : reinterpret_cast<uint16_t*>(ws + off[0]);
   uint16_t* dhg = reinterpret_cast<uint16_t*>(ws + off[1]);
   uint16_t* w2t = reinterpret_cast<uint16_t*>(ws + off[2]);
   uint16_t* w1vt = reinterpret_cast<uint16_t*>(ws + off[3]);
@@ -578,8 +613,8 @@ mb_status launch_geglu_bwd(const void* dy, const void* x, const void* w1v, const
                                                                                2 * inter, hidden, w1vt);
   if (T_cap > 0) {
     const int m_tiles = (T_cap + kBM - 1) / kBM;
-    // h | g = x (W1 | V) again (recomputed, not stored by the forward)
-    launch_plain(x, w1v, T_cap, meta, hidden, 2 * inter, hg, stream);
+    // h | g = x (W1 | V): handed over by a caller that stored it, else computed again
+    if (!hg_saved) launch_plain(x, w1v, T_cap, meta, hidden, 2 * inter, ws + off[0], stream);
     // dA = dy W2^T, and on its way out  dh = dA g GeLU'(h),  dg = dA GeLU(h)
     ffn_gemm_kernel<kGateBwd, 4><<<dim3(m_tiles * (inter / 256)), dim3(256), 0, stream>>>(
         static_cast<const uint16_t*>(dy), hidden, w2t, hidden, hidden, inter / 256, 0, inter, T_cap, meta, dhg,

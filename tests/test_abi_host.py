@@ -209,10 +209,11 @@ def test_geglu_bwd_rejects_bad_arguments():
     need = mb.mb_geglu_bwd_workspace_bytes(512, 768, 3072)
     assert need > 2 * 512 * 6144 * 2 and need % 256 == 0
     assert mb.mb_geglu_bwd_workspace_bytes(512, 768, 3000) == 0
-    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need - 1, None) == mb.MB_ERR_WORKSPACE
-    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, None, need, None) == mb.MB_ERR_WORKSPACE
-    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A + 16, need, None) == mb.MB_ERR_INVALID_ARG
-    assert f(A, A, A, A, A, 512, None, 768, 3200, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
-    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_F32, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
-    assert f(A, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, None, A, A, need, None) == mb.MB_ERR_INVALID_ARG
-    assert f(None, A, A, A, A, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, A, A, None, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need - 1, None) == mb.MB_ERR_WORKSPACE
+    assert f(A, A, A, A, A, None, 512, None, 768, 3072, mb.MB_BF16, A, A, A, None, need, None) == mb.MB_ERR_WORKSPACE
+    assert f(A, A, A, A, A, None, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A + 16, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, A, A, None, 512, None, 768, 3200, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, A, A, None, 512, None, 768, 3072, mb.MB_F32, A, A, A, A, need, None) == mb.MB_ERR_UNSUPPORTED
+    assert f(A, A, A, A, A, None, 512, None, 768, 3072, mb.MB_BF16, A, None, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(None, A, A, A, A, None, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+    assert f(A, A, A, A, A, A + 4, 512, None, 768, 3072, mb.MB_BF16, A, A, A, A, need, None) == mb.MB_ERR_INVALID_ARG

@@ -186,6 +186,11 @@ def test_geglu_backward_parity(mb, T, hidden, inter, w_std):
     dx2, dw1v2, dw22 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act)
     torch.cuda.synchronize()
     assert torch.equal(dx2, dx[:T]) and torch.equal(dw1v2, dw1v) and torch.equal(dw22, dw2)
+    # with the projections handed over by the unfused forward instead of computed again: same numbers
+    hg = mb.mb_linear_fwd(xd, wd)
+    dx3, dw1v3, dw23 = mb.mb_geglu_bwd(dyd, xd, wd, w2d, act, hg=hg)
+    torch.cuda.synchronize()
+    assert torch.equal(dx3, dx[:T]) and torch.equal(dw1v3, dw1v) and torch.equal(dw23, dw2)
 
 
 def test_geglu_backward_device_side_row_count_and_empty(mb):
