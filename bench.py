@@ -301,7 +301,8 @@ def measure_ceilings(mb, dev):
     res = {}
     for name, kind, iters, unit, scale in (("mfma_bf16_32x32x16", 0, 2000, "TFLOP/s", 1e-12),
                                            ("valu_fp32_fma", 1, 20000, "TFLOP/s", 1e-12),
-                                           ("valu_fp32_exp", 2, 5000, "Texp/s", 1e-12)):
+                                           ("valu_fp32_exp", 2, 5000, "Texp/s", 1e-12),
+                                           ("lds_read_16B", 3, 5000, "TB/s", 1e-12)):
         for _ in range(3):
             work = mb.mb_probe_ceiling(kind, iters, scratch)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -273,6 +273,7 @@ MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_strid
  *   kind   0: v_mfma_f32_32x32x16_bf16, independent accumulators (work = flops)
  *          1: fp32 fused multiply-add on the vector unit (work = flops)
  *          2: fp32 exponential on the vector unit (work = exponentials)
+ *          3: 16-byte LDS reads in the pattern of the GEMM fragments (work = bytes)
  *   iters  rounds per lane (> 0).      out  dev, one float, scratch (never written in practice).
  *   work_per_launch  host, written.
  */

@@ -67,6 +67,27 @@ __global__ __launch_bounds__(256) void probe_exp_kernel(int iters, float* __rest
   if (s == 12345.678f) out[0] = s;
 }
 
+// 16-byte LDS reads, the access the GEMM fragments use (rows of 144 bytes, one row per lane of a half-wave):
+// 8 independent reads per round and wave.  One workgroup of 4 waves per compute unit slot.
+__global__ __launch_bounds__(256) void probe_lds_kernel(int iters, float* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[256 * 72];
+  for (int i = threadIdx.x; i < 256 * 72; i += 256) tile[i] = (uint16_t)i;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint16_t* base = &tile[((wave & 1) * 128 + (lane & 31)) * 72 + (lane >> 5) * 8];
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  int off = 0;
+  for (int it = 0; it < iters; ++it) {
+    asm volatile("" : "+v"(off));     // opaque: the reads cannot be hoisted out of the loop
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(base + off + (r & 3) * 32 * 72 + (r >> 2) * 16);
+      acc[0] += v[0]; acc[1] += v[1]; acc[2] += v[2]; acc[3] += v[3];
+    }
+  }
+  if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[0] = 1.f;
+}
+
 }  // namespace
 
 mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch, hipStream_t stream) {
@@ -83,6 +104,10 @@ mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch,
     case 2:   // exponentials: 16 per lane and round
       probe_exp_kernel<<<dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream>>>(iters, out);
       *work_per_launch = lanes * 16.0 * iters;
+      break;
+    case 3:   // bytes read from LDS: 8 reads of 16 bytes per lane and round
+      probe_lds_kernel<<<dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream>>>(iters, out);
+      *work_per_launch = lanes * 8.0 * 16.0 * iters;
       break;
     default:
       return fail(MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
