@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--full-length", action="store_true",
                     help="every sequence gets max_len tokens (no padding): shows what the attention kernels reach "
                          "without ragged tiles; not the benchmark configuration")
+    ap.add_argument("--seeds", type=int, default=1,
+                    help="also time the attention calls on this many draws of the workload's length recipe (seed offsets "
+                         "0..N-1) and report the mean: the ragged workloads have few, very unequal sequences")
     ap.add_argument("--ceilings", action="store_true",
                     help="also measure this machine's ceilings with probe kernels (bf16 MFMA, fp32 FMA, fp32 exp, row copy) "
                          "and print them beside the published peaks")
@@ -238,6 +241,8 @@ def main():
         out["next_rows"]["geglu_ffn_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
+    if args.seeds > 1:
+        out["attention_over_seeds"] = time_attention_over_seeds(mb, wl, args, dev)
     if args.ceilings:
         out["measured_ceilings"] = measure_ceilings(mb, dev)
     if args.copy_calibration:
@@ -290,6 +295,53 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
     res["shape"] = "T=%d W=%d" % (T, W)
     return res
+
+
+def time_attention_over_seeds(mb, wl, args, dev):
+    """Attention forward and backward on several draws of the workload (packed inputs prepared outside the timed
+    region; 20 launches of each between two events per draw)."""
+    import numpy as np
+    import torch
+    rows = []
+    for s in range(args.seeds):
+        batch = wl.make_batch(args.workload, seed_offset=s, batch=args.batch, full_length=args.full_length)
+        w = batch["workload"]
+        B, L, H, D = w.B, w.L, w.H, w.D
+        tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        lengths = batch["lengths"]
+        f_fwd, f_bwd = wl.attention_flops(lengths, H, D)
+        mask = torch.from_numpy(batch["mask"]).to(dev)
+        seqlens, cu, indices, meta = mb.mb_unpad_index(mask)
+        T, _ = mb.mb_read_meta(meta)
+        cap = B * L
+        packed = {}
+        for key in ("q", "k", "v", "do"):
+            t = torch.from_numpy(np.ascontiguousarray(batch[key].reshape(cap, H * D))).to(tdt).to(dev)
+            packed[key] = mb.mb_unpad(t, indices, cap, meta)[:T].view(T, H, D)
+        slopes = mb.mb_alibi_slopes(H).to(dev)
+        o, lse = mb.mb_alibi_attn_fwd(packed["q"], packed["k"], packed["v"], cu, L, slopes, batch["scale"])
+        dq, dk, dv = (torch.empty_like(packed["q"]) for _ in range(3))
+        ws = torch.empty(max(mb.mb_alibi_attn_bwd_workspace_bytes(B, T, L, H, D, mb.MB_BF16 if w.dtype == "bf16" else mb.MB_F32), 16),
+                         dtype=torch.uint8, device=dev)
+        fwd = lambda: mb.mb_alibi_attn_fwd(packed["q"], packed["k"], packed["v"], cu, L, slopes, batch["scale"], out=o, lse=lse)
+        bwd = lambda: mb.mb_alibi_attn_bwd(packed["do"], packed["q"], packed["k"], packed["v"], o, lse, cu, L, slopes,
+                                           batch["scale"], dq=dq, dk=dk, dv=dv, workspace=ws)
+        t_us = []
+        for fn in (fwd, bwd):
+            for _ in range(3):
+                fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(20):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            t_us.append(a.elapsed_time(b) * 1e3 / 20)
+        rows.append({"seed_offset": s, "T": int(T), "sum_len2": int((lengths.astype(np.int64) ** 2).sum()),
+                     "fwd_us": round(t_us[0], 1), "bwd_us": round(t_us[1], 1),
+                     "fwd_tflops": round(f_fwd / t_us[0] * 1e-6, 1), "bwd_tflops": round(f_bwd / t_us[1] * 1e-6, 1)})
+    return {"draws": rows, "mean_fwd_tflops": round(float(np.mean([r["fwd_tflops"] for r in rows])), 1),
+            "mean_bwd_tflops": round(float(np.mean([r["bwd_tflops"] for r in rows])), 1)}
 
 
 def measure_ceilings(mb, dev):
