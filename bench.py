@@ -387,7 +387,7 @@ def measure_ceilings(mb, dev):
 
 def time_geglu(mb, T, hidden, inter, dev):
     """GeGLU feed-forward, forward, on the packed tokens of the same batch ([T, hidden] -> [T, inter] ->
-    [T, hidden]), outside the timed step: 20 launches of each arrangement between two events.
+    [T, hidden]), outside the timed step: 20 launches of each arrangement between two events, after a warm-up.
     fused = mb_geglu_fwd (the activation runs on the accumulators of the first projection); the two
     unfused arrangements of the paper's appendix on GLU implementations are built from the same GEMM
     kernel: `sliced` = one double-width projection stored and sliced, `separate` = two projections; both
@@ -419,8 +419,12 @@ def time_geglu(mb, T, hidden, inter, dev):
 
     flops = 2.0 * T * hidden * 2 * inter + 2.0 * T * inter * hidden
     res = {"shape": "T=%d hidden=%d inter=%d" % (T, hidden, inter)}
+    # Steady state: the clocks of this part take some 50 to 100 ms of matrix-core load to settle (the first
+    # launches after the memory-bound attention step run about 15 % slower), so 200 untimed launches go first.
+    for _ in range(200):
+        fused()
     for name, fn in (("fused", fused), ("sliced", sliced), ("separate", separate)):
-        for _ in range(3):
+        for _ in range(10):
             fn()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
@@ -441,7 +445,7 @@ def time_geglu(mb, T, hidden, inter, dev):
     mb.mb_linear_fwd(x, w1v, y=hg)
     unit = 2.0 * T * hidden * inter
     for name, saved, units in (("bwd_recompute", None, 8.0), ("bwd_stored_projections", hg, 6.0)):
-        for _ in range(2):
+        for _ in range(10):
             mb.mb_geglu_bwd(dyt, x, w1v, w2, act, hg=saved, dx=dx, dw1v=dw1v, dw2=dw2, workspace=ws)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()

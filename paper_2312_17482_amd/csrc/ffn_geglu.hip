@@ -22,6 +22,7 @@
 
 
 
+
 namespace mb {
 namespace {
 
