@@ -8,7 +8,11 @@
  *   - "FlashAttention" + "Attention with Linear Biases" paragraphs, Eq. 1: exact softmax attention,
  *     computed tile-wise without materialising the score matrix, with the bias  -m_h * |i - j|
  *     added to the scores, bidirectional (mb_alibi_attn_fwd / mb_alibi_attn_bwd), m_h geometric with
- *     ratio 2^(-8/H) (mb_alibi_slopes).
+ *     ratio 2^(-8/H) (mb_alibi_slopes);
+ *   - the two neighbouring sublayers of the same block, on the packed token rows: "Low Precision
+ *     LayerNorm" paragraph with the residual add of Figure 1A (mb_add_layernorm_fwd / _bwd), and the
+ *     "Gated Linear Units" paragraph, Eq. 2, with the arrangements of the appendix on GLU
+ *     implementations (mb_geglu_fwd / mb_geglu_bwd, mb_linear_fwd, mb_gelu_gate).
  *
  * Conventions common to every call
  *   Pointers   "dev" = device (HBM) pointer, "host" = host pointer.  The caller allocates and owns
