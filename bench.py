@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--full-length", action="store_true",
                     help="every sequence gets max_len tokens (no padding): shows what the attention kernels reach "
                          "without ragged tiles; not the benchmark configuration")
+    ap.add_argument("--length-sweep", action="store_true",
+                    help="also time attention forward + backward, packed against padded, at max_len 128 .. 2048 with the "
+                         "same number of positions (32768) and the bert_base length recipe scaled to each max_len")
     ap.add_argument("--seeds", type=int, default=1,
                     help="also time the attention calls on this many draws of the workload's length recipe (seed offsets "
                          "0..N-1) and report the mean: the ragged workloads have few, very unequal sequences")
@@ -241,6 +244,8 @@ def main():
         out["next_rows"]["geglu_ffn_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
+    if args.length_sweep:
+        out["length_sweep"] = time_length_sweep(mb, wl, dev)
     if args.seeds > 1:
         out["attention_over_seeds"] = time_attention_over_seeds(mb, wl, args, dev)
     if args.ceilings:
@@ -295,6 +300,55 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
     res["shape"] = "T=%d W=%d" % (T, W)
     return res
+
+
+def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
+    """What removing padding saves in attention as max_len grows (the paper's own code ran attention over the
+    padded batch; its appendix on sequence length trains at 128 .. 2048).  For each max_len L: B = 32768 / L
+    sequences, lengths by the bert_base recipe scaled to L (L with probability 0.6, else uniform in
+    [L/8, L-1]; NumPy default_rng(20231217 + L)), Q, K, V ~ N(0,1)/8; forward + backward on the packed tokens
+    and on all B*L positions, 10 launches each between two events."""
+    import numpy as np
+    import torch
+    bf = torch.bfloat16
+    rows = []
+    for L in (128, 256, 512, 1024, 2048):
+        B = positions // L
+        rng = np.random.default_rng(20231217 + L)
+        full = rng.random(B) < 0.6
+        lengths = np.where(full, L, rng.integers(L // 8, L, size=B)).astype(np.int32)
+        T = int(lengths.sum())
+        f_fwd, f_bwd = wl.attention_flops(lengths, H, D)
+        slopes = mb.mb_alibi_slopes(H).to(dev)
+        res = {"max_len": L, "B": B, "T": T, "fraction_real": round(T / positions, 4)}
+        for name, lens in (("varlen", lengths), ("padded", np.full(B, L, dtype=np.int32))):
+            n_tok = int(lens.sum())
+            cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+            qkv = (torch.randn(n_tok, 3, H, D, device=dev) * 0.125).to(bf)
+            do = torch.randn(n_tok, H, D, device=dev).to(bf)
+            o = torch.empty(n_tok, H, D, dtype=bf, device=dev)
+            lse = torch.empty(H, n_tok, dtype=torch.float32, device=dev)
+            dqkv = torch.empty_like(qkv)
+            ws = torch.empty(max(mb.mb_alibi_attn_bwd_workspace_bytes(B, n_tok, L, H, D, mb.MB_BF16), 16), dtype=torch.uint8,
+                             device=dev)
+
+            def run():
+                mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, 0.125, out=o, lse=lse)
+                mb.mb_alibi_attn_bwd(do, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, L, slopes, 0.125, dq=dqkv[:, 0],
+                                     dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
+            for _ in range(3):
+                run()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                run()
+            b.record()
+            torch.cuda.synchronize()
+            res[name + "_fwd_bwd_us"] = round(a.elapsed_time(b) * 1e3 / 10, 1)
+        res["varlen_tflops"] = round((f_fwd + f_bwd) / res["varlen_fwd_bwd_us"] * 1e-6, 1)
+        res["speedup_from_unpadding"] = round(res["padded_fwd_bwd_us"] / res["varlen_fwd_bwd_us"], 3)
+        rows.append(res)
+    return rows
 
 
 def time_attention_over_seeds(mb, wl, args, dev):
