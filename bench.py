@@ -242,6 +242,7 @@ def main():
                         "padded_attention_comparison": time_padded_vs_varlen(mb, locals())}
     if bf16 and (H * D) % 256 == 0:
         out["next_rows"]["geglu_ffn_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
+        out["next_rows"]["mlm_head_on_masked_rows"] = time_mlm_head(mb, T_host, H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
     if args.length_sweep:
@@ -299,6 +300,45 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_GBs"] = round(nbytes / (us * 1e-6) * 1e-9, 1)
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
     res["shape"] = "T=%d W=%d" % (T, W)
+    return res
+
+
+def time_mlm_head(mb, T, hidden, dev, vocab=30528, mask_ratio=0.30):
+    """The output projection to the vocabulary on the masked token rows only ("Vocab Size as a Multiple of
+    64" paragraph: 30528; the training recipe masks 30 % of the tokens): mb_unpad gathers the masked rows of
+    the packed activations, mb_linear_fwd projects them; against projecting every token.  20 launches each
+    between two events after a warm-up; the logits buffers are scratch."""
+    import torch
+    bf = torch.bfloat16
+    x = torch.randn(T, hidden, device=dev).to(bf)
+    wv = (torch.randn(vocab, hidden, device=dev) * 0.02).to(bf)
+    n_masked = int(round(T * mask_ratio))
+    rows = torch.sort(torch.randperm(T, device=dev)[:n_masked]).values.to(torch.int32)
+    xm = torch.empty((n_masked, hidden), dtype=bf, device=dev)
+    logits_m = torch.empty((n_masked, vocab), dtype=bf, device=dev)
+    logits_all = torch.empty((T, vocab), dtype=bf, device=dev)
+
+    def masked():
+        mb.mb_unpad(x, rows, n_masked, None, out=xm)
+        mb.mb_linear_fwd(xm, wv, y=logits_m)
+
+    def every():
+        mb.mb_linear_fwd(x, wv, y=logits_all)
+
+    res = {"shape": "T=%d hidden=%d vocab=%d masked_rows=%d" % (T, hidden, vocab, n_masked)}
+    for name, fn, nrows in (("masked_rows", masked, n_masked), ("all_rows", every, T)):
+        for _ in range(20):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(20):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) * 1e3 / 20
+        res[name + "_us"] = round(us, 1)
+        res[name + "_tflops"] = round(2.0 * nrows * hidden * vocab / us * 1e-6, 1)
+    res["speedup_from_masked_rows_only"] = round(res["all_rows_us"] / res["masked_rows_us"], 2)
     return res
 
 

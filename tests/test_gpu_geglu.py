@@ -100,7 +100,7 @@ def test_geglu_empty_input(mb):
 
 
 @pytest.mark.parametrize("T,n_in,n_out", [(300, 768, 6144), (513, 3072, 768), (64, 128, 192), (1000, 256, 1024),
-                                          (257, 640, 384)])
+                                          (257, 640, 384), (400, 768, 30528)])   # last: the paper's vocabulary size
 def test_linear_forward_parity(mb, T, n_in, n_out):
     print("linear T=%d n_in=%d n_out=%d" % (T, n_in, n_out), flush=True)
     rng = np.random.default_rng(21)
