@@ -443,12 +443,16 @@ def measure_ceilings(mb, dev):
     row copy through the gather kernel, once with 128 MiB each way (as large as the 256 MB Infinity Cache) and once
     with 1 GiB each way (far beyond it)."""
     import torch
-    scratch = torch.zeros(4, dtype=torch.float32, device=dev)
+    scratch = torch.zeros(4 + (16 << 20) // 4, dtype=torch.float32, device=dev)   # 4 floats + 16 MiB for probe 7
     res = {}
     for name, kind, iters, unit, scale in (("mfma_bf16_32x32x16", 0, 2000, "TFLOP/s", 1e-12),
                                            ("valu_fp32_fma", 1, 20000, "TFLOP/s", 1e-12),
                                            ("valu_fp32_exp", 2, 5000, "Texp/s", 1e-12),
-                                           ("lds_read_16B", 3, 5000, "TB/s", 1e-12)):
+                                           ("lds_read_16B", 3, 5000, "TB/s", 1e-12),
+                                           ("gemm_inner_loop_from_lds", 4, 200, "TFLOP/s", 1e-12),
+                                           ("gemm_inner_loop_from_lds_with_barrier", 5, 200, "TFLOP/s", 1e-12),
+                                           ("gemm_inner_loop_plus_lds_writes", 6, 200, "TFLOP/s", 1e-12),
+                                           ("gemm_inner_loop_plus_lds_writes_and_l2_loads", 7, 200, "TFLOP/s", 1e-12)):
         for _ in range(3):
             work = mb.mb_probe_ceiling(kind, iters, scratch)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

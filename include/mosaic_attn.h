@@ -278,7 +278,12 @@ MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_strid
  *          1: fp32 fused multiply-add on the vector unit (work = flops)
  *          2: fp32 exponential on the vector unit (work = exponentials)
  *          3: 16-byte LDS reads in the pattern of the GEMM fragments (work = bytes)
- *   iters  rounds per lane (> 0).      out  dev, one float, scratch (never written in practice).
+ *          4: the GEMM kernels' inner loop fed from LDS, without global loads, LDS writes or barriers (work = flops)
+ *          5: the same with the GEMM's one workgroup barrier per k step
+ *          6: the same plus the GEMM's 16 LDS writes per thread and k step
+ *          7: the same plus its 16 global loads per thread and k step, from 16 MiB that stay in L2
+ *   iters  rounds per lane (> 0).      out  dev, 4 floats of scratch (never written in practice); for kind 7 they
+ *          are followed by the 16 MiB the probe reads (any content).
  *   work_per_launch  host, written.
  */
 MB_API mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream);

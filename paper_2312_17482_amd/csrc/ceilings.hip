@@ -88,9 +88,82 @@ __global__ __launch_bounds__(256) void probe_lds_kernel(int iters, float* __rest
   if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) out[0] = 1.f;
 }
 
+// The inner loop of the GEMM kernels without their memory traffic: one workgroup of 4 waves per compute
+// unit (the LDS allocation sees to that), each wave 16 accumulator tiles, per k sub-step 8 fragment reads
+// of 16 bytes (double-buffered) and 16 matrix instructions, in the same fenced issue order; no global
+// loads, no LDS writes; `with_barrier` adds the GEMM's one workgroup barrier per 4 sub-steps.
+template <bool kBarrier, bool kWrites, bool kLoads>
+__global__ __launch_bounds__(256, 1) void probe_gemm_loop_kernel(int iters, float* __restrict__ out,
+                                                                 const uint16_t* __restrict__ src) {
+  __shared__ __attribute__((aligned(16))) uint16_t tile[2 * 512 * 72];
+  for (int i = threadIdx.x; i < 2 * 512 * 72; i += 256) tile[i] = (uint16_t)(0x3c00 + (i & 63));
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane & 31, g = lane >> 5, wm = wave >> 1, wn = wave & 1;
+  const uint16_t* xb = &tile[(wm * 128 + c) * 72 + g * 8];
+  const uint16_t* wb = &tile[(256 + wn * 128 + c) * 72 + g * 8];
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+  bf16x8 wf[2][4], xf[2][4];
+  int off = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    xf[0][i] = lds_read8(xb + i * 32 * 72);
+    wf[0][i] = lds_read8(wb + i * 32 * 72);
+  }
+  // staging registers of a k step (16 x 16 bytes per thread), written to the other LDS stage / loaded from a
+  // 64 KB region per workgroup that stays in L2
+  u32x4 st[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st[i] = u32x4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+  const int lrow = threadIdx.x >> 3, lchunk = (threadIdx.x & 7) * 8;
+  uint16_t* dep = &tile[512 * 72 + lrow * 72 + lchunk];
+  const uint16_t* gsrc = src + (size_t)(blockIdx.x & 255) * 32768 + lrow * 64 + lchunk;
+  for (int it = 0; it < iters; ++it) {
+    asm volatile("" : "+v"(off));
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kBarrier && kk == 3) __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          const int slot = 4 * q + mb;
+          if (slot < 8) {
+            const int nk = (kk + 1) & 3;
+            if (slot < 4) xf[(kk + 1) & 1][slot] = lds_read8(xb + off + slot * 32 * 72 + nk * 16);
+            else wf[(kk + 1) & 1][slot - 4] = lds_read8(wb + off + (slot - 4) * 32 * 72 + nk * 16);
+          }
+          if (kWrites && kk == 0) *reinterpret_cast<u32x4*>(dep + off + slot * 32 * 72) = st[slot];
+          if (kLoads && kk == 1)
+            st[slot] = *reinterpret_cast<const u32x4*>(gsrc + off + slot * 2048);
+          __builtin_amdgcn_sched_barrier(0);
+          acc[q][mb] = mfma32(wf[kk & 1][q], xf[kk & 1][mb], acc[q][mb]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum += acc[a][b][v];
+  if (sum == 12345.678f) out[0] = sum;
+}
+
 }  // namespace
 
 mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch, hipStream_t stream) {
+  // kind 7 reads a 16 MiB source that starts 4 floats into `out` (the caller sizes `out` accordingly)
+  const uint16_t* src = reinterpret_cast<const uint16_t*>(out + 4);
   const double lanes = (double)kProbeBlocks * kProbeThreads;
   switch (kind) {
     case 0:   // flops: 8 instructions of 2*32*32*16 per wave and round
@@ -108,6 +181,16 @@ mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch,
     case 3:   // bytes read from LDS: 8 reads of 16 bytes per lane and round
       probe_lds_kernel<<<dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream>>>(iters, out);
       *work_per_launch = lanes * 8.0 * 16.0 * iters;
+      break;
+    case 4:   // flops of the GEMM inner loop fed from LDS, no barrier: 64 instructions per wave and round
+    case 5:   // the same with one workgroup barrier per round
+    case 6:   // the same plus the 16 LDS writes per thread and k step
+    case 7:   // the same plus the 16 global loads per thread and k step (from a region that stays in L2)
+      if (kind == 4) probe_gemm_loop_kernel<false, false, false><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
+      else if (kind == 5) probe_gemm_loop_kernel<true, false, false><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
+      else if (kind == 6) probe_gemm_loop_kernel<true, true, false><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
+      else probe_gemm_loop_kernel<true, true, true><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
+      *work_per_launch = 256.0 * 4 * 4 * 64.0 * 32768.0 * iters;
       break;
     default:
       return fail(MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
