@@ -68,12 +68,22 @@ constexpr int kBuf = 2 * kHalf;                     // one buffer: two operand t
 
 // ------------------------------------------------------------------------------------------------ dK, dV
 // One workgroup per (sequence, head, 128 keys); wave w owns keys 32w.. and streams all queries.
+//
+// kDirect (both kernels): token t sits at row t of the activation buffers and a sequence's rows span fewer
+// than 2^31 bytes.  Then the rows of a streamed tile are fetched with buffer loads whose descriptor starts
+// at the tile's first row and ends at the sequence's last one: the address is scalar arithmetic plus one
+// constant per-lane offset, and rows past the end read as zeros without a compare.  Otherwise every row's
+// address is formed per lane (row index looked up in token_rows when given).
+constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+
+template <bool kDirect>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
-    const int32_t* __restrict__ rows) {
+    const int32_t* __restrict__ token_rows) {
+  const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: Q tile, dO tile
   __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
   __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
@@ -86,7 +96,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   const int kv0 = blockIdx.x * kTile;
   if (kv0 >= n) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps per-wave branches scalar
   const int c = lane & 31, g = lane >> 5;
   const int kw = kv0 + 32 * wave;
   const bool wave_active = kw < n;
@@ -130,15 +141,30 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   const uint16_t* gh = dout + h * kD + st_col;
   u32x4 tq[2], tg[2];
   float tl = 0.f, td = 0.f;
+  const uint32_t qoff = ((uint32_t)st_row * (uint32_t)qs + (uint32_t)(h * kD + st_col)) * 2u;
+  const uint32_t goff = ((uint32_t)st_row * (uint32_t)dos + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int i0) {
+    if (kDirect) {
+      const int left = n - i0;      // > 0: rows i0 .. n-1 exist
+      const __amdgpu_buffer_rsrc_t qr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(q) + (int64_t)(start + i0) * qs, 0, left * (int)qs * 2, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t gr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(dout) + (int64_t)(start + i0) * dos, 0, left * (int)dos * 2, kRsrcFlags);
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      tq[it] = tg[it] = u32x4{0u, 0u, 0u, 0u};
-      const int i = i0 + 32 * it + st_row;
-      if (i < n) {
-        const int64_t gr = tok_row(rows, start + i);
-        tq[it] = *reinterpret_cast<const u32x4*>(qh + gr * qs);
-        tg[it] = *reinterpret_cast<const u32x4*>(gh + gr * dos);
+      for (int it = 0; it < 2; ++it) {
+        tq[it] = __builtin_amdgcn_raw_buffer_load_b128(qr, qoff + (uint32_t)it * 64u * (uint32_t)qs, 0, 0);
+        tg[it] = __builtin_amdgcn_raw_buffer_load_b128(gr, goff + (uint32_t)it * 64u * (uint32_t)dos, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        tq[it] = tg[it] = u32x4{0u, 0u, 0u, 0u};
+        const int i = i0 + 32 * it + st_row;
+        if (i < n) {
+          const int64_t gr = tok_row(rows, start + i);
+          tq[it] = *reinterpret_cast<const u32x4*>(qh + gr * qs);
+          tg[it] = *reinterpret_cast<const u32x4*>(gh + gr * dos);
+        }
       }
     }
     if (tid < kTileS) {
@@ -267,11 +293,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 
 // ------------------------------------------------------------------------------------------------ dQ
 // One workgroup per (sequence, head, 128 queries); wave w owns queries 32w.. and streams all keys.
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
+// (at most 168 registers, so that three workgroups share a compute unit)
+template <bool kDirect>
+__global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
-    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ rows) {
+    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows) {
+  const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
   __shared__ int s_seq;
 
@@ -282,7 +311,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int q0 = blockIdx.x * kTile;
   if (q0 >= n) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int c = lane & 31, g = lane >> 5;
   const int qw = q0 + 32 * wave;
   const bool wave_active = qw < n;
@@ -328,7 +358,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const uint16_t* kh = k + h * kD + st_col;
   const uint16_t* vh = v + h * kD + st_col;
   u32x4 tk[2], tv[2];
+  const uint32_t koff = ((uint32_t)st_row * (uint32_t)ks + (uint32_t)(h * kD + st_col)) * 2u;
+  const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {
+    if (kDirect) {
+      const int left = n - j0;      // > 0: rows j0 .. n-1 exist
+      const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(k) + (int64_t)(start + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(v) + (int64_t)(start + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, koff + (uint32_t)it * 64u * (uint32_t)ks, 0, 0);
+        tv[it] = __builtin_amdgcn_raw_buffer_load_b128(vr, voff + (uint32_t)it * 64u * (uint32_t)vs, 0, 0);
+      }
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
@@ -730,14 +775,27 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   const int tiles = (s.max_seqlen + kTile - 1) / kTile;
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
-                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows);
+  // buffer-load path: rows in packed order, and a sequence's rows within 2^31 bytes of its first
+  int64_t widest = qs > ks ? qs : ks;
+  widest = widest > vs ? widest : vs;
+  widest = widest > dos ? widest : dos;
+  const bool direct = !s.token_rows && (int64_t)s.max_seqlen * widest * 2 < ((int64_t)1 << 31);
+#define MB_LAUNCH_DKV(R)                                                                                           \
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,   \
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows)
+  if (direct) MB_LAUNCH_DKV(true);
+  else MB_LAUNCH_DKV(false);
+#undef MB_LAUNCH_DKV
   st = check_launch("attn_bwd_dkv_kernel");
   if (st != MB_OK) return st;
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,
-                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows);
+#define MB_LAUNCH_DQ(R)                                                                                            \
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows)
+  if (direct) MB_LAUNCH_DQ(true);
+  else MB_LAUNCH_DQ(false);
+#undef MB_LAUNCH_DQ
   return check_launch("attn_bwd_dq_kernel");
 }
 

@@ -32,10 +32,18 @@ constexpr int kVStride = 80;   // LDS row pitch of V in bf16 (160 B): 4-row tran
 constexpr int kTileK = 64;                                        // keys per LDS tile
 constexpr int kBufElems = kTileK * kKStride + kTileK * kVStride;  // one K tile + one V tile
 
+//
+// kDirect: token t sits at row t of the activation buffers and a sequence's K and V rows span fewer than
+// 2^31 bytes.  Then the K/V rows of a tile are fetched with buffer loads whose descriptor starts at the
+// tile's first row and ends at the sequence's last one: the address is scalar arithmetic plus one constant
+// per-lane offset, and rows past the end read as zeros without a compare.  Otherwise every row's address
+// is formed per lane (row index looked up in token_rows when given).
+template <bool kDirect>
 __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
-    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows) {
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ token_rows) {
+  const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
   __shared__ int s_seq;
 
@@ -46,7 +54,8 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const int q0 = blockIdx.x * kBlockQ;
   if (q0 >= n) return;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps per-wave branches scalar
   const int c = lane & 31, g = lane >> 5;
   const int qw = q0 + 32 * wave;          // first query of this wave
   const bool wave_active = qw < n;
@@ -58,7 +67,23 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const uint16_t* vh = v + h * kD + st_col;
 
   u32x4 tk[2], tv[2];
+  constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+  const uint32_t koff = ((uint32_t)st_row * (uint32_t)ks + (uint32_t)(h * kD + st_col)) * 2u;
+  const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {   // rows j0 + 32it + st_row of K and V -> registers (zeros past the end)
+    if (kDirect) {
+      const int left = n - j0;      // > 0: rows j0 .. n-1 exist
+      const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(k) + (int64_t)(start + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<uint16_t*>(v) + (int64_t)(start + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, koff + (uint32_t)it * 64u * (uint32_t)ks, 0, 0);
+        tv[it] = __builtin_amdgcn_raw_buffer_load_b128(vr, voff + (uint32_t)it * 64u * (uint32_t)vs, 0, 0);
+      }
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
@@ -165,14 +190,14 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     }
     m_run = m_new;
     const float mc = m_new * cs;
-    float lsum = 0.f;
+    float lsum[4] = {0.f, 0.f, 0.f, 0.f};   // four short chains of additions instead of one long one
 #pragma unroll
     for (int jb = 0; jb < 2; ++jb) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
         sacc[jb][i] = p;
-        lsum += p;
+        lsum[i & 3] += p;
       }
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
@@ -188,7 +213,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
         }
       }
     }
-    l_run += lsum;
+    l_run += (lsum[0] + lsum[1]) + (lsum[2] + lsum[3]);
   };
 
 #pragma unroll 1
@@ -462,9 +487,16 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
                          (uint16_t*)o, os, lse, s.T, s.token_rows);
     return check_launch("attn_fwd_short_kernel");
   }
-  hipLaunchKernelGGL(attn_fwd_tiled_kernel, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
-                     (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                     (uint16_t*)o, os, lse, s.T, s.token_rows);
+  // buffer-load path: rows in packed order, and a sequence's K / V rows within 2^31 bytes of its first
+  const int64_t span = (int64_t)s.max_seqlen * (ks > vs ? ks : vs) * 2;
+  if (!s.token_rows && span < ((int64_t)1 << 31))
+    hipLaunchKernelGGL(attn_fwd_tiled_kernel<true>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
+                       (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
+                       (uint16_t*)o, os, lse, s.T, s.token_rows);
+  else
+    hipLaunchKernelGGL(attn_fwd_tiled_kernel<false>, dim3(tiles, s.H, s.B), dim3(256), 0, stream,
+                       (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens,
+                       s.slopes, s.scale, (uint16_t*)o, os, lse, s.T, s.token_rows);
   return check_launch("attn_fwd_tiled_kernel");
 }
 
