@@ -283,7 +283,7 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
 size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt) {
   if (B < 0 || T < 0 || max_seqlen < 0 || H <= 0 || D <= 0 || D > 128) return 0;
   if (dt != MB_F32 && dt != MB_BF16) return 0;
-  return align_up((size_t)H * (size_t)T * sizeof(float), 256);  // Delta, [H, T] float
+  return attn_bwd_workspace_bytes(B, H, T);   // Delta [H, T] float + sequence order [B] int32
 }
 
 mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v, const void* o,

@@ -29,11 +29,29 @@ constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
 
 // ------------------------------------------------------------------------------------------------ delta
 // 8 lanes per (token, head) row: 16 bytes of dO and O each, then a 3-step butterfly.
+//
+// The first blocks also rank the sequences by length for the two kernels that follow: order[r] = the
+// sequence with r longer ones before it (ties by index), so that those kernels dispatch their heaviest
+// workgroups first and short ones fill the tail.  One thread per sequence counts the larger keys
+// (length, reversed index); `order` is NULL when there are too many sequences for that to pay.
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
                                                              const uint16_t* __restrict__ o, int64_t dos, int64_t os,
                                                              int T, int H, const int32_t* __restrict__ cu, int B,
                                                              float* __restrict__ delta,
-                                                             const int32_t* __restrict__ rows) {
+                                                             const int32_t* __restrict__ rows,
+                                                             int32_t* __restrict__ order) {
+  if (order != nullptr && (int)blockIdx.x * 256 < B) {
+    const int cand = blockIdx.x * 256 + threadIdx.x;
+    if (cand < B) {
+      const int len = cu[cand + 1] - cu[cand];
+      int r = 0;
+      for (int other = 0; other < B; ++other) {   // uniform index: scalar loads
+        const int lo = cu[other + 1] - cu[other];
+        r += (lo > len || (lo == len && other < cand)) ? 1 : 0;
+      }
+      order[r] = cand;
+    }
+  }
   const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
   const int sub = threadIdx.x & 7;
   float acc = 0.f;
@@ -61,7 +79,8 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
 // Both kernels below stream their second operand in tiles of 64 rows through two LDS buffers: while
 // one tile is consumed the next travels HBM -> registers -> the other buffer (one barrier per tile).
 // Global memory is touched only as full 128-byte rows of one head; fragments and output rows pass
-// through LDS.  Workgroups are dispatched longest sequence first.
+// through LDS.  Workgroups are dispatched longest sequence first (`order`, written by the delta kernel;
+// NULL: in the order given).
 constexpr int kTileS = 64;                          // rows of a streamed tile
 constexpr int kHalf = kTileS * kPitch;              // elements of one streamed operand tile (4608)
 constexpr int kBuf = 2 * kHalf;                     // one buffer: two operand tiles (= 128 rows of pitch 72)
@@ -82,17 +101,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
-    const int32_t* __restrict__ token_rows) {
+    const int32_t* __restrict__ token_rows, const int32_t* __restrict__ order) {
   const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: Q tile, dO tile
   __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
   __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
-  __shared__ int s_seq;
 
-  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
-  const int h = blockIdx.y;
+  const int b = order ? order[blockIdx.z] : (int)blockIdx.z;
   const int start = cu[b];
   const int n = cu[b + 1] - start;
+  const int h = blockIdx.y;
   const int kv0 = blockIdx.x * kTile;
   if (kv0 >= n) return;
 
@@ -299,15 +317,15 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
-    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows) {
+    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows,
+    const int32_t* __restrict__ order) {
   const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
-  __shared__ int s_seq;
 
-  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
-  const int h = blockIdx.y;
+  const int b = order ? order[blockIdx.z] : (int)blockIdx.z;
   const int start = cu[b];
   const int n = cu[b + 1] - start;
+  const int h = blockIdx.y;
   const int q0 = blockIdx.x * kTile;
   if (q0 >= n) return;
 
@@ -769,9 +787,15 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
     return check_launch("attn_bwd_fused128_kernel");
   }
   const int64_t rows = (int64_t)s.T * s.H;
-  hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, stream,
-                     (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B, delta_ws,
-                     s.token_rows);
+  // the sequence order sits behind Delta in the workspace
+  int32_t* order = s.B <= kSortMaxB
+                       ? reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T))
+                       : nullptr;
+  const int64_t delta_blocks = (rows + 31) / 32, order_blocks = order ? (s.B + 255) / 256 : 0;
+  hipLaunchKernelGGL(attn_bwd_delta_kernel,
+                     dim3((unsigned)(delta_blocks > order_blocks ? delta_blocks : order_blocks)), dim3(256), 0,
+                     stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B,
+                     delta_ws, s.token_rows, order);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   const int tiles = (s.max_seqlen + kTile - 1) / kTile;
@@ -783,7 +807,8 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
 #define MB_LAUNCH_DKV(R)                                                                                           \
   hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,   \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows)
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows,   \
+                     order)
   if (direct) MB_LAUNCH_DKV(true);
   else MB_LAUNCH_DKV(false);
 #undef MB_LAUNCH_DKV
@@ -792,7 +817,7 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
 #define MB_LAUNCH_DQ(R)                                                                                            \
   hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows)
+                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows, order)
   if (direct) MB_LAUNCH_DQ(true);
   else MB_LAUNCH_DQ(false);
 #undef MB_LAUNCH_DQ

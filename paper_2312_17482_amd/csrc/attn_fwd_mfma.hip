@@ -45,12 +45,11 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ token_rows) {
   const int32_t* rows = kDirect ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
-  __shared__ int s_seq;
+  __shared__ __attribute__((aligned(16))) uint32_t s_sort[kSortLdsWords];
 
-  const int b = seq_by_length_rank(cu, gridDim.z, blockIdx.z, &s_seq);
+  int start, n;
+  seq_by_length_rank(cu, gridDim.z, blockIdx.z, s_sort, &start, &n);
   const int h = blockIdx.y;
-  const int start = cu[b];
-  const int n = cu[b + 1] - start;
   const int q0 = blockIdx.x * kBlockQ;
   if (q0 >= n) return;
 
