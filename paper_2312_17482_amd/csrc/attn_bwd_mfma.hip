@@ -88,21 +88,22 @@ constexpr int kBuf = 2 * kHalf;                     // one buffer: two operand t
 // ------------------------------------------------------------------------------------------------ dK, dV
 // One workgroup per (sequence, head, 128 keys); wave w owns keys 32w.. and streams all queries.
 //
-// kDirect (both kernels): token t sits at row t of the activation buffers and a sequence's rows span fewer
-// than 2^31 bytes.  Then the rows of a streamed tile are fetched with buffer loads whose descriptor starts
-// at the tile's first row and ends at the sequence's last one: the address is scalar arithmetic plus one
-// constant per-lane offset, and rows past the end read as zeros without a compare.  Otherwise every row's
-// address is formed per lane (row index looked up in token_rows when given).
+// kMode (both kernels; see kRowsIdentity .. in common.h): for a sequence whose tokens sit in consecutive
+// rows of the activation buffers, spanning fewer than 2^31 bytes, the rows of a streamed tile are fetched
+// with buffer loads whose descriptor starts at the tile's first row and ends at the sequence's last one:
+// the address is scalar arithmetic plus one constant per-lane offset, and rows past the end read as
+// zeros without a compare.  Otherwise every row's address is formed per lane (row index looked up in
+// token_rows when given).
 constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
 
-template <bool kDirect>
+template <int kMode>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
     const int32_t* __restrict__ token_rows, const int32_t* __restrict__ order) {
-  const int32_t* rows = kDirect ? nullptr : token_rows;
+  const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: Q tile, dO tile
   __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
   __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
@@ -113,6 +114,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   const int h = blockIdx.y;
   const int kv0 = blockIdx.x * kTile;
   if (kv0 >= n) return;
+  // first buffer row of the sequence, and whether its tokens sit in consecutive rows
+  const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
+  const bool contig =
+      kMode == kRowsIdentity ||
+      (kMode == kRowsMaybeContiguous && __builtin_amdgcn_readfirstlane(rows[start + n - 1]) - row0 == n - 1);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps per-wave branches scalar
@@ -162,12 +168,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   const uint32_t qoff = ((uint32_t)st_row * (uint32_t)qs + (uint32_t)(h * kD + st_col)) * 2u;
   const uint32_t goff = ((uint32_t)st_row * (uint32_t)dos + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int i0) {
-    if (kDirect) {
+    if (contig) {
       const int left = n - i0;      // > 0: rows i0 .. n-1 exist
       const __amdgpu_buffer_rsrc_t qr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(q) + (int64_t)(start + i0) * qs, 0, left * (int)qs * 2, kRsrcFlags);
+          const_cast<uint16_t*>(q) + (int64_t)(row0 + i0) * qs, 0, left * (int)qs * 2, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t gr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(dout) + (int64_t)(start + i0) * dos, 0, left * (int)dos * 2, kRsrcFlags);
+          const_cast<uint16_t*>(dout) + (int64_t)(row0 + i0) * dos, 0, left * (int)dos * 2, kRsrcFlags);
 #pragma unroll
       for (int it = 0; it < 2; ++it) {
         tq[it] = __builtin_amdgcn_raw_buffer_load_b128(qr, qoff + (uint32_t)it * 64u * (uint32_t)qs, 0, 0);
@@ -312,14 +318,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 // ------------------------------------------------------------------------------------------------ dQ
 // One workgroup per (sequence, head, 128 queries); wave w owns queries 32w.. and streams all keys.
 // (at most 168 registers, so that three workgroups share a compute unit)
-template <bool kDirect>
+template <int kMode>
 __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows,
     const int32_t* __restrict__ order) {
-  const int32_t* rows = kDirect ? nullptr : token_rows;
+  const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
 
   const int b = order ? order[blockIdx.z] : (int)blockIdx.z;
@@ -328,6 +334,10 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const int h = blockIdx.y;
   const int q0 = blockIdx.x * kTile;
   if (q0 >= n) return;
+  const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
+  const bool contig =
+      kMode == kRowsIdentity ||
+      (kMode == kRowsMaybeContiguous && __builtin_amdgcn_readfirstlane(rows[start + n - 1]) - row0 == n - 1);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -379,12 +389,12 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const uint32_t koff = ((uint32_t)st_row * (uint32_t)ks + (uint32_t)(h * kD + st_col)) * 2u;
   const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {
-    if (kDirect) {
+    if (contig) {
       const int left = n - j0;      // > 0: rows j0 .. n-1 exist
       const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(k) + (int64_t)(start + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
+          const_cast<uint16_t*>(k) + (int64_t)(row0 + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(v) + (int64_t)(start + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
+          const_cast<uint16_t*>(v) + (int64_t)(row0 + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
 #pragma unroll
       for (int it = 0; it < 2; ++it) {
         tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, koff + (uint32_t)it * 64u * (uint32_t)ks, 0, 0);
@@ -799,18 +809,19 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   const int tiles = (s.max_seqlen + kTile - 1) / kTile;
-  // buffer-load path: rows in packed order, and a sequence's rows within 2^31 bytes of its first
+  // buffer-load path: a sequence's rows within 2^31 bytes of its first
   int64_t widest = qs > ks ? qs : ks;
   widest = widest > vs ? widest : vs;
   widest = widest > dos ? widest : dos;
-  const bool direct = !s.token_rows && (int64_t)s.max_seqlen * widest * 2 < ((int64_t)1 << 31);
+  const bool narrow = (int64_t)s.max_seqlen * widest * 2 < ((int64_t)1 << 31);
 #define MB_LAUNCH_DKV(R)                                                                                           \
   hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,   \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
                      s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows,   \
                      order)
-  if (direct) MB_LAUNCH_DKV(true);
-  else MB_LAUNCH_DKV(false);
+  if (!narrow) MB_LAUNCH_DKV(kRowsPerLane);
+  else if (s.token_rows) MB_LAUNCH_DKV(kRowsMaybeContiguous);
+  else MB_LAUNCH_DKV(kRowsIdentity);
 #undef MB_LAUNCH_DKV
   st = check_launch("attn_bwd_dkv_kernel");
   if (st != MB_OK) return st;
@@ -818,8 +829,9 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
                      s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows, order)
-  if (direct) MB_LAUNCH_DQ(true);
-  else MB_LAUNCH_DQ(false);
+  if (!narrow) MB_LAUNCH_DQ(kRowsPerLane);
+  else if (s.token_rows) MB_LAUNCH_DQ(kRowsMaybeContiguous);
+  else MB_LAUNCH_DQ(kRowsIdentity);
 #undef MB_LAUNCH_DQ
   return check_launch("attn_bwd_dq_kernel");
 }

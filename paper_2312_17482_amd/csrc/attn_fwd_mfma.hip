@@ -33,17 +33,17 @@ constexpr int kTileK = 64;                                        // keys per LD
 constexpr int kBufElems = kTileK * kKStride + kTileK * kVStride;  // one K tile + one V tile
 
 //
-// kDirect: token t sits at row t of the activation buffers and a sequence's K and V rows span fewer than
-// 2^31 bytes.  Then the K/V rows of a tile are fetched with buffer loads whose descriptor starts at the
-// tile's first row and ends at the sequence's last one: the address is scalar arithmetic plus one constant
-// per-lane offset, and rows past the end read as zeros without a compare.  Otherwise every row's address
-// is formed per lane (row index looked up in token_rows when given).
-template <bool kDirect>
+// kMode (see kRowsIdentity .. in common.h): for a sequence whose tokens sit in consecutive rows of the
+// activation buffers, spanning fewer than 2^31 bytes, the K/V rows of a tile are fetched with buffer loads
+// whose descriptor starts at the tile's first row and ends at the sequence's last one: the address is
+// scalar arithmetic plus one constant per-lane offset, and rows past the end read as zeros without a
+// compare.  Otherwise every row's address is formed per lane (row index looked up in token_rows when given).
+template <int kMode>
 __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
     uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ token_rows) {
-  const int32_t* rows = kDirect ? nullptr : token_rows;
+  const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
   __shared__ __attribute__((aligned(16))) uint32_t s_sort[kSortLdsWords];
 
@@ -52,6 +52,11 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const int h = blockIdx.y;
   const int q0 = blockIdx.x * kBlockQ;
   if (q0 >= n) return;
+  // first buffer row of the sequence, and whether its tokens sit in consecutive rows
+  const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
+  const bool contig =
+      kMode == kRowsIdentity ||
+      (kMode == kRowsMaybeContiguous && __builtin_amdgcn_readfirstlane(rows[start + n - 1]) - row0 == n - 1);
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps per-wave branches scalar
@@ -70,12 +75,12 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const uint32_t koff = ((uint32_t)st_row * (uint32_t)ks + (uint32_t)(h * kD + st_col)) * 2u;
   const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {   // rows j0 + 32it + st_row of K and V -> registers (zeros past the end)
-    if (kDirect) {
+    if (contig) {
       const int left = n - j0;      // > 0: rows j0 .. n-1 exist
       const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(k) + (int64_t)(start + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
+          const_cast<uint16_t*>(k) + (int64_t)(row0 + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
-          const_cast<uint16_t*>(v) + (int64_t)(start + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
+          const_cast<uint16_t*>(v) + (int64_t)(row0 + j0) * vs, 0, left * (int)vs * 2, kRsrcFlags);
 #pragma unroll
       for (int it = 0; it < 2; ++it) {
         tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, koff + (uint32_t)it * 64u * (uint32_t)ks, 0, 0);
@@ -486,16 +491,16 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
                          (uint16_t*)o, os, lse, s.T, s.token_rows);
     return check_launch("attn_fwd_short_kernel");
   }
-  // buffer-load path: rows in packed order, and a sequence's K / V rows within 2^31 bytes of its first
+  // buffer-load path: a sequence's K / V rows within 2^31 bytes of its first
   const int64_t span = (int64_t)s.max_seqlen * (ks > vs ? ks : vs) * 2;
-  if (!s.token_rows && span < ((int64_t)1 << 31))
-    hipLaunchKernelGGL(attn_fwd_tiled_kernel<true>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                       (uint16_t*)o, os, lse, s.T, s.token_rows);
-  else
-    hipLaunchKernelGGL(attn_fwd_tiled_kernel<false>, dim3(tiles, s.H, s.B), dim3(256), 0, stream,
-                       (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens,
-                       s.slopes, s.scale, (uint16_t*)o, os, lse, s.T, s.token_rows);
+#define MB_LAUNCH_TILED(M)                                                                                        \
+  hipLaunchKernelGGL(attn_fwd_tiled_kernel<M>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,   \
+                     (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,         \
+                     (uint16_t*)o, os, lse, s.T, s.token_rows)
+  if (span >= ((int64_t)1 << 31)) MB_LAUNCH_TILED(kRowsPerLane);
+  else if (s.token_rows) MB_LAUNCH_TILED(kRowsMaybeContiguous);
+  else MB_LAUNCH_TILED(kRowsIdentity);
+#undef MB_LAUNCH_TILED
   return check_launch("attn_fwd_tiled_kernel");
 }
 

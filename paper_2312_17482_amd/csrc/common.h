@@ -30,6 +30,16 @@ __device__ __forceinline__ int64_t tok_row(const int32_t* __restrict__ rows, int
   return rows ? (int64_t)rows[t] : (int64_t)t;
 }
 
+// How the any-length attention kernels find the buffer rows of a sequence's tokens (template parameter):
+//   kRowsPerLane          every row's address is formed per lane (token_rows looked up when given); no limit
+//                         on strides.
+//   kRowsIdentity         no token_rows: token t sits at row t, so a sequence's rows are consecutive.
+//   kRowsMaybeContiguous  token_rows given: a sequence whose rows are listed in ascending order with first
+//                         and last n - 1 apart (the usual case: padding behind each sequence) is handled
+//                         like kRowsIdentity from its first row, any other like kRowsPerLane.
+// The last two require that a sequence's rows span fewer than 2^31 bytes.
+enum { kRowsPerLane = 0, kRowsIdentity = 1, kRowsMaybeContiguous = 2 };
+
 // Longest-sequence-first work order for kernels whose workgroups run for a time that grows with the
 // sequence length: finds the sequence whose length has rank `rank` (0 = longest; ties by index), so
 // that the heaviest workgroups are dispatched first and short ones fill the tail, and returns its index

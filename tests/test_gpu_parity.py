@@ -370,6 +370,22 @@ def test_bf16_tile_boundary_lengths(mb):
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 tile boundaries")
 
 
+@pytest.mark.parametrize("B", [300, 530])
+def test_bf16_many_sequences_through_the_any_length_kernels(mb, B):
+    """More sequences than one pass of the longest-first ranking covers (256 candidates per pass), and more
+    than it is applied to at all (512): mostly very short sequences, many of equal length, two long ones."""
+    rng = np.random.default_rng(77 + B)
+    lengths = [int(x) for x in rng.integers(0, 13, size=B)]
+    lengths[B // 3] = 130
+    lengths[B - 2] = 129
+    c = wl.random_attention_case(300 + B, lengths, 130, 1, 64, std=0.7, bf16=True, v_std=0.5)
+    slopes = mb.mb_alibi_slopes(1)
+    got = run_hip_path(mb, c, slopes, bf16=True)
+    check_index_maps(got, c["mask"])
+    ref = run_oracle(c, slopes.double().numpy())
+    compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 %d sequences" % B)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
 def test_bf16_random_shapes(mb, seed):
     """Random batch sizes, head counts and lengths (both kernel families, chosen by the longest sequence)."""
