@@ -238,7 +238,7 @@ def main():
         "paper_context": "MosaicBERT-Base: 79.6 GLUE in 1.13 h on 8xA100-80GB (end-to-end pretraining; not comparable)",
     }
 
-    out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev),
+    out["next_rows"] = {"add_layernorm_bf16": time_layernorm(mb, T_host, H * D, tdt, dev, indices, B, L),
                         "padded_attention_comparison": time_padded_vs_varlen(mb, locals())}
     if bf16 and (H * D) % 256 == 0:
         out["next_rows"]["geglu_ffn_bf16"] = time_geglu(mb, T_host, H * D, 4 * H * D, dev)
@@ -266,10 +266,11 @@ def main():
     print(json.dumps(out))
 
 
-def time_layernorm(mb, T, W, tdt, dev):
+def time_layernorm(mb, T, W, tdt, dev, indices, B, L):
     """Add & LayerNorm on the packed tokens of the same batch ([T, H*D]), outside the timed step: 50 launches
     between two events.  Algorithmic bytes: forward reads x, r and writes s, y (4 T W e); backward reads dy, s
-    and writes ds (3 T W e)."""
+    and writes ds (3 T W e).  Also the last operation of an encoder stack writing the padded batch itself
+    (y_rows = indices, then mb_zero_padding) against LayerNorm followed by mb_pad."""
     import torch
     e = 2 if tdt == torch.bfloat16 else 4
     x = torch.randn(T, W, device=dev).to(tdt)
@@ -299,6 +300,21 @@ def time_layernorm(mb, T, W, tdt, dev):
         res[name + "_us"] = round(us, 2)
         res[name + "_GBs"] = round(nbytes / (us * 1e-6) * 1e-9, 1)
         res[name + "_frac_of_hbm_peak"] = round(nbytes / (us * 1e-6) * 1e-9 / PEAK_HBM_GBS, 4)
+    y_padded = torch.empty((B * L, W), dtype=tdt, device=dev)
+    then_pad = lambda: (fwd(), mb.mb_pad(y, indices, T, None, B, L, out=y_padded))
+    scattering = lambda: (mb.mb_add_layernorm_fwd(x, r, gamma, beta, 1e-5, y=y_padded, s=s, mean=mean, rstd=rstd,
+                                                  y_rows=indices),
+                          mb.mb_zero_padding(y_padded, indices, T, None, B, L))
+    for name, fn in (("fwd_then_pad_us", then_pad), ("fwd_writing_the_padded_batch_us", scattering)):
+        for _ in range(5):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(50):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        res[name] = round(a.elapsed_time(b) * 1e3 / 50, 2)
     res["shape"] = "T=%d W=%d" % (T, W)
     return res
 

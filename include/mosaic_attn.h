@@ -186,10 +186,14 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
  *   T_cap, meta_dev  rows [0, T) are processed, T = min(meta_dev[0], T_cap), or T_cap if meta_dev is NULL.
  *   W         row width; W * element_size a multiple of 16 bytes and at most 4096 bytes.
  *   y, s      dev, [T_cap, W], written.     mean, rstd  dev, [T_cap] float, written (needed by the backward).
+ *   y_rows    dev, NULL or [T] int32 (the `indices` of mb_unpad_index): row t of the result is written to row
+ *             y_rows[t] of y, which is then a padded batch [B*L, W]: the scatter of mb_pad happens in this
+ *             call's own stores when the LayerNorm is the last operation on the packed tokens (the padding rows
+ *             are not written: see mb_zero_padding).  s, mean and rstd stay packed.
  */
 MB_API mb_status mb_add_layernorm_fwd(const void* x, const void* r, const void* gamma, const void* beta, int T_cap,
                                       const int32_t* meta_dev, int W, float eps, mb_dtype dt, void* y, void* s,
-                                      float* mean, float* rstd, void* stream);
+                                      float* mean, float* rstd, const int32_t* y_rows, void* stream);
 
 /* Bytes of device workspace mb_add_layernorm_bwd needs for rows of W elements (0 on invalid W). */
 MB_API size_t mb_add_layernorm_bwd_workspace_bytes(int W);
@@ -201,11 +205,13 @@ MB_API size_t mb_add_layernorm_bwd_workspace_bytes(int W);
  *   dy, s  dev, [T_cap, W], read (s = the stored sum of the forward, or x when r was NULL).
  *   ds     dev, [T_cap, W], written.   dgamma, dbeta  dev, [W] float, written.
  *   workspace  dev, at least mb_add_layernorm_bwd_workspace_bytes(W) bytes, scratch.
+ *   dy_rows    dev, NULL or [T] int32: row t of dy is read from row dy_rows[t] of a padded batch (the gather of
+ *              mb_unpad in this call's own loads); everything else stays packed.
  */
 MB_API mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma, const float* mean,
                                       const float* rstd, int T_cap, const int32_t* meta_dev, int W, mb_dtype dt,
                                       void* ds, float* dgamma, float* dbeta, void* workspace,
-                                      size_t workspace_bytes, void* stream);
+                                      size_t workspace_bytes, const int32_t* dy_rows, void* stream);
 
 /*
  * GeGLU feed-forward sublayer, forward (Eq. 2 of the paper:  y = (GeLU(x W1) (*) x V) W2,  GeLU(h) = h Phi(h)

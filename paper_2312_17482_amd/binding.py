@@ -55,12 +55,12 @@ _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] +
 
 _lib.mb_add_layernorm_fwd.restype = c_int
 _lib.mb_add_layernorm_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_float, c_int,
-                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
 _lib.mb_add_layernorm_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_add_layernorm_bwd_workspace_bytes.argtypes = [c_int]
 _lib.mb_add_layernorm_bwd.restype = c_int
 _lib.mb_add_layernorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int,
-                                      c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p, c_void_p]
 _lib.mb_geglu_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_geglu_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
 _lib.mb_geglu_bwd.restype = c_int
@@ -223,11 +223,14 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
     return dq, dk, dv
 
 
-def mb_add_layernorm_fwd(x, r, gamma, beta, eps: float, T_cap=None, meta=None, y=None, s=None, mean=None, rstd=None):
-    """x, r: [rows, W] (r may be None).  Returns (y, s, mean, rstd); s is x itself when r is None."""
+def mb_add_layernorm_fwd(x, r, gamma, beta, eps: float, T_cap=None, meta=None, y=None, s=None, mean=None, rstd=None,
+                         y_rows=None):
+    """x, r: [rows, W] (r may be None).  Returns (y, s, mean, rstd); s is x itself when r is None.
+    With y_rows, y must be given: a padded batch whose row y_rows[t] receives the result of token t."""
     assert x.dim() == 2 and x.is_contiguous()
     rows, W = x.shape
     T_cap = rows if T_cap is None else T_cap
+    assert y_rows is None or y is not None
     y = torch.empty_like(x) if y is None else y
     if r is not None and s is None:
         s = torch.empty_like(x)
@@ -235,7 +238,7 @@ def mb_add_layernorm_fwd(x, r, gamma, beta, eps: float, T_cap=None, meta=None, y
     rstd = torch.empty(rows, dtype=torch.float32, device=x.device) if rstd is None else rstd
     _check(_lib.mb_add_layernorm_fwd(_ptr(x), _ptr(r), _ptr(gamma), _ptr(beta), T_cap, _ptr(meta), W, float(eps),
                                      _dtype_code(x), _ptr(y), _ptr(s) if r is not None else None, _ptr(mean),
-                                     _ptr(rstd), _stream()))
+                                     _ptr(rstd), _ptr(y_rows), _stream()))
     return y, (s if r is not None else x), mean, rstd
 
 
@@ -244,8 +247,9 @@ def mb_add_layernorm_bwd_workspace_bytes(W: int) -> int:
 
 
 def mb_add_layernorm_bwd(dy, s, gamma, mean, rstd, T_cap=None, meta=None, ds=None, dgamma=None, dbeta=None,
-                         workspace=None):
-    """Returns (ds [rows, W], dgamma [W] float32, dbeta [W] float32)."""
+                         workspace=None, dy_rows=None):
+    """Returns (ds [rows, W], dgamma [W] float32, dbeta [W] float32).
+    With dy_rows, dy is a padded batch and token t's row is dy[dy_rows[t]]."""
     rows, W = s.shape
     T_cap = rows if T_cap is None else T_cap
     ds = torch.empty_like(s) if ds is None else ds
@@ -255,7 +259,7 @@ def mb_add_layernorm_bwd(dy, s, gamma, mean, rstd, T_cap=None, meta=None, ds=Non
         workspace = torch.empty(mb_add_layernorm_bwd_workspace_bytes(W), dtype=torch.uint8, device=s.device)
     _check(_lib.mb_add_layernorm_bwd(_ptr(dy), _ptr(s), _ptr(gamma), _ptr(mean), _ptr(rstd), T_cap, _ptr(meta), W,
                                      _dtype_code(s), _ptr(ds), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
-                                     workspace.numel(), _stream()))
+                                     workspace.numel(), _ptr(dy_rows), _stream()))
     return ds, dgamma, dbeta
 
 

@@ -197,7 +197,7 @@ static mb_status check_ln(int T_cap, int W, mb_dtype dt) {
 
 mb_status mb_add_layernorm_fwd(const void* x, const void* r, const void* gamma, const void* beta, int T_cap,
                                const int32_t* meta_dev, int W, float eps, mb_dtype dt, void* y, void* s, float* mean,
-                               float* rstd, void* stream) {
+                               float* rstd, const int32_t* y_rows, void* stream) {
   clear_error();
   mb_status st = check_ln(T_cap, W, dt);
   if (st != MB_OK) return st;
@@ -213,7 +213,8 @@ mb_status mb_add_layernorm_fwd(const void* x, const void* r, const void* gamma, 
     MB_REQUIRE(aligned16(r), MB_ERR_INVALID_ARG, "r is not 16-byte aligned");
     MB_CHECK_PTR(s);
   }
-  return launch_add_layernorm_fwd(dt, x, r, gamma, beta, T_cap, meta_dev, W, eps, y, s, mean, rstd,
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(y_rows) & 3u) == 0, MB_ERR_INVALID_ARG, "y_rows is not 4-byte aligned");
+  return launch_add_layernorm_fwd(dt, x, r, gamma, beta, T_cap, meta_dev, W, eps, y, s, mean, rstd, y_rows,
                                   (hipStream_t)stream);
 }
 
@@ -224,7 +225,8 @@ size_t mb_add_layernorm_bwd_workspace_bytes(int W) {
 
 mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma, const float* mean, const float* rstd,
                                int T_cap, const int32_t* meta_dev, int W, mb_dtype dt, void* ds, float* dgamma,
-                               float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+                               float* dbeta, void* workspace, size_t workspace_bytes, const int32_t* dy_rows,
+                               void* stream) {
   clear_error();
   mb_status st = check_ln(T_cap, W, dt);
   if (st != MB_OK) return st;
@@ -242,9 +244,10 @@ mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma,
     MB_CHECK_PTR(rstd);
     MB_CHECK_PTR(ds);
   }
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(dy_rows) & 3u) == 0, MB_ERR_INVALID_ARG, "dy_rows is not 4-byte aligned");
   // with T_cap == 0 only the column-sum pass runs, over zero partial rows: dgamma and dbeta become zeros
   return launch_add_layernorm_bwd(dt, dy, s, gamma, mean, rstd, T_cap, meta_dev, W, ds, dgamma, dbeta,
-                                  (float*)workspace, (hipStream_t)stream);
+                                  (float*)workspace, dy_rows, (hipStream_t)stream);
 }
 
 mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,

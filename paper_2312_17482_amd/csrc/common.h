@@ -140,10 +140,10 @@ mb_status launch_gelu_gate(const void* h, const void* gate, int64_t ld, int T_ca
 
 mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
                                    int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
-                                   float* rstd, hipStream_t stream);
+                                   float* rstd, const int32_t* y_rows, hipStream_t stream);
 mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, const void* gamma, const float* mean,
                                    const float* rstd, int T_cap, const int32_t* meta, int W, void* ds, float* dgamma,
-                                   float* dbeta, float* part, hipStream_t stream);
+                                   float* dbeta, float* part, const int32_t* dy_rows, hipStream_t stream);
 
 // Generic ALU kernels: any D <= 128, fp32 or bf16 storage, fp32 arithmetic.
 // Their backward keeps two score rows of max_seqlen floats plus two head vectors in LDS and must stay

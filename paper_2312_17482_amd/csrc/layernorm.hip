@@ -65,7 +65,7 @@ template <typename E, int kMaxPieces>
 __global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
     const E* __restrict__ x, const E* __restrict__ r, const E* __restrict__ gamma, const E* __restrict__ beta,
     int T_cap, const int32_t* __restrict__ meta, int W, float eps, E* __restrict__ y, E* __restrict__ s,
-    float* __restrict__ mean, float* __restrict__ rstd) {
+    float* __restrict__ mean, float* __restrict__ rstd, const int32_t* __restrict__ y_rows) {
   constexpr int N = Piece<E>::kN;
   const int T = meta ? min(meta[0], T_cap) : T_cap;
   const int row = blockIdx.x * kLnWaves + (threadIdx.x >> 6);
@@ -73,6 +73,7 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
   const int lane = threadIdx.x & 63;
   const int pieces = W / N;
   const E* xr = x + (size_t)row * W;
+  E* yr = y + (size_t)tok_row(y_rows, row) * W;   // packed row, or the token's row in the padded batch
   float v[kMaxPieces][N];
   float sum = 0.f;
 #pragma unroll
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_fwd_kernel(
       Piece<E>::load(beta + pc * N, b);
 #pragma unroll
       for (int i = 0; i < N; ++i) out[i] = fmaf((v[c][i] - mu) * rs, g[i], b[i]);
-      Piece<E>::store(y + (size_t)row * W + pc * N, out);
+      Piece<E>::store(yr + pc * N, out);
     }
   }
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
@@ -122,7 +123,7 @@ template <typename E, int kMaxPieces>
 __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
     const E* __restrict__ dy, const E* __restrict__ s, const E* __restrict__ gamma, const float* __restrict__ mean,
     const float* __restrict__ rstd, int T_cap, const int32_t* __restrict__ meta, int W, E* __restrict__ ds,
-    float* __restrict__ part) {
+    float* __restrict__ part, const int32_t* __restrict__ dy_rows) {
   constexpr int N = Piece<E>::kN;
   extern __shared__ float lds[];   // [kLnWaves][2][W]
   const int T = meta ? min(meta[0], T_cap) : T_cap;
@@ -137,6 +138,7 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
   }
   for (int row = blockIdx.x * kLnWaves + wave; row < T; row += gridDim.x * kLnWaves) {
     const float mu = mean[row], rs = rstd[row];
+    const E* dyr = dy + (size_t)tok_row(dy_rows, row) * W;   // packed row, or the token's row in the padded batch
     float xh[kMaxPieces][N], gy[kMaxPieces][N];
     float c1 = 0.f, c2 = 0.f;
 #pragma unroll
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(kLnThreads) void add_layernorm_bwd_kernel(
       if (pc < pieces) {
         float d[N];
         Piece<E>::load(s + (size_t)row * W + pc * N, xh[c]);
-        Piece<E>::load(dy + (size_t)row * W + pc * N, d);
+        Piece<E>::load(dyr + pc * N, d);
 #pragma unroll
         for (int i = 0; i < N; ++i) {
           xh[c][i] = (xh[c][i] - mu) * rs;
@@ -227,12 +229,13 @@ int bwd_blocks(int T_cap) { return max(1, min((T_cap + kLnWaves - 1) / kLnWaves,
 
 mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, const void* gamma, const void* beta,
                                    int T_cap, const int32_t* meta, int W, float eps, void* y, void* s, float* mean,
-                                   float* rstd, hipStream_t stream) {
+                                   float* rstd, const int32_t* y_rows, hipStream_t stream) {
   const int blocks = (T_cap + kLnWaves - 1) / kLnWaves;
   const bool small = (size_t)W * elem_size(dt) <= 2048;
 #define MB_LN_FWD(E, P)                                                                                           \
   hipLaunchKernelGGL((add_layernorm_fwd_kernel<E, P>), dim3(blocks), dim3(kLnThreads), 0, stream, (const E*)x,    \
-                     (const E*)r, (const E*)gamma, (const E*)beta, T_cap, meta, W, eps, (E*)y, (E*)s, mean, rstd)
+                     (const E*)r, (const E*)gamma, (const E*)beta, T_cap, meta, W, eps, (E*)y, (E*)s, mean, rstd,  \
+                     y_rows)
   if (dt == MB_BF16) { if (small) MB_LN_FWD(uint16_t, 2); else MB_LN_FWD(uint16_t, 4); }
   else { if (small) MB_LN_FWD(float, 2); else MB_LN_FWD(float, 4); }
 #undef MB_LN_FWD
@@ -241,7 +244,7 @@ mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, co
 
 mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, const void* gamma, const float* mean,
                                    const float* rstd, int T_cap, const int32_t* meta, int W, void* ds, float* dgamma,
-                                   float* dbeta, float* part, hipStream_t stream) {
+                                   float* dbeta, float* part, const int32_t* dy_rows, hipStream_t stream) {
   if (T_cap == 0) {
     // no rows (dy, s, gamma, ... may be NULL): nothing to read, the column sums are zeros
     hipLaunchKernelGGL(add_layernorm_colsum_kernel, dim3((2 * W + 63) / 64), dim3(64 * kColsumSlices), 0, stream, part, 0, W,
@@ -253,7 +256,7 @@ mb_status launch_add_layernorm_bwd(mb_dtype dt, const void* dy, const void* s, c
   const bool small = (size_t)W * elem_size(dt) <= 2048;
 #define MB_LN_BWD(E, P)                                                                                          \
   hipLaunchKernelGGL((add_layernorm_bwd_kernel<E, P>), dim3(blocks), dim3(kLnThreads), smem, stream,             \
-                     (const E*)dy, (const E*)s, (const E*)gamma, mean, rstd, T_cap, meta, W, (E*)ds, part)
+                     (const E*)dy, (const E*)s, (const E*)gamma, mean, rstd, T_cap, meta, W, (E*)ds, part, dy_rows)
   if (dt == MB_BF16) { if (small) MB_LN_BWD(uint16_t, 2); else MB_LN_BWD(uint16_t, 4); }
   else { if (small) MB_LN_BWD(float, 2); else MB_LN_BWD(float, 4); }
 #undef MB_LN_BWD

@@ -151,18 +151,22 @@ def test_product_package_never_imports_the_oracle():
 
 
 def test_layernorm_rejects_bad_arguments():
-    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 100, 1e-5, mb.MB_BF16, A, A, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 100, 1e-5, mb.MB_BF16, A, A, A, A, None, None) == mb.MB_ERR_INVALID_ARG
     assert "16 bytes" in mb.mb_last_error()
-    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 4096, 1e-5, mb.MB_BF16, A, A, A, A, None) == mb.MB_ERR_UNSUPPORTED
-    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 768, -1.0, mb.MB_BF16, A, A, A, A, None) == mb.MB_ERR_INVALID_ARG
-    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 768, 1e-5, mb.MB_BF16, A, None, A, A, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 4096, 1e-5, mb.MB_BF16, A, A, A, A, None, None) == mb.MB_ERR_UNSUPPORTED
+    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 768, -1.0, mb.MB_BF16, A, A, A, A, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 768, 1e-5, mb.MB_BF16, A, None, A, A, None, None) == mb.MB_ERR_INVALID_ARG
     assert "s is NULL" in mb.mb_last_error()
-    assert lib.mb_add_layernorm_fwd(None, None, A, A, 16, None, 768, 1e-5, mb.MB_BF16, A, None, A, A, None) == mb.MB_ERR_INVALID_ARG
-    assert lib.mb_add_layernorm_fwd(None, None, None, None, 0, None, 768, 1e-5, mb.MB_BF16, None, None, None, None, None) == mb.MB_OK
+    assert lib.mb_add_layernorm_fwd(None, None, A, A, 16, None, 768, 1e-5, mb.MB_BF16, A, None, A, A, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_fwd(None, None, None, None, 0, None, 768, 1e-5, mb.MB_BF16, None, None, None, None, None, None) == mb.MB_OK
     need = mb.mb_add_layernorm_bwd_workspace_bytes(768)
     assert need == 1024 * 2 * 768 * 4 and mb.mb_add_layernorm_bwd_workspace_bytes(0) == 0
-    assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, A, A, A, need - 1, None) == mb.MB_ERR_WORKSPACE
-    assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, None, A, A, need, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, A, A, A, need - 1, None, None) == mb.MB_ERR_WORKSPACE
+    assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, None, A, A, need, None, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_add_layernorm_fwd(A, A, A, A, 16, None, 768, 1e-5, mb.MB_BF16, A, A, A, A, A + 2, None) == mb.MB_ERR_INVALID_ARG
+    assert "y_rows" in mb.mb_last_error()
+    assert lib.mb_add_layernorm_bwd(A, A, A, A, A, 16, None, 768, mb.MB_BF16, A, A, A, A, need, A + 1, None) == mb.MB_ERR_INVALID_ARG
+    assert "dy_rows" in mb.mb_last_error()
 
 
 def test_geglu_rejects_bad_arguments():

@@ -95,6 +95,39 @@ def test_layernorm_empty_input_writes_zero_column_sums(mb):
     db = torch.full((W,), 5.0, device="cuda")
     ws = torch.empty(mb.mb_add_layernorm_bwd_workspace_bytes(W), dtype=torch.uint8, device="cuda")
     assert lib.mb_add_layernorm_bwd(None, None, None, None, None, 0, None, W, mb.MB_BF16, None, dg.data_ptr(),
-                                    db.data_ptr(), ws.data_ptr(), ws.numel(), None) == 0
+                                    db.data_ptr(), ws.data_ptr(), ws.numel(), None, None) == 0
     torch.cuda.synchronize()
     assert torch.all(dg == 0) and torch.all(db == 0)
+
+
+@pytest.mark.parametrize("bf16,W,holes", [(True, 768, False), (True, 1024, True), (False, 96, True)])
+def test_layernorm_reads_and_writes_a_padded_batch_directly(mb, bf16, W, holes):
+    """y_rows / dy_rows: the scatter of mb_pad in the forward's stores and the gather of mb_unpad in the
+    backward's loads give bit for bit what the explicit calls give, for suffix padding and for masks with holes."""
+    rng = np.random.default_rng(11)
+    B, L = 9, 37
+    if holes:
+        mask = (rng.random((B, L)) < 0.7).astype(np.int32)
+    else:
+        mask = wl.suffix_mask(rng.integers(0, L + 1, size=B), L)
+    mask[3] = 0
+    maskd = torch.from_numpy(mask).cuda()
+    _, _, indices, meta = mb.mb_unpad_index(maskd)
+    T = int(mask.sum())
+    x, r, gamma, beta, dy = make(5, T, W, bf16)
+    xd, rd_, gd, bd, dyd = (dev(a, bf16) for a in (x, r, gamma, beta, dy))
+    # explicit: packed LayerNorm, then mb_pad
+    y, s, mean, rstd = mb.mb_add_layernorm_fwd(xd, rd_, gd, bd, EPS)
+    y_padded = mb.mb_pad(y, indices, T, None, B, L)
+    # fused: rows scattered by the LayerNorm itself, padding rows zeroed separately
+    y2 = torch.full((B * L, W), 7.0, dtype=xd.dtype, device="cuda")
+    _, s2, mean2, rstd2 = mb.mb_add_layernorm_fwd(xd, rd_, gd, bd, EPS, y=y2, y_rows=indices)
+    mb.mb_zero_padding(y2, indices, T, None, B, L)
+    assert torch.equal(y2.view(torch.uint8), y_padded.view(torch.uint8))
+    assert torch.equal(s2, s) and torch.equal(mean2, mean) and torch.equal(rstd2, rstd)
+    # backward: dy handed over as a padded batch
+    dy_padded = mb.mb_pad(dyd, indices, T, None, B, L)
+    dy_padded[torch.from_numpy(mask.reshape(-1) == 0).cuda()] = float("nan")   # padding rows must not be read
+    ds, dg, db = mb.mb_add_layernorm_bwd(dyd, s, gd, mean, rstd)
+    ds2, dg2, db2 = mb.mb_add_layernorm_bwd(dy_padded, s, gd, mean, rstd, dy_rows=indices)
+    assert torch.equal(ds2, ds) and torch.equal(dg2, dg) and torch.equal(db2, db)
