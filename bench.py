@@ -478,6 +478,22 @@ def measure_ceilings(mb, dev):
         b.record()
         torch.cuda.synchronize()
         res[name] = {"value": round(work * 10 / (a.elapsed_time(b) * 1e-3) * scale, 2), "unit": unit}
+    # matrix cores and vector ALU together: microseconds for the same number of rounds of 4 MFMA / 48 FMA / both
+    for label, kinds in (("mfma_and_valu_8_waves_per_simd", (8, 9, 10)), ("mfma_and_valu_1_wave_per_simd", (11, 12, 13)),
+                         ("mfma_16x16x32_and_valu_8_waves_per_simd", (14, 9, 15))):
+        t = []
+        for kind in kinds:
+            for _ in range(3):
+                mb.mb_probe_ceiling(kind, 4000, scratch)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(5):
+                mb.mb_probe_ceiling(kind, 4000, scratch)
+            b.record()
+            torch.cuda.synchronize()
+            t.append(a.elapsed_time(b) * 1e3 / 5)
+        res[label] = {"mfma_only_us": round(t[0], 1), "fma_only_us": round(t[1], 1), "both_us": round(t[2], 1),
+                      "hidden_fraction_of_the_shorter": round((t[0] + t[1] - t[2]) / min(t[0], t[1]), 3)}
     for label, rows in (("hbm_copy_128MiB_each_way", 65536), ("hbm_copy_1GiB_each_way", 524288)):
         width = 1024                                    # 2048-byte rows
         src = torch.ones((rows, width), dtype=torch.bfloat16, device=dev)

@@ -288,6 +288,10 @@ MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_strid
  *          5: the same with the GEMM's one workgroup barrier per k step
  *          6: the same plus the GEMM's 16 LDS writes per thread and k step
  *          7: the same plus its 16 global loads per thread and k step, from 16 MiB that stay in L2
+ *          8, 9, 10: rounds of 4 matrix instructions / of 48 independent multiply-adds / of both interleaved,
+ *             eight waves per SIMD (work = rounds over all waves): do the matrix cores and the vector unit
+ *             work at the same time?      11, 12, 13: the same with one wave per SIMD
+ *          14, 15: kinds 8 and 10 with the same flops as 8 instructions of the 16x16x32 shape
  *   iters  rounds per lane (> 0).      out  dev, 4 floats of scratch (never written in practice); for kind 7 they
  *          are followed by the 16 MiB the probe reads (any content).
  *   work_per_launch  host, written.

@@ -399,7 +399,7 @@ mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_stride, int 
 
 mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream) {
   clear_error();
-  MB_REQUIRE(kind >= 0 && kind <= 7, MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
+  MB_REQUIRE(kind >= 0 && kind <= 15, MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
   MB_REQUIRE(iters > 0 && iters <= (1 << 24), MB_ERR_INVALID_ARG, "iters must be in [1, 2^24] (got %d)", iters);
   MB_REQUIRE(work_per_launch != nullptr, MB_ERR_INVALID_ARG, "work_per_launch is NULL");
   MB_CHECK_PTR(out);

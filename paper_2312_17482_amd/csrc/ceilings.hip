@@ -159,6 +159,86 @@ __global__ __launch_bounds__(256, 1) void probe_gemm_loop_kernel(int iters, floa
   if (sum == 12345.678f) out[0] = sum;
 }
 
+// Do the matrix cores and the vector ALU of a SIMD work at the same time?  One round = 4 matrix instructions
+// (independent accumulators) and / or 48 independent fused multiply-adds, written interleaved; the three
+// variants run the same number of rounds, so  t(both)  against  t(matrix) + t(vector)  and  max of the two
+// answers the question for the instruction mix of the attention kernels.
+// kSmall: the same flops as 8 instructions of the 16x16x32 shape (4 accumulator registers each instead of 16).
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+template <bool kFma>
+__global__ __launch_bounds__(256) void probe_mix16_kernel(int iters, float* __restrict__ out) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7));
+    b[i] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+  }
+  f32x4v acc[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[t][v] = 0.f;
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
+  const float m = 0.999f, c = 0.0005f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[t], 0, 0, 0);
+      if (kFma) {
+#pragma unroll
+        for (int i = 0; i < 6; ++i) x[(2 * t + i) & 15] = fmaf(x[(2 * t + i) & 15], m, c);
+      }
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) s += acc[t][v];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += x[i];
+  if (s == 12345.678f) out[0] = s;
+}
+
+template <bool kMfma, bool kFma>
+__global__ __launch_bounds__(256) void probe_mix_kernel(int iters, float* __restrict__ out) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7));
+    b[i] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  float x[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
+  const float m = 0.999f, c = 0.0005f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (kMfma) acc[t] = mfma32(a, b, acc[t]);
+      if (kFma) {
+#pragma unroll
+        for (int i = 0; i < 12; ++i) x[(4 * t + i) & 15] = fmaf(x[(4 * t + i) & 15], m, c);
+      }
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[t][v];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += x[i];
+  if (s == 12345.678f) out[0] = s;
+}
+
 }  // namespace
 
 mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch, hipStream_t stream) {
@@ -191,6 +271,21 @@ mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch,
       else if (kind == 6) probe_gemm_loop_kernel<true, true, false><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
       else probe_gemm_loop_kernel<true, true, true><<<dim3(256 * 4), dim3(256), 0, stream>>>(iters, out, src);
       *work_per_launch = 256.0 * 4 * 4 * 64.0 * 32768.0 * iters;
+      break;
+    case 8: case 9: case 10:     // rounds of (4 matrix instructions, 48 multiply-adds, both): 8 waves per SIMD
+    case 11: case 12: case 13: { // the same with one wave per SIMD
+      const int blocks = kind < 11 ? kProbeBlocks : 256;
+      const int v = (kind - 8) % 3;
+      if (v == 0) probe_mix_kernel<true, false><<<dim3(blocks), dim3(256), 0, stream>>>(iters, out);
+      else if (v == 1) probe_mix_kernel<false, true><<<dim3(blocks), dim3(256), 0, stream>>>(iters, out);
+      else probe_mix_kernel<true, true><<<dim3(blocks), dim3(256), 0, stream>>>(iters, out);
+      *work_per_launch = (double)blocks * 4.0 * iters;   // rounds, over all waves
+      break;
+    }
+    case 14: case 15:   // kinds 8 and 10 with the 16x16x32 shape (8 instructions per round), 8 waves per SIMD
+      if (kind == 14) probe_mix16_kernel<false><<<dim3(kProbeBlocks), dim3(256), 0, stream>>>(iters, out);
+      else probe_mix16_kernel<true><<<dim3(kProbeBlocks), dim3(256), 0, stream>>>(iters, out);
+      *work_per_launch = (double)kProbeBlocks * 4.0 * iters;
       break;
     default:
       return fail(MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);

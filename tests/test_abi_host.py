@@ -202,7 +202,7 @@ def test_linear_and_gelu_gate_reject_bad_arguments():
 
 def test_probe_rejects_bad_arguments():
     w = ctypes.c_double(0.0)
-    assert lib.mb_probe_ceiling(8, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_ceiling(16, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 0, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, None, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, A, None, None) == mb.MB_ERR_INVALID_ARG
