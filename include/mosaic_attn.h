@@ -127,7 +127,8 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  * Forward attention, Eq. 1:  for every sequence b, head h and tokens i, j of that sequence
  *   S_ij = softmax_scale * q_i . k_j - slopes[h] * |i - j|,   P = softmax_j(S),   O_i = sum_j P_ij v_j,
  *   lse_i = log sum_j exp(S_ij).
- *   q, k, v      dev, [T, H, D] with row strides q/k/v_row_stride (elements), read.
+ *   q, k, v      dev, [T, H, D] with row strides q/k/v_row_stride (elements; >= H*D, rows a multiple of 16
+ *                bytes, < 2^24), read.
  *   cu_seqlens   dev, [B+1] int32, read.
  *   T            number of token rows the packed buffers hold; T >= cu_seqlens[B].  It may be a capacity
  *                (e.g. B*L) known without reading anything back from the device: rows at or beyond
@@ -142,7 +143,8 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *                write o into the padded layout, i.e. the gather of mb_unpad and the scatter of mb_pad
  *                happen inside the attention kernel's own row loads and stores (rows of o that belong to
  *                padding are not written: see mb_zero_padding).  lse stays packed, [H, T].
- * Errors: head_dim > 128 -> MB_ERR_UNSUPPORTED.  MB_BF16 with D = 64 and softmax_scale > 0 runs on the
+ * Errors: head_dim > 128, a row stride of 2^24 elements or more, T*H >= 2^31, B > 65535 -> MB_ERR_UNSUPPORTED.
+ * MB_BF16 with D = 64 and softmax_scale > 0 runs on the
  * matrix cores; every other supported combination runs the generic fp32-arithmetic kernels.
  */
 MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,

@@ -54,6 +54,8 @@ mb_status check_stride(int64_t stride, int H, int D, mb_dtype dt, const char* na
              (long long)stride, (long long)H * D);
   MB_REQUIRE((stride * (int64_t)elem_size(dt)) % 16 == 0, MB_ERR_INVALID_ARG,
              "%s=%lld elements is not a multiple of 16 bytes", name, (long long)stride);
+  // kernels form offsets of up to 128 rows inside a sequence in 32 bits
+  MB_REQUIRE(stride < ((int64_t)1 << 24), MB_ERR_UNSUPPORTED, "%s=%lld elements exceeds 2^24", name, (long long)stride);
   return MB_OK;
 }
 #define MB_CHECK_STRIDE(s, H, D)                               \

@@ -72,6 +72,7 @@ def bwd_args(**over):
     (dict(D=12, dt=mb.MB_BF16, qs=768), mb.MB_ERR_UNSUPPORTED, "multiple of 8"),
     (dict(qs=100), mb.MB_ERR_INVALID_ARG, "smaller than H*D"),
     (dict(vs=772), mb.MB_ERR_INVALID_ARG, "multiple of 16 bytes"),
+    (dict(ks=1 << 24), mb.MB_ERR_UNSUPPORTED, "exceeds 2^24"),
     (dict(dt=7), mb.MB_ERR_INVALID_ARG, "dtype"),
     (dict(scale=float("nan")), mb.MB_ERR_INVALID_ARG, "finite"),
     (dict(max_seqlen=0), mb.MB_ERR_INVALID_ARG, "max_seqlen"),
@@ -87,6 +88,7 @@ def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
     (dict(do=None), mb.MB_ERR_INVALID_ARG, "dout is NULL"),
     (dict(dv=None), mb.MB_ERR_INVALID_ARG, "dv is NULL"),
     (dict(dqs=8), mb.MB_ERR_INVALID_ARG, "smaller than H*D"),
+    (dict(dos=1 << 25), mb.MB_ERR_UNSUPPORTED, "exceeds 2^24"),
     (dict(ws=None), mb.MB_ERR_WORKSPACE, "workspace"),
     (dict(wsb=16), mb.MB_ERR_WORKSPACE, "needed"),
     (dict(ws=A + 4), mb.MB_ERR_INVALID_ARG, "workspace is not 16-byte"),

@@ -402,3 +402,45 @@ def test_bf16_random_shapes(mb, seed):
     check_index_maps(got, c["mask"])
     ref = run_oracle(c, slopes.double().numpy())
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 random %d" % seed)
+
+
+@pytest.mark.parametrize("n,B", [(2000, 3000), (100, 60000)])
+def test_bf16_buffers_beyond_four_gigabytes(mb, n, B):
+    """Packed QKV of 9.2 GB (6 million tokens x 3 x 4 heads x 64): element offsets pass 2^32, so every row
+    address must be formed in 64 bits.  Both kernel families (n = 2000: any-length, n = 100: single tile);
+    the oracle checks the first, a middle and the last sequence, which sit at the two ends of the buffers."""
+    H, D = 4, 64
+    T = n * B
+    print("large buffers n=%d B=%d T=%d" % (n, B, T), flush=True)
+    dev, bf = "cuda", torch.bfloat16
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    qkv = torch.empty((T, 3, H, D), dtype=bf, device=dev)
+    dout = torch.empty((T, H, D), dtype=bf, device=dev)
+    step = 1 << 20
+    for t0 in range(0, T, step):   # filled in pieces: no fp32 copy of the whole buffer
+        t1 = min(T, t0 + step)
+        qkv[t0:t1] = (torch.randn((t1 - t0, 3, H, D), device=dev, generator=gen) * 0.5).to(bf)
+        dout[t0:t1] = torch.randn((t1 - t0, H, D), device=dev, generator=gen).to(bf)
+    cu = torch.arange(0, T + 1, n, dtype=torch.int32, device=dev)
+    slopes = mb.mb_alibi_slopes(H).to(dev)
+    o, lse = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, n, slopes, 0.125)
+    dqkv = torch.empty_like(qkv)
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, n, slopes, 0.125,
+                         dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2])
+    torch.cuda.synchronize()
+    s64 = slopes.double().cpu().numpy()
+    ones = np.ones((1, n), dtype=np.int32)
+    for b in (0, B // 2, B - 1):
+        sl = slice(b * n, (b + 1) * n)
+        q, k, v = (qkv[sl, i].float().cpu().numpy()[None] for i in range(3))
+        do = dout[sl].float().cpu().numpy()[None]
+        O, LSE = orc.attention_fwd(q, k, v, ones, s64, 0.125)
+        dQ, dK, dV = orc.attention_bwd(do, q, k, v, ones, s64, 0.125)
+        for name, got, ref in (("o", o[sl], O[0]), ("dq", dqkv[sl, 0], dQ[0]), ("dk", dqkv[sl, 1], dK[0]),
+                               ("dv", dqkv[sl, 2], dV[0])):
+            ma, rf = err_stats(got.float().cpu().numpy().astype(np.float64), ref)
+            assert ma <= BF16_TOL[0] and rf <= BF16_TOL[1], "seq %d %s: %.3e %.3e" % (b, name, ma, rf)
+        assert np.max(np.abs(lse[:, sl].cpu().numpy() - LSE[0])) <= 1e-3
+    del qkv, dqkv, dout, o, lse
+    torch.cuda.empty_cache()
