@@ -142,7 +142,9 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *                `indices` of mb_unpad_index lets the call read a padded [B*L, ...] batch directly and
  *                write o into the padded layout, i.e. the gather of mb_unpad and the scatter of mb_pad
  *                happen inside the attention kernel's own row loads and stores (rows of o that belong to
- *                padding are not written: see mb_zero_padding).  lse stays packed, [H, T].
+ *                padding are not written: see mb_zero_padding).  lse stays packed, [H, T].  The rows of one
+ *                sequence must be listed in strictly ascending order (as `indices` lists them): the kernels
+ *                take a sequence whose first and last row are n - 1 apart as n consecutive rows.
  * Errors: head_dim > 128, a row stride of 2^24 elements or more, T*H >= 2^31, B > 65535 -> MB_ERR_UNSUPPORTED.
  * MB_BF16 with D = 64 and softmax_scale > 0 runs on the
  * matrix cores; every other supported combination runs the generic fp32-arithmetic kernels.
