@@ -286,6 +286,7 @@ def test_capacity_mode_needs_no_host_round_trip(mb, bf16, D, L):
 
 
 @pytest.mark.parametrize("bf16,D,L,holes", [(True, 64, 128, False), (True, 64, 128, True), (True, 64, 300, False),
+                                             (True, 64, 300, True), (True, 64, 700, False), (True, 64, 700, True),
                                              (False, 16, 64, False), (True, 32, 40, False)])
 def test_token_rows_mode_equals_explicit_unpad_and_pad(mb, bf16, D, L, holes):
     """Attention reading and writing the padded batch directly (token_rows = indices) + mb_zero_padding
