@@ -471,3 +471,66 @@ def test_unpad_pad_buffers_beyond_four_gigabytes(mb):
     assert torch.equal(back[keep], packed) and not bool(back[~keep].view(torch.int16).any())
     del padded, packed, back
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("L", [128, 300])
+def test_whole_path_replays_from_a_hip_graph(mb, L):
+    """The library allocates nothing, never synchronises and enqueues only kernels, so the whole path can be
+    captured in a HIP graph: three replays, with eager runs and synchronisation between them, each give the
+    bits of the eager run (both kernel families)."""
+    lengths = [L, 17, 0, L // 2, 33, 1, L - 1, 64]
+    c = wl.random_attention_case(81, lengths, L, 2, 64, std=0.5, bf16=True)
+    B, _, H, D = c["q"].shape
+    cap = B * L
+    bf = torch.bfloat16
+    mask = torch.from_numpy(c["mask"]).cuda()
+    qkv_p = to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(cap, 3 * H * D), True)
+    do_p = to_dev(c["do"].reshape(cap, H * D), True)
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    qkv = torch.empty((cap, 3, H, D), dtype=bf, device="cuda")
+    dout = torch.empty((cap, H, D), dtype=bf, device="cuda")
+    o = torch.empty((cap, H, D), dtype=bf, device="cuda")
+    dqkv = torch.empty((cap, 3, H, D), dtype=bf, device="cuda")
+    o_pad = torch.empty((cap, H * D), dtype=bf, device="cuda")
+    g_pad = torch.empty((cap, 3 * H * D), dtype=bf, device="cuda")
+    lse = torch.empty((H, cap), dtype=torch.float32, device="cuda")
+    ws = torch.empty(mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16), dtype=torch.uint8, device="cuda")
+    seqlens = torch.empty(B, dtype=torch.int32, device="cuda")
+    cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
+    indices = torch.empty(cap, dtype=torch.int32, device="cuda")
+    meta = torch.empty(2, dtype=torch.int32, device="cuda")
+    lib = mb.raw()
+
+    def path():   # capacity mode: no host round trip anywhere
+        assert lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
+                                  meta.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
+        mb.mb_unpad(qkv_p, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
+        mb.mb_unpad(do_p, indices, cap, meta, out=dout.view(cap, H * D))
+        mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, c["scale"], out=o, lse=lse)
+        mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, L, slopes, c["scale"],
+                             dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
+        mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_pad)
+        mb.mb_pad(dqkv.view(cap, 3 * H * D), indices, cap, meta, B, L, out=g_pad)
+
+    path()
+    torch.cuda.synchronize()
+    ref_o, ref_g = o_pad.clone(), g_pad.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        path()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            path()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        o_pad.fill_(7.0)
+        g_pad.fill_(7.0)
+        qkv.fill_(1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_pad, ref_o) and torch.equal(g_pad, ref_g)
+        path()                      # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(o_pad, ref_o) and torch.equal(g_pad, ref_g)
