@@ -19,12 +19,14 @@
  *              every buffer; the library allocates nothing, keeps no state between calls and never
  *              frees.  Device pointers must be 16-byte aligned.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
- *              work is enqueued on it; no call synchronises with the host.
+ *              work is enqueued on it; no call synchronises with the host except mb_read_meta.  Calls
+ *              enqueue kernels only (no memsets, no allocations), so a sequence of them can be captured in
+ *              a HIP graph.
  *   Errors     every call returns an mb_status and never throws or aborts.  Arguments are validated
  *              on the host before anything is launched, so error paths need no GPU.  A message for
  *              the last failing call on this thread is available from mb_last_error().
  *   Layouts    packed activations are [T, H, D] with D contiguous; consecutive tokens are
- *              `row_stride` ELEMENTS apart (row_stride >= H*D, a multiple of 16 bytes), so q, k and v may
+ *              `row_stride` ELEMENTS apart (H*D <= row_stride < 2^24, a multiple of 16 bytes), so q, k and v may
  *              point into one fused [T, 3, H, D] buffer.  The row log-sum-exp is [H, T] float,
  *              natural log.  Positions used by the bias are positions inside the packed sequence:
  *              token t of sequence b sits at position t - cu_seqlens[b].
