@@ -216,57 +216,71 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   float fj = (float)(kj - 4 * g);   // i - j = ci - fj with ci = i0 + 32ib + 8*(v/4) + v%4
   asm volatile("" : "+v"(fj));
 
-  // One block of 32 queries (rows 32ib.. of the staged tile) against this wave's keys.  The S accumulator
+  // The two blocks of 32 queries of a staged tile (rows 32ib..) against this wave's keys.  The S accumulator
   // is pre-loaded with bias/scale and the dP accumulator with -Delta_i, so that after the products
   // P = exp2(acc_S * c - lse2_i) and dS = P * acc_dP.  Rows past the sequence end are staged as zeros
   // with lse = +inf, which makes their P and dS exact zeros: no branch around the accumulating code.
-  auto qblock = [&](const uint16_t* sQ, const uint16_t* sG, const float* pl, const float* pd, int i0, int ib) {
-    f32x16 sacc, pacc;
-    const float d0 = (float)(i0 + 32 * ib) - fj;
-    const int qb = (i0 >> 5) + ib;
-    if (qb == kblk) {   // block with the diagonal
+  // Only the bias pre-load has variants (diagonal block or not); everything after it is one straight
+  // run of instructions for both blocks, so that the exponentials of one block can be issued between
+  // the matrix instructions of the other.
+  auto qtile = [&](const uint16_t* sQ, const uint16_t* sG, const float* pl, const float* pd, int i0) {
+    f32x16 sacc[2], pacc[2];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
-    } else {            // |i-j| = +-(ci - fj) on the whole block
-      const float sk = qb < kblk ? k1 : -k1;
-      const float a = sk * d0;
+    for (int ib = 0; ib < 2; ++ib) {
+      const float d0 = (float)(i0 + 32 * ib) - fj;
+      const int qb = (i0 >> 5) + ib;
+      if (qb == kblk) {   // block with the diagonal
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
-    }
-    float nl[16];
+        for (int i = 0; i < 16; ++i) sacc[ib][i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
+      } else {            // |i-j| = +-(ci - fj) on the whole block
+        const float sk = qb < kblk ? k1 : -k1;
+        const float a = sk * d0;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float4 l4 = *reinterpret_cast<const float4*>(&pl[32 * ib + 8 * r + 4 * g]);
-      const float4 d4 = *reinterpret_cast<const float4*>(&pd[32 * ib + 8 * r + 4 * g]);
-      nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
-      pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
-    }
-    const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
-    const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
-      pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
+        for (int i = 0; i < 16; ++i) sacc[ib][i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
+      }
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float p = fast_exp2(fmaf(sacc[i], cs, nl[i]));
-      sacc[i] = p;
-      pacc[i] = p * pacc[i];
+    for (int ib = 0; ib < 2; ++ib) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float4 d4 = *reinterpret_cast<const float4*>(&pd[32 * ib + 8 * r + 4 * g]);
+        pacc[ib][4 * r + 0] = d4.x; pacc[ib][4 * r + 1] = d4.y; pacc[ib][4 * r + 2] = d4.z; pacc[ib][4 * r + 3] = d4.w;
+      }
+      const uint16_t* qrow = &sQ[(32 * ib + c) * kPitch + 8 * g];
+      const uint16_t* grow = &sG[(32 * ib + c) * kPitch + 8 * g];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sacc[ib] = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc[ib]);
+        pacc[ib] = mfma32(lds_read8(grow + 16 * s), bv[s], pacc[ib]);
+      }
     }
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
-                              sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
-      const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
-                              pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
-      const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+    for (int ib = 0; ib < 2; ++ib) {
 #pragma unroll
-      for (int db = 0; db < 2; ++db) {
-        const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
-        dvacc[db] = mfma32(ag, bp, dvacc[db]);
-        const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
-        dkacc[db] = mfma32(aq, bs, dkacc[db]);
+      for (int r = 0; r < 4; ++r) {
+        const float4 l4 = *reinterpret_cast<const float4*>(&pl[32 * ib + 8 * r + 4 * g]);
+        const float nl[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = fast_exp2(fmaf(sacc[ib][4 * r + e], cs, nl[e]));
+          sacc[ib][4 * r + e] = p;
+          pacc[ib][4 * r + e] = p * pacc[ib][4 * r + e];
+        }
+      }
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        const bf16x8 bp = pack8(sacc[ib][8 * kk + 0], sacc[ib][8 * kk + 1], sacc[ib][8 * kk + 2], sacc[ib][8 * kk + 3],
+                                sacc[ib][8 * kk + 4], sacc[ib][8 * kk + 5], sacc[ib][8 * kk + 6], sacc[ib][8 * kk + 7]);
+        const bf16x8 bs = pack8(pacc[ib][8 * kk + 0], pacc[ib][8 * kk + 1], pacc[ib][8 * kk + 2], pacc[ib][8 * kk + 3],
+                                pacc[ib][8 * kk + 4], pacc[ib][8 * kk + 5], pacc[ib][8 * kk + 6], pacc[ib][8 * kk + 7]);
+        const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          const bf16x8 ag = join_tr(lds_read_tr4(&sG[roff + 32 * db]), lds_read_tr4(&sG[roff + 32 * db + 8 * kPitch]));
+          dvacc[db] = mfma32(ag, bp, dvacc[db]);
+          const bf16x8 aq = join_tr(lds_read_tr4(&sQ[roff + 32 * db]), lds_read_tr4(&sQ[roff + 32 * db + 8 * kPitch]));
+          dkacc[db] = mfma32(aq, bs, dkacc[db]);
+        }
       }
     }
   };
@@ -283,8 +297,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
       const uint16_t* sG = sQ + kHalf;
       const float* pl = sL[it & 1];
       const float* pd = sD[it & 1];
-      qblock(sQ, sG, pl, pd, i0, 0);
-      qblock(sQ, sG, pl, pd, i0, 1);
+      qtile(sQ, sG, pl, pd, i0);
     }
     if (it + 1 < ntiles) store_tile((it + 1) & 1);
   }
