@@ -459,16 +459,11 @@ def measure_ceilings(mb, dev):
     row copy through the gather kernel, once with 128 MiB each way (as large as the 256 MB Infinity Cache) and once
     with 1 GiB each way (far beyond it)."""
     import torch
-    scratch = torch.zeros(4 + (16 << 20) // 4, dtype=torch.float32, device=dev)   # 4 floats + 16 MiB for probe 7
+    scratch = torch.zeros(4, dtype=torch.float32, device=dev)
     res = {}
     for name, kind, iters, unit, scale in (("mfma_bf16_32x32x16", 0, 2000, "TFLOP/s", 1e-12),
                                            ("valu_fp32_fma", 1, 20000, "TFLOP/s", 1e-12),
-                                           ("valu_fp32_exp", 2, 5000, "Texp/s", 1e-12),
-                                           ("lds_read_16B", 3, 5000, "TB/s", 1e-12),
-                                           ("gemm_inner_loop_from_lds", 4, 200, "TFLOP/s", 1e-12),
-                                           ("gemm_inner_loop_from_lds_with_barrier", 5, 200, "TFLOP/s", 1e-12),
-                                           ("gemm_inner_loop_plus_lds_writes", 6, 200, "TFLOP/s", 1e-12),
-                                           ("gemm_inner_loop_plus_lds_writes_and_l2_loads", 7, 200, "TFLOP/s", 1e-12)):
+                                           ("valu_fp32_exp", 2, 5000, "Texp/s", 1e-12)):
         for _ in range(3):
             work = mb.mb_probe_ceiling(kind, iters, scratch)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -478,22 +473,6 @@ def measure_ceilings(mb, dev):
         b.record()
         torch.cuda.synchronize()
         res[name] = {"value": round(work * 10 / (a.elapsed_time(b) * 1e-3) * scale, 2), "unit": unit}
-    # matrix cores and vector ALU together: microseconds for the same number of rounds of 4 MFMA / 48 FMA / both
-    for label, kinds in (("mfma_and_valu_8_waves_per_simd", (8, 9, 10)), ("mfma_and_valu_1_wave_per_simd", (11, 12, 13)),
-                         ("mfma_16x16x32_and_valu_8_waves_per_simd", (14, 9, 15))):
-        t = []
-        for kind in kinds:
-            for _ in range(3):
-                mb.mb_probe_ceiling(kind, 4000, scratch)
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(5):
-                mb.mb_probe_ceiling(kind, 4000, scratch)
-            b.record()
-            torch.cuda.synchronize()
-            t.append(a.elapsed_time(b) * 1e3 / 5)
-        res[label] = {"mfma_only_us": round(t[0], 1), "fma_only_us": round(t[1], 1), "both_us": round(t[2], 1),
-                      "hidden_fraction_of_the_shorter": round((t[0] + t[1] - t[2]) / min(t[0], t[1]), 3)}
     for label, rows in (("hbm_copy_128MiB_each_way", 65536), ("hbm_copy_1GiB_each_way", 524288)):
         width = 1024                                    # 2048-byte rows
         src = torch.ones((rows, width), dtype=torch.bfloat16, device=dev)

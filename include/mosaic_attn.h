@@ -16,10 +16,12 @@
  *
  * Conventions common to every call
  *   Pointers   "dev" = device (HBM) pointer, "host" = host pointer.  The caller allocates and owns
- *              every buffer; the library allocates nothing, keeps no state between calls and never
- *              frees.  Device pointers must be 16-byte aligned.
+ *              every buffer; the library allocates nothing and never frees.  Device pointers must be
+ *              16-byte aligned.  The only state kept between calls lives on the device: one sticky
+ *              misuse word (see mb_device_status).
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
- *              work is enqueued on it; no call synchronises with the host except mb_read_meta.  Calls
+ *              work is enqueued on it; no call synchronises with the host except mb_read_meta and
+ *              mb_device_status.  Calls
  *              enqueue kernels only (no memsets, no allocations), so a sequence of them can be captured in
  *              a HIP graph.
  *   Errors     every call returns an mb_status and never throws or aborts.  Arguments are validated
@@ -136,9 +138,16 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *                (e.g. B*L) known without reading anything back from the device: rows at or beyond
  *                cu_seqlens[B] are neither read nor written.  T is also the row pitch of lse.
  *   max_seqlen   any upper bound of the longest sequence (e.g. L); sizes the launch and picks the kernel.
+ *                A sequence that turns out to be LONGER than max_seqlen is skipped as a whole, never truncated:
+ *                its rows of o are left untouched, its rows of lse are set to NaN, and the device's sticky
+ *                misuse word is raised (mb_device_status then reports MB_ERR_INVALID_ARG).  The lengths live
+ *                on the device, so the call itself still returns MB_OK.
  *   slopes       dev, [H] float, read.
  *   o            dev, [T, H, D] with row stride o_row_stride, written.
  *   lse          dev, [H, T] float, written.
+ *   workspace    dev, at least mb_alibi_attn_fwd_workspace_bytes(...) bytes, scratch (the work plan of the
+ *                any-length kernels); may be NULL when that is 0 (max_seqlen <= 128, or a combination served by
+ *                the generic kernels).
  *   token_rows   dev, [>= cu_seqlens[B]] int32, or NULL.  NULL: token t is row t of q, k, v and o (packed
  *                buffers).  Otherwise token t is row token_rows[t] of all four buffers: passing the
  *                `indices` of mb_unpad_index lets the call read a padded [B*L, ...] batch directly and
@@ -147,7 +156,8 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *                padding are not written: see mb_zero_padding).  lse stays packed, [H, T].  The rows of one
  *                sequence must be listed in strictly ascending order (as `indices` lists them): the kernels
  *                take a sequence whose first and last row are n - 1 apart as n consecutive rows.
- * Errors: head_dim > 128, a row stride of 2^24 elements or more, T*H >= 2^31, B > 65535 -> MB_ERR_UNSUPPORTED.
+ * Errors: head_dim > 128, a row stride of 2^24 elements or more, T*H >= 2^31, B*H >= 2^30, max_seqlen >= 2^22,
+ * B > 65535 -> MB_ERR_UNSUPPORTED; workspace NULL or too small -> MB_ERR_WORKSPACE.
  * MB_BF16 with D = 64 and softmax_scale > 0 runs on the
  * matrix cores; every other supported combination runs the generic fp32-arithmetic kernels.
  */
@@ -155,9 +165,12 @@ MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, 
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens,
                             int B, int T, int max_seqlen, int H, int D, const float* slopes,
                             float softmax_scale, mb_dtype dt, void* o, int64_t o_row_stride,
-                            float* lse, const int32_t* token_rows, void* stream);
+                            float* lse, void* workspace, size_t workspace_bytes, const int32_t* token_rows,
+                            void* stream);
 
-/* Bytes of device workspace mb_alibi_attn_bwd needs for these sizes (0 on invalid sizes). */
+/* Bytes of device workspace mb_alibi_attn_fwd / mb_alibi_attn_bwd need for these sizes (0 on invalid sizes; the
+ * forward's is also 0 when it needs none). */
+MB_API size_t mb_alibi_attn_fwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt);
 MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt);
 
 /*
@@ -172,6 +185,8 @@ MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, in
  *   workspace    dev, at least mb_alibi_attn_bwd_workspace_bytes(...) bytes, scratch.
  *   token_rows   as in the forward; applies to dout, q, k, v, o, dq, dk and dv alike.
  * Deterministic: no atomics; two calls on the same inputs give identical bits.
+ * A sequence longer than max_seqlen is skipped as in the forward (its rows of dq, dk, dv are left untouched, the
+ * misuse word is raised).
  */
 MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
                             const void* o, const float* lse, int64_t do_row_stride,
@@ -181,6 +196,14 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
                             size_t workspace_bytes, const int32_t* token_rows, void* stream);
+
+/*
+ * Reads and clears the current device's sticky misuse word.  Synchronises `stream`.
+ *   MB_OK               no attention call since the last check met a sequence longer than its max_seqlen;
+ *   MB_ERR_INVALID_ARG  one did (see max_seqlen of mb_alibi_attn_fwd for what happened to that sequence).
+ * The word is per device and shared by all streams and threads: a check reports misuse by any of them.
+ */
+MB_API mb_status mb_device_status(void* stream);
 
 /*
  * Add & LayerNorm over packed token rows with 2-byte storage ("Low Precision LayerNorm" paragraph of the
@@ -289,17 +312,8 @@ MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_strid
  *   kind   0: v_mfma_f32_32x32x16_bf16, independent accumulators (work = flops)
  *          1: fp32 fused multiply-add on the vector unit (work = flops)
  *          2: fp32 exponential on the vector unit (work = exponentials)
- *          3: 16-byte LDS reads in the pattern of the GEMM fragments (work = bytes)
- *          4: the GEMM kernels' inner loop fed from LDS, without global loads, LDS writes or barriers (work = flops)
- *          5: the same with the GEMM's one workgroup barrier per k step
- *          6: the same plus the GEMM's 16 LDS writes per thread and k step
- *          7: the same plus its 16 global loads per thread and k step, from 16 MiB that stay in L2
- *          8, 9, 10: rounds of 4 matrix instructions / of 48 independent multiply-adds / of both interleaved,
- *             eight waves per SIMD (work = rounds over all waves): do the matrix cores and the vector unit
- *             work at the same time?      11, 12, 13: the same with one wave per SIMD
- *          14, 15: kinds 8 and 10 with the same flops as 8 instructions of the 16x16x32 shape
- *   iters  rounds per lane (> 0).      out  dev, 4 floats of scratch (never written in practice); for kind 7 they
- *          are followed by the 16 MiB the probe reads (any content).
+ *          (the HBM ceiling is measured with mb_unpad as a plain row copy: identity indices)
+ *   iters  rounds per lane (> 0).      out  dev, 4 floats of scratch (never written in practice).
  *   work_per_launch  host, written.
  */
 MB_API mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream);

@@ -22,9 +22,11 @@ MB_OK, MB_ERR_INVALID_ARG, MB_ERR_UNSUPPORTED, MB_ERR_WORKSPACE, MB_ERR_HIP = ra
 MB_F32, MB_BF16 = 0, 1
 
 EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "mb_read_meta", "mb_unpad",
-           "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_bwd_workspace_bytes",
+           "mb_pad", "mb_zero_padding", "mb_alibi_attn_fwd", "mb_alibi_attn_fwd_workspace_bytes",
+           "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
-           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling")
+           "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling",
+           "mb_device_status")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -45,13 +47,16 @@ _lib.mb_zero_padding.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int,
 _lib.mb_alibi_attn_fwd.restype = c_int
 _lib.mb_alibi_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int, c_int,
                                    c_int, c_int, c_int, c_void_p, c_float, c_int, c_void_p, c_int64, c_void_p,
-                                   c_void_p, c_void_p]
+                                   c_void_p, c_size_t, c_void_p, c_void_p]
+_lib.mb_alibi_attn_fwd_workspace_bytes.restype = c_size_t
+_lib.mb_alibi_attn_fwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
                                    + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p])
-
+_lib.mb_device_status.restype = c_int
+_lib.mb_device_status.argtypes = [c_void_p]
 
 _lib.mb_add_layernorm_fwd.restype = c_int
 _lib.mb_add_layernorm_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_float, c_int,
@@ -182,7 +187,7 @@ def mb_zero_padding(padded: torch.Tensor, indices: torch.Tensor, T_cap: int, met
 
 
 def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None,
-                      token_rows=None, T=None):
+                      token_rows=None, T=None, workspace=None):
     """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32).
     With token_rows the views are over a padded batch ([B*L, H, D]) and T (the lse pitch) must be given."""
     _, H, D = q.shape
@@ -192,11 +197,18 @@ def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scal
         out = torch.empty((q.shape[0], H, D), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
+    need = mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, _dtype_code(q))
+    if workspace is None and need > 0:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     _check(_lib.mb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                   _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
-                                  _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _ptr(token_rows),
-                                  _stream()))
+                                  _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _ptr(token_rows), _stream()))
     return out, lse
+
+
+def mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int:
+    return int(_lib.mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code))
 
 
 def mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int:
@@ -221,6 +233,12 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
                                   _ptr(workspace), workspace.numel(), _ptr(token_rows), _stream()))
     return dq, dk, dv
+
+
+def mb_device_status() -> None:
+    """Raises MosaicAttnError(MB_ERR_INVALID_ARG) if an attention call since the last check met a sequence
+    longer than its max_seqlen; clears the device's sticky word.  Synchronises the current stream."""
+    _check(_lib.mb_device_status(_stream()))
 
 
 def mb_add_layernorm_fwd(x, r, gamma, beta, eps: float, T_cap=None, meta=None, y=None, s=None, mean=None, rstd=None,

@@ -1,14 +1,24 @@
 // C ABI of libmosaicattn: argument validation on the host (before any launch, so every error path is
 // testable without a GPU), then dispatch to the kernel launchers.
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 
 #include "common.h"
 
+// Device-resident state of the library (one copy per GPU, held until the process ends):
+//   g_misuse   sticky word set by an attention kernel that met a sequence longer than max_seqlen.
+// Host code never passes these names to a kernel (on the host they are stand-ins, not device addresses): it
+// asks the runtime for their device addresses once per device and uses those.
+__device__ int32_t g_misuse = 0;
+
 namespace mb {
 namespace {
 thread_local char g_error[512] = "";
+
+constexpr int kMaxDevices = 64;
+std::atomic<int32_t*> g_misuse_ptr[kMaxDevices];
 }
 
 mb_status fail(mb_status code, const char* fmt, ...) {
@@ -19,6 +29,27 @@ mb_status fail(mb_status code, const char* fmt, ...) {
   return code;
 }
 void clear_error() { g_error[0] = '\0'; }
+
+static mb_status current_device(int* dev) {
+  const hipError_t e = hipGetDevice(dev);
+  if (e != hipSuccess) return fail(MB_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (*dev < 0 || *dev >= kMaxDevices) return fail(MB_ERR_UNSUPPORTED, "device ordinal %d is beyond %d", *dev, kMaxDevices);
+  return MB_OK;
+}
+
+mb_status misuse_flag_address(int32_t** flag) {
+  int dev = 0;
+  const mb_status st = current_device(&dev);
+  if (st != MB_OK) return st;
+  int32_t* p = g_misuse_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {   // first call on this device (two racing threads get the same answer)
+    const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(g_misuse));
+    if (e != hipSuccess || p == nullptr) return fail(MB_ERR_HIP, "hipGetSymbolAddress(g_misuse): %s", hipGetErrorString(e));
+    g_misuse_ptr[dev].store(p, std::memory_order_release);
+  }
+  *flag = p;
+  return MB_OK;
+}
 
 mb_status check_launch(const char* what) {
   const hipError_t e = hipGetLastError();
@@ -75,6 +106,8 @@ mb_status check_attn_dims(int B, int T, int max_seqlen, int H, int D, mb_dtype d
   MB_REQUIRE(D % 8 == 0 || dt == MB_F32, MB_ERR_UNSUPPORTED, "bf16 head_dim %d is not a multiple of 8", D);
   MB_REQUIRE(dt != MB_F32 || D % 4 == 0, MB_ERR_UNSUPPORTED, "fp32 head_dim %d is not a multiple of 4", D);
   MB_REQUIRE((int64_t)T * H < ((int64_t)1 << 31), MB_ERR_UNSUPPORTED, "T*H=%lld exceeds 2^31", (long long)T * H);
+  MB_REQUIRE((int64_t)B * H < ((int64_t)1 << 30), MB_ERR_UNSUPPORTED, "B*H=%lld exceeds 2^30", (long long)B * H);
+  MB_REQUIRE(max_seqlen < (1 << 22), MB_ERR_UNSUPPORTED, "max_seqlen=%d exceeds 2^22", max_seqlen);
   return MB_OK;
 }
 
@@ -255,7 +288,8 @@ mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma,
 mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
-                            void* o, int64_t o_row_stride, float* lse, const int32_t* token_rows, void* stream) {
+                            void* o, int64_t o_row_stride, float* lse, void* workspace, size_t workspace_bytes,
+                            const int32_t* token_rows, void* stream) {
   clear_error();
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
@@ -275,30 +309,68 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   MB_CHECK_PTR(lse);
   MB_REQUIRE(token_rows == nullptr || aligned16(token_rows), MB_ERR_INVALID_ARG,
              "token_rows is not 16-byte aligned");
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows};
-  if (use_mfma(dt, D, softmax_scale))
-    return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
-                                (hipStream_t)stream);
-  MB_REQUIRE(max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
+  const bool mfma = use_mfma(dt, D, softmax_scale);
+  MB_REQUIRE(mfma || max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
              "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  const size_t need = mfma ? attn_fwd_mfma_workspace_bytes(B, max_seqlen, H) : 0;
+  MB_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), MB_ERR_WORKSPACE,
+             "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
+  MB_REQUIRE(need == 0 || aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
+  int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
+  st = misuse_flag_address(&misuse);
+  if (st != MB_OK) return st;
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows, misuse};
+  if (mfma)
+    return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
+                                workspace, (hipStream_t)stream);
   return launch_attn_fwd_generic(s, dt, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
                                  (hipStream_t)stream);
+}
+
+size_t mb_alibi_attn_fwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt) {
+  if (B < 0 || T < 0 || max_seqlen < 0 || H <= 0 || D <= 0 || D > 128) return 0;
+  if (dt != MB_BF16 || D != 64) return 0;                    // the generic kernels need none
+  return attn_fwd_mfma_workspace_bytes(B, max_seqlen, H);   // the work plan (nothing for max_seqlen <= 128)
 }
 
 size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, int D, mb_dtype dt) {
   if (B < 0 || T < 0 || max_seqlen < 0 || H <= 0 || D <= 0 || D > 128) return 0;
   if (dt != MB_F32 && dt != MB_BF16) return 0;
-  return attn_bwd_workspace_bytes(B, H, T);   // Delta [H, T] float + sequence order [B] int32
+  if (dt != MB_BF16 || D != 64) return attn_bwd_delta_bytes(H, T);   // Delta [H, T] float
+  return attn_bwd_mfma_workspace_bytes(B, T, max_seqlen, H);          // Delta, then the work plan
 }
 
-mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v, const void* o,
-                            const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
-                            int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
-                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
-                            void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
-                            int64_t dv_row_stride, void* workspace, size_t workspace_bytes,
-                            const int32_t* token_rows, void* stream) {
-  clear_error();
+// The backward after its workspace checks.
+static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k, const void* v, const void* o,
+                                  const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
+                                  int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                                  int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
+                                  void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
+                                  int64_t dv_row_stride, void* workspace, const int32_t* token_rows, void* stream) {
+  const bool mfma = use_mfma(dt, D, softmax_scale);
+  MB_REQUIRE(mfma || max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
+             "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
+  const mb_status st = misuse_flag_address(&misuse);
+  if (st != MB_OK) return st;
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows, misuse};
+  if (mfma)
+    return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
+                                o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
+                                (float*)workspace, (hipStream_t)stream);
+  return launch_attn_bwd_generic(s, dt, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride,
+                                 v_row_stride, o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride,
+                                 dv_row_stride, (float*)workspace, (hipStream_t)stream);
+}
+
+// Host-side validation of the backward; *empty is set when there is nothing to do.
+static mb_status attn_bwd_validate(const void* dout, const void* q, const void* k, const void* v, const void* o,
+                                   const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
+                                   int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                                   int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
+                                   void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
+                                   int64_t dv_row_stride, const int32_t* token_rows, bool* empty) {
+  *empty = false;
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
   MB_CHECK_STRIDE(do_row_stride, H, D);
@@ -310,7 +382,10 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
   MB_CHECK_STRIDE(dk_row_stride, H, D);
   MB_CHECK_STRIDE(dv_row_stride, H, D);
   MB_REQUIRE(std::isfinite(softmax_scale), MB_ERR_INVALID_ARG, "softmax_scale is not finite");
-  if (B == 0 || T == 0) return MB_OK;
+  if (B == 0 || T == 0) {
+    *empty = true;
+    return MB_OK;
+  }
   MB_REQUIRE(max_seqlen > 0, MB_ERR_INVALID_ARG, "max_seqlen=0 with T=%d tokens", T);
   MB_CHECK_PTR(dout);
   MB_CHECK_PTR(q);
@@ -323,22 +398,50 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
   MB_CHECK_PTR(dq);
   MB_CHECK_PTR(dk);
   MB_CHECK_PTR(dv);
+  MB_REQUIRE(token_rows == nullptr || aligned16(token_rows), MB_ERR_INVALID_ARG,
+             "token_rows is not 16-byte aligned");
+  return MB_OK;
+}
+
+mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, const void* v, const void* o,
+                            const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
+                            int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
+                            void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
+                            int64_t dv_row_stride, void* workspace, size_t workspace_bytes,
+                            const int32_t* token_rows, void* stream) {
+  clear_error();
+  bool empty = false;
+  const mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
+                                         o_row_stride, cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq,
+                                         dk, dv, dq_row_stride, dk_row_stride, dv_row_stride, token_rows, &empty);
+  if (st != MB_OK || empty) return st;
   const size_t need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
   MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
-  MB_REQUIRE(token_rows == nullptr || aligned16(token_rows), MB_ERR_INVALID_ARG,
-             "token_rows is not 16-byte aligned");
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows};
-  if (use_mfma(dt, D, softmax_scale))
-    return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
-                                o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
-                                (float*)workspace, (hipStream_t)stream);
-  MB_REQUIRE(max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
-             "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
-  return launch_attn_bwd_generic(s, dt, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride,
-                                 v_row_stride, o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride,
-                                 dv_row_stride, (float*)workspace, (hipStream_t)stream);
+  return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
+                          cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
+                          dk_row_stride, dv_row_stride, workspace, token_rows, stream);
+}
+
+mb_status mb_device_status(void* stream) {
+  clear_error();
+  int32_t* flag = nullptr;
+  mb_status st = misuse_flag_address(&flag);
+  if (st != MB_OK) return st;
+  int32_t seen = 0;
+  hipError_t e = hipMemcpyAsync(&seen, flag, sizeof(seen), hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return fail(MB_ERR_HIP, "mb_device_status: %s", hipGetErrorString(e));
+  if (seen == 0) return MB_OK;
+  const int32_t zero = 0;
+  e = hipMemcpyAsync(flag, &zero, sizeof(zero), hipMemcpyHostToDevice, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return fail(MB_ERR_HIP, "mb_device_status: %s", hipGetErrorString(e));
+  return fail(MB_ERR_INVALID_ARG,
+              "an attention call since the last check met a sequence longer than its max_seqlen; that sequence was "
+              "skipped (forward: its log-sum-exp rows are NaN; backward: its gradient rows were left untouched)");
 }
 
 mb_status mb_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta_dev, int hidden,
@@ -401,7 +504,7 @@ mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_stride, int 
 
 mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream) {
   clear_error();
-  MB_REQUIRE(kind >= 0 && kind <= 15, MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
+  MB_REQUIRE(kind >= 0 && kind <= 2, MB_ERR_INVALID_ARG, "unknown probe kind %d", kind);
   MB_REQUIRE(iters > 0 && iters <= (1 << 24), MB_ERR_INVALID_ARG, "iters must be in [1, 2^24] (got %d)", iters);
   MB_REQUIRE(work_per_launch != nullptr, MB_ERR_INVALID_ARG, "work_per_launch is NULL");
   MB_CHECK_PTR(out);

@@ -17,6 +17,7 @@
 //           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.
 // Masking costs nothing: rows beyond the sequence end are staged as zeros and their lse as +inf
 // (P = 0); zero K/V rows make the products with out-of-range keys vanish.
+#include "attn_plan.h"
 #include "common.h"
 #include "mfma_util.h"
 
@@ -30,27 +31,18 @@ constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
 // ------------------------------------------------------------------------------------------------ delta
 // 8 lanes per (token, head) row: 16 bytes of dO and O each, then a 3-step butterfly.
 //
-// The first blocks also rank the sequences by length for the two kernels that follow: order[r] = the
-// sequence with r longer ones before it (ties by index), so that those kernels dispatch their heaviest
-// workgroups first and short ones fill the tail.  One thread per sequence counts the larger keys
-// (length, reversed index); `order` is NULL when there are too many sequences for that to pay.
+// The first eight workgroups also build the work plan of the two kernels that follow (one list each; see
+// attn_plan.h) before they take their share of rows.
 __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
                                                              const uint16_t* __restrict__ o, int64_t dos, int64_t os,
                                                              int T, int H, const int32_t* __restrict__ cu, int B,
                                                              float* __restrict__ delta,
-                                                             const int32_t* __restrict__ rows,
-                                                             int32_t* __restrict__ order) {
-  if (order != nullptr && (int)blockIdx.x * 256 < B) {
-    const int cand = blockIdx.x * 256 + threadIdx.x;
-    if (cand < B) {
-      const int len = cu[cand + 1] - cu[cand];
-      int r = 0;
-      for (int other = 0; other < B; ++other) {   // uniform index: scalar loads
-        const int lo = cu[other + 1] - cu[other];
-        r += (lo > len || (lo == len && other < cand)) ? 1 : 0;
-      }
-      order[r] = cand;
-    }
+                                                             const int32_t* __restrict__ rows, int max_seqlen,
+                                                             int64_t plan_cap, int32_t* __restrict__ plan,
+                                                             int32_t* __restrict__ misuse) {
+  if (blockIdx.x < kPlanXcds) {
+    __shared__ __attribute__((aligned(16))) PlanLds lds;
+    build_plan_list(cu, B, H, max_seqlen, plan_cap, plan, blockIdx.x, misuse, lds);
   }
   const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
   const int sub = threadIdx.x & 7;
@@ -100,20 +92,17 @@ template <int kMode>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
-    int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
+    int64_t qs, int64_t ks, int64_t vs, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int64_t dks, int64_t dvs, int T,
-    const int32_t* __restrict__ token_rows, const int32_t* __restrict__ order) {
+    const int32_t* __restrict__ token_rows, const int32_t* __restrict__ plan, int64_t plan_cap) {
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: Q tile, dO tile
   __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
   __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
 
-  const int b = order ? order[blockIdx.z] : (int)blockIdx.z;
-  const int start = cu[b];
-  const int n = cu[b + 1] - start;
-  const int h = blockIdx.y;
-  const int kv0 = blockIdx.x * kTile;
-  if (kv0 >= n) return;
+  int start, n, ktile, h;
+  if (!plan_fetch(plan, plan_cap, &start, &n, &ktile, &h)) return;   // this XCD's list is shorter
+  const int kv0 = ktile * kTile;   // < n by construction of the plan
   // first buffer row of the sequence, and whether its tokens sit in consecutive rows
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
   const bool contig =
@@ -335,18 +324,15 @@ template <int kMode>
 __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
-    int64_t qs, int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes,
+    int64_t qs, int64_t ks, int64_t vs, const float* __restrict__ slopes,
     float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows,
-    const int32_t* __restrict__ order) {
+    const int32_t* __restrict__ plan, int64_t plan_cap) {
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
 
-  const int b = order ? order[blockIdx.z] : (int)blockIdx.z;
-  const int start = cu[b];
-  const int n = cu[b + 1] - start;
-  const int h = blockIdx.y;
-  const int q0 = blockIdx.x * kTile;
-  if (q0 >= n) return;
+  int start, n, qtile, h;
+  if (!plan_fetch(plan, plan_cap, &start, &n, &qtile, &h)) return;
+  const int q0 = qtile * kTile;
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
   const bool contig =
       kMode == kRowsIdentity ||
@@ -550,7 +536,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
-    uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows) {
+    uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows,
+    int32_t* __restrict__ misuse) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
   __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
@@ -559,8 +546,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 
   const int h = blockIdx.x, b = blockIdx.y;
   const int start = cu[b];
-  const int n = min(cu[b + 1] - start, kTile);   // the caller promised max_seqlen <= 128
+  const int n = cu[b + 1] - start;
   if (n <= 0) return;
+  if (n > kTile) {   // the caller promised max_seqlen <= 128: skipped, never truncated
+    raise_misuse(misuse);
+    return;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
@@ -803,35 +794,33 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   hipLaunchKernelGGL(attn_bwd_fused128_kernel<R>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs, \
                      ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv,     \
-                     dqs, dks, dvs, s.T, s.token_rows)
+                     dqs, dks, dvs, s.T, s.token_rows, s.misuse)
     if (s.token_rows) MB_LAUNCH_FUSED(true);
     else MB_LAUNCH_FUSED(false);
 #undef MB_LAUNCH_FUSED
     return check_launch("attn_bwd_fused128_kernel");
   }
   const int64_t rows = (int64_t)s.T * s.H;
-  // the sequence order sits behind Delta in the workspace
-  int32_t* order = s.B <= kSortMaxB
-                       ? reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T))
-                       : nullptr;
-  const int64_t delta_blocks = (rows + 31) / 32, order_blocks = order ? (s.B + 255) / 256 : 0;
-  hipLaunchKernelGGL(attn_bwd_delta_kernel,
-                     dim3((unsigned)(delta_blocks > order_blocks ? delta_blocks : order_blocks)), dim3(256), 0,
-                     stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens, s.B,
-                     delta_ws, s.token_rows, order);
+  // the work plan sits behind Delta in the workspace
+  const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
+  if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
+  int32_t* plan = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T));
+  const int64_t delta_blocks = (rows + 31) / 32;
+  hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)(delta_blocks > kPlanXcds ? delta_blocks : kPlanXcds)),
+                     dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens,
+                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, plan, s.misuse);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
-  const int tiles = (s.max_seqlen + kTile - 1) / kTile;
   // buffer-load path: a sequence's rows within 2^31 bytes of its first
   int64_t widest = qs > ks ? qs : ks;
   widest = widest > vs ? widest : vs;
   widest = widest > dos ? widest : dos;
   const bool narrow = (int64_t)s.max_seqlen * widest * 2 < ((int64_t)1 << 31);
+  const dim3 grid((unsigned)(cap * kPlanXcds));
 #define MB_LAUNCH_DKV(R)                                                                                           \
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,   \
-                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows,   \
-                     order)
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, grid, dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)q, \
+                     (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs, s.slopes, s.scale,     \
+                     (uint16_t*)dk, (uint16_t*)dv, dks, dvs, s.T, s.token_rows, plan, cap)
   if (!narrow) MB_LAUNCH_DKV(kRowsPerLane);
   else if (s.token_rows) MB_LAUNCH_DKV(kRowsMaybeContiguous);
   else MB_LAUNCH_DKV(kRowsIdentity);
@@ -839,14 +828,18 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   st = check_launch("attn_bwd_dkv_kernel");
   if (st != MB_OK) return st;
 #define MB_LAUNCH_DQ(R)                                                                                            \
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
-                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs,   \
-                     s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows, order)
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, grid, dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)q,  \
+                     (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs, s.slopes, s.scale,     \
+                     (uint16_t*)dq, dqs, s.T, s.token_rows, plan, cap)
   if (!narrow) MB_LAUNCH_DQ(kRowsPerLane);
   else if (s.token_rows) MB_LAUNCH_DQ(kRowsMaybeContiguous);
   else MB_LAUNCH_DQ(kRowsIdentity);
 #undef MB_LAUNCH_DQ
   return check_launch("attn_bwd_dq_kernel");
+}
+
+size_t attn_bwd_mfma_workspace_bytes(int B, int T, int max_seqlen, int H) {
+  return attn_bwd_delta_bytes(H, T) + (max_seqlen <= kTile ? 0 : attn_plan_bytes(B, max_seqlen, H));
 }
 
 }  // namespace mb

@@ -11,6 +11,7 @@
 //   * a query's row statistics (max, sum) are reductions over a lane's own registers plus one
 //     exchange with the partner lane l^32, and
 //   * the accumulator tile, rounded to bf16, is already the B operand of O^T += V^T P^T.
+#include "attn_plan.h"
 #include "common.h"
 #include "mfma_util.h"
 
@@ -32,7 +33,29 @@ constexpr int kVStride = 80;   // LDS row pitch of V in bf16 (160 B): 4-row tran
 constexpr int kTileK = 64;                                        // keys per LDS tile
 constexpr int kBufElems = kTileK * kKStride + kTileK * kVStride;  // one K tile + one V tile
 
-//
+// A sequence longer than the max_seqlen the launch was sized for: the sticky flag is raised and the
+// sequence's log-sum-exp rows (n of them, from `row`) become NaN, so the misuse shows in the result too.
+__device__ __forceinline__ void poison_lse(float* __restrict__ row, int n, int32_t* __restrict__ misuse) {
+  raise_misuse(misuse);
+  for (int i = threadIdx.x; i < n; i += blockDim.x) row[i] = __builtin_nanf("");
+}
+
+// The forward's own plan launch: workgroup c builds list c (see attn_plan.h); workgroup 0 then marks the
+// sequences the plan skipped (longer than max_seqlen) by setting their log-sum-exp rows to NaN.
+__global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(const int32_t* __restrict__ cu, int B, int H,
+                                                                 int max_seqlen, int64_t cap, int32_t* __restrict__ plan,
+                                                                 int32_t* __restrict__ misuse, float* __restrict__ lse,
+                                                                 int T) {
+  __shared__ __attribute__((aligned(16))) PlanLds lds;
+  build_plan_list(cu, B, H, max_seqlen, cap, plan, blockIdx.x, misuse, lds);
+  if (blockIdx.x != 0) return;
+  for (int b = 0; b < B; ++b) {
+    const int s0 = cu[b], len = cu[b + 1] - s0;
+    if (len > max_seqlen)
+      for (int h = 0; h < H; ++h) poison_lse(lse + (int64_t)h * T + s0, len, misuse);
+  }
+}
+
 // kMode (see kRowsIdentity .. in common.h): for a sequence whose tokens sit in consecutive rows of the
 // activation buffers, spanning fewer than 2^31 bytes, the K/V rows of a tile are fetched with buffer loads
 // whose descriptor starts at the tile's first row and ends at the sequence's last one: the address is
@@ -41,17 +64,15 @@ constexpr int kBufElems = kTileK * kKStride + kTileK * kVStride;  // one K tile 
 template <int kMode>
 __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
-    int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
-    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ token_rows) {
+    int64_t ks, int64_t vs, const float* __restrict__ slopes, float scale, uint16_t* __restrict__ o, int64_t os,
+    float* __restrict__ lse, int T, const int32_t* __restrict__ token_rows, const int32_t* __restrict__ plan,
+    int64_t plan_cap) {
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
-  __shared__ __attribute__((aligned(16))) uint32_t s_sort[kSortLdsWords];
 
-  int start, n;
-  seq_by_length_rank(cu, gridDim.z, blockIdx.z, s_sort, &start, &n);
-  const int h = blockIdx.y;
-  const int q0 = blockIdx.x * kBlockQ;
-  if (q0 >= n) return;
+  int start, n, qtile, h;
+  if (!plan_fetch(plan, plan_cap, &start, &n, &qtile, &h)) return;   // this XCD's list is shorter
+  const int q0 = qtile * kBlockQ;   // < n by construction of the plan
   // first buffer row of the sequence, and whether its tokens sit in consecutive rows
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
   const bool contig =
@@ -275,7 +296,8 @@ template <bool kRows>
 __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
-    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows) {
+    uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows,
+    int32_t* __restrict__ misuse) {
   // Every global access is a full 128-byte row of one head shared by 8 lanes (16 bytes each); the
   // fragment layouts the matrix cores need are produced by passing through LDS:
   //   sV first carries the Q tile (rows -> Q^T fragments), then V;  after the S phase each wave reuses
@@ -285,8 +307,12 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
 
   const int h = blockIdx.x, b = blockIdx.y;
   const int start = cu[b];
-  const int n = min(cu[b + 1] - start, kBlockK);   // the caller promised max_seqlen <= 128
+  const int n = cu[b + 1] - start;
   if (n <= 0) return;
+  if (n > kBlockK) {   // the caller promised max_seqlen <= 128: skipped, never truncated
+    poison_lse(lse + (int64_t)h * T + start, n, misuse);
+    return;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
@@ -477,31 +503,43 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
 }  // namespace
 
 mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
-                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream) {
-  const int tiles = (s.max_seqlen + kBlockQ - 1) / kBlockQ;
+                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, void* workspace,
+                               hipStream_t stream) {
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
   if (s.max_seqlen <= kBlockK) {
     if (s.token_rows)
       hipLaunchKernelGGL(attn_fwd_short_kernel<true>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                         (uint16_t*)o, os, lse, s.T, s.token_rows);
+                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse);
     else
       hipLaunchKernelGGL(attn_fwd_short_kernel<false>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                         (uint16_t*)o, os, lse, s.T, s.token_rows);
+                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse);
     return check_launch("attn_fwd_short_kernel");
   }
+  // any length: plan (8 small workgroups), then one workgroup per plan slot
+  const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
+  if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
+  int32_t* plan = static_cast<int32_t*>(workspace);
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(kPlanXcds), dim3(kPlanThreads), 0, stream, s.cu_seqlens, s.B, s.H,
+                     s.max_seqlen, cap, plan, s.misuse, lse, s.T);
+  mb_status st = check_launch("attn_plan_kernel");
+  if (st != MB_OK) return st;
   // buffer-load path: a sequence's K / V rows within 2^31 bytes of its first
   const int64_t span = (int64_t)s.max_seqlen * (ks > vs ? ks : vs) * 2;
-#define MB_LAUNCH_TILED(M)                                                                                        \
-  hipLaunchKernelGGL(attn_fwd_tiled_kernel<M>, dim3(tiles, s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,   \
-                     (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,         \
-                     (uint16_t*)o, os, lse, s.T, s.token_rows)
+#define MB_LAUNCH_TILED(M)                                                                                         \
+  hipLaunchKernelGGL(attn_fwd_tiled_kernel<M>, dim3((unsigned)(cap * kPlanXcds)), dim3(256), 0, stream,            \
+                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.slopes, s.scale,    \
+                     (uint16_t*)o, os, lse, s.T, s.token_rows, plan, cap)
   if (span >= ((int64_t)1 << 31)) MB_LAUNCH_TILED(kRowsPerLane);
   else if (s.token_rows) MB_LAUNCH_TILED(kRowsMaybeContiguous);
   else MB_LAUNCH_TILED(kRowsIdentity);
 #undef MB_LAUNCH_TILED
   return check_launch("attn_fwd_tiled_kernel");
+}
+
+size_t attn_fwd_mfma_workspace_bytes(int B, int max_seqlen, int H) {
+  return max_seqlen <= kBlockK ? 0 : attn_plan_bytes(B, max_seqlen, H);
 }
 
 }  // namespace mb

@@ -42,7 +42,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
                                                          const int32_t* __restrict__ cu, int B, int T, int H, int D,
                                                          const float* __restrict__ slopes, float scale,
                                                          E* __restrict__ o, int64_t os, float* __restrict__ lse,
-                                                         const int32_t* __restrict__ rows) {
+                                                         const int32_t* __restrict__ rows, int max_seqlen,
+                                                         int32_t* __restrict__ misuse) {
   extern __shared__ float smem[];
   float* sq = smem;
   float* ss = smem + D;
@@ -50,6 +51,11 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const E* __restrict__ q
   if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, i = t - start;
+  if (n > max_seqlen) {   // longer than the caller promised (the score row in LDS holds max_seqlen entries): skipped
+    raise_misuse(misuse);
+    if (lane == 0) lse[(int64_t)h * T + t] = __builtin_nanf("");
+    return;
+  }
   const float slope = slopes[h];
   for (int d = lane; d < D; d += 64) sq[d] = to_f32(q[tok_row(rows, t) * qs + h * D + d]);
   __syncthreads();
@@ -87,7 +93,8 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
     const E* __restrict__ dout, const E* __restrict__ q, const E* __restrict__ k, const E* __restrict__ v,
     const E* __restrict__ o, const float* __restrict__ lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
     int64_t os, const int32_t* __restrict__ cu, int B, int T, int H, int D, const float* __restrict__ slopes,
-    float scale, E* __restrict__ dq, int64_t dqs, float* __restrict__ delta, const int32_t* __restrict__ rows) {
+    float scale, E* __restrict__ dq, int64_t dqs, float* __restrict__ delta, const int32_t* __restrict__ rows,
+    int max_seqlen, int32_t* __restrict__ misuse) {
   extern __shared__ float smem[];
   float* sq = smem;
   float* sg = smem + D;
@@ -96,6 +103,10 @@ __global__ __launch_bounds__(64) void bwd_generic_row_kernel(
   if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, i = t - start;
+  if (n > max_seqlen) {
+    raise_misuse(misuse);
+    return;
+  }
   const float slope = slopes[h];
   float part = 0.f;
   for (int d = lane; d < D; d += 64) {
@@ -135,7 +146,7 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
     const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos, int64_t qs, int64_t ks,
     int64_t vs, const int32_t* __restrict__ cu, int B, int T, int H, int D, int max_seqlen,
     const float* __restrict__ slopes, float scale, E* __restrict__ dk, E* __restrict__ dv, int64_t dks,
-    int64_t dvs, const int32_t* __restrict__ rows) {
+    int64_t dvs, const int32_t* __restrict__ rows, int32_t* __restrict__ misuse) {
   extern __shared__ float smem[];
   float* sk = smem;
   float* sv = smem + D;
@@ -145,6 +156,10 @@ __global__ __launch_bounds__(64) void bwd_generic_col_kernel(
   if (t >= cu[B]) return;   // T may be a capacity: rows past the last real token are not touched
   const int b = find_seq(cu, B, t);
   const int start = cu[b], n = cu[b + 1] - start, j = t - start;
+  if (n > max_seqlen) {
+    raise_misuse(misuse);
+    return;
+  }
   const float slope = slopes[h];
   for (int d = lane; d < D; d += 64) {
     sk[d] = to_f32(k[tok_row(rows, t) * ks + h * D + d]);
@@ -180,7 +195,8 @@ mb_status fwd_t(const AttnShape& s, const void* q, const void* k, const void* v,
                 void* o, int64_t os, float* lse, hipStream_t stream) {
   const size_t smem = sizeof(float) * ((size_t)s.D + s.max_seqlen);
   hipLaunchKernelGGL(fwd_generic_kernel<E>, dim3(s.T, s.H), dim3(64), smem, stream, (const E*)q, (const E*)k,
-                     (const E*)v, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H, s.D, s.slopes, s.scale, (E*)o, os, lse, s.token_rows);
+                     (const E*)v, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H, s.D, s.slopes, s.scale, (E*)o, os, lse, s.token_rows,
+                     s.max_seqlen, s.misuse);
   return check_launch("fwd_generic_kernel");
 }
 
@@ -191,13 +207,13 @@ mb_status bwd_t(const AttnShape& s, const void* dout, const void* q, const void*
   const size_t smem_row = sizeof(float) * (2 * (size_t)s.D + s.max_seqlen);
   hipLaunchKernelGGL(bwd_generic_row_kernel<E>, dim3(s.T, s.H), dim3(64), smem_row, stream, (const E*)dout,
                      (const E*)q, (const E*)k, (const E*)v, (const E*)o, lse, dos, qs, ks, vs, os, s.cu_seqlens, s.B,
-                     s.T, s.H, s.D, s.slopes, s.scale, (E*)dq, dqs, delta, s.token_rows);
+                     s.T, s.H, s.D, s.slopes, s.scale, (E*)dq, dqs, delta, s.token_rows, s.max_seqlen, s.misuse);
   mb_status st = check_launch("bwd_generic_row_kernel");
   if (st != MB_OK) return st;
   const size_t smem_col = sizeof(float) * (2 * (size_t)s.D + 2 * (size_t)s.max_seqlen);
   hipLaunchKernelGGL(bwd_generic_col_kernel<E>, dim3(s.T, s.H), dim3(64), smem_col, stream, (const E*)dout,
                      (const E*)q, (const E*)k, (const E*)v, lse, delta, dos, qs, ks, vs, s.cu_seqlens, s.B, s.T, s.H,
-                     s.D, s.max_seqlen, s.slopes, s.scale, (E*)dk, (E*)dv, dks, dvs, s.token_rows);
+                     s.D, s.max_seqlen, s.slopes, s.scale, (E*)dk, (E*)dv, dks, dvs, s.token_rows, s.misuse);
   return check_launch("bwd_generic_col_kernel");
 }
 

@@ -22,7 +22,16 @@ struct AttnShape {
   const float* slopes;
   float scale;
   const int32_t* token_rows;   // NULL, or [T]: row of token t inside the activation buffers
+  int32_t* misuse;             // this device's sticky flag: set by a kernel that meets a sequence longer than max_seqlen
 };
+
+// Device word that the attention kernels set when a sequence is longer than the max_seqlen their launch was
+// sized for (such a sequence is skipped, never truncated); read and cleared by mb_device_status.  One copy per
+// device; returns its device address for the current device in *flag.
+mb_status misuse_flag_address(int32_t** flag);
+
+// What a kernel does on meeting such a sequence: raise the flag (every thread stores the same word).
+__device__ __forceinline__ void raise_misuse(int32_t* flag) { *flag = 1; }
 
 // Row of packed token t inside the activation buffers: t itself, or token_rows[t] when the call reads
 // and writes a padded batch directly.
@@ -40,71 +49,13 @@ __device__ __forceinline__ int64_t tok_row(const int32_t* __restrict__ rows, int
 // The last two require that a sequence's rows span fewer than 2^31 bytes.
 enum { kRowsPerLane = 0, kRowsIdentity = 1, kRowsMaybeContiguous = 2 };
 
-// Longest-sequence-first work order for kernels whose workgroups run for a time that grows with the
-// sequence length: finds the sequence whose length has rank `rank` (0 = longest; ties by index), so
-// that the heaviest workgroups are dispatched first and short ones fill the tail, and returns its index
-// with its first token in *start and its length in *len.  Every thread of the block must call it (it
-// contains barriers); `lds` is kSortLdsWords words of LDS that nothing else writes.
-// Each sequence gets the key (length, reversed index) packed in one word; keys and sequence starts are
-// staged in LDS once (the only global loads), and a thread ranks its candidate by counting the larger
-// keys, sixteen per round of LDS reads (with few sequences, two or four threads share a candidate).  For
-// B > kSortMaxB the order is left as it is (many sequences balance by themselves).
-static constexpr int kSortMaxB = 512;
-static constexpr int kSortLdsWords = 2 * kSortMaxB + 24;
-__device__ __forceinline__ int seq_by_length_rank(const int32_t* __restrict__ cu, int B, int rank, uint32_t* lds,
-                                                  int* start, int* len) {
-  if (B > kSortMaxB) {
-    const int s0 = __builtin_amdgcn_readfirstlane(cu[rank]);
-    *start = s0;
-    *len = __builtin_amdgcn_readfirstlane(cu[rank + 1]) - s0;
-    return rank;
-  }
-  uint32_t* keys = lds;                                        // [kSortMaxB + 16]
-  int* starts = reinterpret_cast<int*>(lds) + kSortMaxB + 16;  // [kSortMaxB + 1]
-  int* slot = starts + kSortMaxB + 1;                          // [1]
-  const int Bp = (B + 15) & ~15;                               // keys are scanned 16 at a time
-  for (int i = threadIdx.x; i < Bp; i += blockDim.x) {
-    const int s0 = cu[min(i, B)], s1 = cu[min(i + 1, B)];      // both loads in flight together
-    if (i < B) starts[i] = s0;
-    // padding keys are 0: never larger than a real key
-    keys[i] = i < B ? ((uint32_t)min(s1 - s0, (1 << 22)) << 9) | (uint32_t)(kSortMaxB - 1 - i) : 0u;
-  }
-  if (threadIdx.x == 0) starts[B] = cu[B];
-  __syncthreads();
-  // `split` neighbouring lanes share a candidate, each scanning every split-th group of 16 keys
-  const int split = B <= 64 ? 4 : (B <= 128 ? 2 : 1);
-  const int part = threadIdx.x & (split - 1);
-  for (int cand = threadIdx.x / split; cand < B; cand += blockDim.x / split) {
-    const uint32_t mine = keys[cand];
-    int r = 0;
-    for (int other = 16 * part; other < Bp; other += 16 * split) {
-      uint4 k4[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) k4[u] = *reinterpret_cast<const uint4*>(&keys[other + 4 * u]);
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        r += (k4[u].x > mine ? 1 : 0) + (k4[u].y > mine ? 1 : 0) + (k4[u].z > mine ? 1 : 0) + (k4[u].w > mine ? 1 : 0);
-    }
-    if (split > 1) r += __shfl_xor(r, 1, 64);
-    if (split > 2) r += __shfl_xor(r, 2, 64);
-    if (r == rank) *slot = cand;
-  }
-  __syncthreads();
-  // (values read from LDS: readfirstlane tells the compiler that they are wave-uniform)
-  const int b = __builtin_amdgcn_readfirstlane(*slot);
-  const int s0 = __builtin_amdgcn_readfirstlane(starts[b]);
-  *start = s0;
-  *len = __builtin_amdgcn_readfirstlane(starts[b + 1]) - s0;
-  return b;
-}
-
-// Workspace of the backward attention: Delta [H, T] float, then the sequence order [B] int32.
+// Workspace of the backward attention: Delta [H, T] float, then (matrix-core kernels, max_seqlen > 128) the
+// work plan; the forward's workspace is the work plan alone (nothing for max_seqlen <= 128).
 __host__ __device__ inline size_t attn_bwd_delta_bytes(int H, int T) {
   return ((size_t)H * (size_t)T * sizeof(float) + 255) / 256 * 256;
 }
-__host__ __device__ inline size_t attn_bwd_workspace_bytes(int B, int H, int T) {
-  return attn_bwd_delta_bytes(H, T) + ((size_t)B * sizeof(int32_t) + 255) / 256 * 256;
-}
+size_t attn_fwd_mfma_workspace_bytes(int B, int max_seqlen, int H);
+size_t attn_bwd_mfma_workspace_bytes(int B, int T, int max_seqlen, int H);
 
 // ---- launchers (each enqueues on `stream`, returns MB_OK or MB_ERR_HIP) ----
 mb_status launch_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,
@@ -159,7 +110,8 @@ mb_status launch_attn_bwd_generic(const AttnShape& s, mb_dtype dt, const void* d
 
 // bf16, D = 64 matrix-core kernels.
 mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k, const void* v, int64_t qs,
-                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, hipStream_t stream);
+                               int64_t ks, int64_t vs, void* o, int64_t os, float* lse, void* workspace,
+                               hipStream_t stream);
 mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void* q, const void* k, const void* v,
                                const void* o, const float* lse, int64_t dos, int64_t qs, int64_t ks, int64_t vs,
                                int64_t os, void* dq, void* dk, void* dv, int64_t dqs, int64_t dks, int64_t dvs,

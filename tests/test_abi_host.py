@@ -46,10 +46,10 @@ def test_slopes_against_fixture():
 
 def fwd_args(**over):
     a = dict(q=A, k=A, v=A, qs=768, ks=768, vs=768, cu=A, B=2, T=64, max_seqlen=32, H=12, D=64, slopes=A,
-             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, rows=None, stream=None)
+             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, ws=None, wsb=0, rows=None, stream=None)
     a.update(over)
     return [a[x] for x in ("q", "k", "v", "qs", "ks", "vs", "cu", "B", "T", "max_seqlen", "H", "D", "slopes", "scale",
-                           "dt", "o", "os", "lse", "rows", "stream")]
+                           "dt", "o", "os", "lse", "ws", "wsb", "rows", "stream")]
 
 
 def bwd_args(**over):
@@ -78,6 +78,10 @@ def bwd_args(**over):
     (dict(max_seqlen=0), mb.MB_ERR_INVALID_ARG, "max_seqlen"),
     (dict(dt=mb.MB_F32, D=16, H=2, max_seqlen=1 << 20), mb.MB_ERR_UNSUPPORTED, "max_seqlen"),
     (dict(rows=A + 4), mb.MB_ERR_INVALID_ARG, "token_rows"),
+    (dict(max_seqlen=512), mb.MB_ERR_WORKSPACE, "workspace"),                       # any-length kernels need their plan
+    (dict(max_seqlen=512, ws=A, wsb=64), mb.MB_ERR_WORKSPACE, "needed"),
+    (dict(max_seqlen=512, ws=A + 4, wsb=1 << 20), mb.MB_ERR_INVALID_ARG, "workspace is not 16-byte"),
+    (dict(max_seqlen=1 << 23), mb.MB_ERR_UNSUPPORTED, "2^22"),
 ])
 def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
     assert lib.mb_alibi_attn_fwd(*fwd_args(**over)) == status
@@ -111,6 +115,12 @@ def test_degenerate_sizes_are_ok_and_touch_nothing():
 def test_workspace_query():
     need = mb.mb_alibi_attn_bwd_workspace_bytes(256, 27000, 128, 12, 64, mb.MB_BF16)
     assert need >= 12 * 27000 * 4 and need % 256 == 0
+    # the any-length kernels add their work plan: 8 lists of 16-byte items, one per (sequence, head, 128 tokens)
+    plan = mb.mb_alibi_attn_fwd_workspace_bytes(64, 32768, 512, 12, 64, mb.MB_BF16)
+    assert plan >= 64 * 12 * 4 * 16 and plan % 256 == 0
+    assert mb.mb_alibi_attn_bwd_workspace_bytes(64, 32768, 512, 12, 64, mb.MB_BF16) >= 12 * 32768 * 4 + plan
+    assert mb.mb_alibi_attn_fwd_workspace_bytes(256, 32768, 128, 12, 64, mb.MB_BF16) == 0      # single-tile kernel
+    assert mb.mb_alibi_attn_fwd_workspace_bytes(4, 128, 32, 2, 16, mb.MB_F32) == 0              # generic kernels
     assert mb.mb_alibi_attn_bwd_workspace_bytes(1, 1, 1, 0, 64, mb.MB_BF16) == 0
     assert mb.mb_alibi_attn_bwd_workspace_bytes(1, 1, 1, 1, 64, 9) == 0
 
@@ -204,7 +214,7 @@ def test_linear_and_gelu_gate_reject_bad_arguments():
 
 def test_probe_rejects_bad_arguments():
     w = ctypes.c_double(0.0)
-    assert lib.mb_probe_ceiling(16, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_ceiling(3, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 0, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, None, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
     assert lib.mb_probe_ceiling(0, 10, A, None, None) == mb.MB_ERR_INVALID_ARG

@@ -131,3 +131,18 @@ def test_layernorm_reads_and_writes_a_padded_batch_directly(mb, bf16, W, holes):
     ds, dg, db = mb.mb_add_layernorm_bwd(dyd, s, gd, mean, rstd)
     ds2, dg2, db2 = mb.mb_add_layernorm_bwd(dy_padded, s, gd, mean, rstd, dy_rows=indices)
     assert torch.equal(ds2, ds) and torch.equal(dg2, dg) and torch.equal(db2, db)
+    # ... and the fused calls agree with the oracle on this very case
+    idx = np.flatnonzero(mask.reshape(-1))
+    y_ref, s_ref, mean_ref, rstd_ref = orc.add_layernorm_fwd(x, r, gamma, beta, EPS, round_sum=bf16)
+    ds_ref, dg_ref, db_ref = orc.add_layernorm_bwd(dy, s_ref, gamma, EPS)
+    y_got = y2.double().cpu().numpy()
+    tol_abs, tol_rel = (2e-2, 1e-2) if bf16 else (1e-4, 1e-5)
+    ma, rf = err_stats(y_got[idx], y_ref)
+    assert ma <= tol_abs and rf <= tol_rel, "y (scattered) max_abs=%.3e rel_fro=%.3e" % (ma, rf)
+    pad_rows = np.setdiff1d(np.arange(B * L), idx)
+    assert not y2.view(torch.int16 if bf16 else torch.int32).cpu().numpy()[pad_rows].any()
+    ma, rf = err_stats(ds2.double().cpu().numpy(), ds_ref)
+    assert ma <= tol_abs and rf <= tol_rel, "ds (gathered dy) max_abs=%.3e rel_fro=%.3e" % (ma, rf)
+    for name, g_, ref in (("dgamma", dg2, dg_ref), ("dbeta", db2, db_ref)):
+        _, rf = err_stats(g_.double().cpu().numpy(), ref)
+        assert rf <= (1e-4 if bf16 else 1e-5), "%s rel_fro=%.3e" % (name, rf)

@@ -122,6 +122,15 @@ def test_unpad_pad_rows_bit_exact(mb, dtype, seed, B, L, W, p):
         assert torch.equal(packed2, packed[:T])
 
 
+# ------------------------------------------------------------------ slopes
+@pytest.mark.parametrize("H", [1, 2, 8, 12, 16, 24])
+def test_slopes_equal_the_oracles_rounded_to_float(mb, H):
+    """"Attention with Linear Biases" paragraph: geometric slopes with ratio 2^(-8/H).  The product's values
+    are the oracle's doubles rounded to float, for power-of-two and other head counts alike; every parity
+    test below hands the oracle ITS OWN slopes and the kernels the product's."""
+    assert np.array_equal(mb.mb_alibi_slopes(H).numpy(), orc.alibi_slopes(H).astype(np.float32))
+
+
 # ------------------------------------------------------------------ attention, fp32 generic path
 def test_tiny_fp32_full_path(mb):
     b = wl.make_batch("tiny")
@@ -129,7 +138,7 @@ def test_tiny_fp32_full_path(mb):
     assert np.array_equal(slopes.numpy(), orc.alibi_slopes(2).astype(np.float32))
     got = run_hip_path(mb, b, slopes, bf16=False)
     check_index_maps(got, b["mask"])
-    ref = run_oracle(b, slopes.double().numpy())
+    ref = run_oracle(b, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, b["mask"], F32_TOL, 1e-4, "tiny fp32")
 
 
@@ -139,7 +148,7 @@ def test_generic_fp32_shapes(mb, D, H, lengths, L):
     slopes = mb.mb_alibi_slopes(H)
     got = run_hip_path(mb, c, slopes, bf16=False)
     check_index_maps(got, c["mask"])
-    ref = run_oracle(c, slopes.double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, c["mask"], F32_TOL, 1e-4, "generic fp32 D=%d" % D)
 
 
@@ -148,7 +157,7 @@ def test_fp32_scale_one_matches_eq1_literally(mb):
     c = wl.random_attention_case(22, [9, 31], 31, 2, 16, std=0.5)
     slopes = mb.mb_alibi_slopes(2)
     got = run_hip_path(mb, c, slopes, bf16=False, scale=1.0)
-    ref = run_oracle(c, slopes.double().numpy(), scale=1.0)
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)), scale=1.0)
     compare_attention(got, ref, c["mask"], F32_TOL, 1e-4, "fp32 scale=1")
 
 
@@ -168,7 +177,7 @@ def test_bf16_attention_cases(mb, name, lengths, L, H, std, v_std):
     slopes = mb.mb_alibi_slopes(H)
     got = run_hip_path(mb, c, slopes, bf16=True)
     check_index_maps(got, c["mask"])
-    ref = run_oracle(c, slopes.double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 " + name, abs_floor_ulps=(name == "large-logits"))
 
 
@@ -189,7 +198,7 @@ def test_bf16_full_size_workloads(mb, name):
     slopes = mb.mb_alibi_slopes(H)
     got = run_hip_path(mb, b, slopes, bf16=True)
     check_index_maps(got, b["mask"])
-    ref = run_oracle(b, slopes.double().numpy())
+    ref = run_oracle(b, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, b["mask"], BF16_TOL, 1e-3, name)
 
 
@@ -205,7 +214,7 @@ def test_bf16_long_workloads_sampled(mb, name, nseq):
     check_index_maps(got, b["mask"])
     order = np.argsort(b["lengths"])
     pick = sorted(set([int(order[0]), int(order[-1])] + [int(x) for x in np.random.default_rng(5).choice(len(order), nseq, replace=False)]))
-    ref = run_oracle(b, slopes.double().numpy(), seq_ids=pick)
+    ref = run_oracle(b, orc.alibi_slopes(H), seq_ids=pick)
     for key in ("o", "dq", "dk", "dv"):
         assert np.all(got[key][b["mask"] == 0] == 0) and np.all(np.isfinite(got[key]))
     for s in pick:
@@ -322,6 +331,31 @@ def test_token_rows_mode_equals_explicit_unpad_and_pad(mb, bf16, D, L, holes):
     assert np.array_equal(got[:, :, 0], ref["dq"]) and np.array_equal(got[:, :, 1], ref["dk"])
     assert np.array_equal(got[:, :, 2], ref["dv"])
     assert np.array_equal(lse[:, :T].double().cpu().numpy(), ref["lse"]) and torch.all(lse[:, T:] == garbage)
+    # ... and the padded-layout results agree with the oracle.  The kept tokens of a batch row form its
+    # sequence and positions are those inside that sequence, so for a mask with holes the oracle is given the
+    # kept tokens moved to the front of their row (a plain numpy gather), which is a suffix-padded batch.
+    mask = c["mask"]
+    lens = mask.astype(bool).sum(1)
+    cc = {key: np.zeros_like(c[key]) for key in ("q", "k", "v", "do")}
+    for b in range(B):
+        keep = np.flatnonzero(mask[b])
+        for key in cc:
+            cc[key][b, :len(keep)] = c[key][b, keep]
+    cc.update(mask=wl.suffix_mask(lens, L), scale=c["scale"], lengths=lens)
+    oref = run_oracle(cc, orc.alibi_slopes(H))
+    tol = BF16_TOL if bf16 else F32_TOL
+    fused = {"o": o_p.double().cpu().numpy().reshape(B, L, H, D), "dq": got[:, :, 0], "dk": got[:, :, 1],
+             "dv": got[:, :, 2]}
+    for key, arr in fused.items():
+        for b in range(B):
+            keep = np.flatnonzero(mask[b])
+            if len(keep) == 0:
+                continue
+            ma, rf = err_stats(arr[b, keep], oref[key][b, :len(keep)])
+            # (a one-token sequence has dQ = dK = 0 up to fp64 round-off: no relative error to speak of)
+            assert ma <= tol[0] and (rf <= tol[1] or ma <= 1e-7), \
+                "token_rows vs oracle %s row %d: %.3e %.3e" % (key, b, ma, rf)
+        assert np.all(arr[mask == 0] == 0)
 
 
 @pytest.mark.parametrize("scale", [-0.2, 0.0])
@@ -330,7 +364,7 @@ def test_bf16_nonpositive_scale_takes_the_generic_kernels(mb, scale):
     c = wl.random_attention_case(61, [70, 128, 5], 128, 2, 64, std=0.5, bf16=True)
     slopes = mb.mb_alibi_slopes(2)
     got = run_hip_path(mb, c, slopes, bf16=True, scale=scale)
-    ref = run_oracle(c, slopes.double().numpy(), scale=scale)
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)), scale=scale)
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 scale=%g" % scale)
 
 
@@ -355,9 +389,57 @@ def test_all_sequences_empty_and_single_token_batches(mb):
     assert torch.all(padded == 0)
     c = wl.random_attention_case(62, [1], 1, 1, 64, bf16=True)
     got = run_hip_path(mb, c, mb.mb_alibi_slopes(1), bf16=True)
-    ref = run_oracle(c, mb.mb_alibi_slopes(1).double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(1))
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "single token")
     assert np.array_equal(got["o"][0, 0], c["v"][0, 0].astype(np.float64))      # O = V for a length-1 sequence
+
+
+@pytest.mark.parametrize("bf16,D,lengths,promised", [(True, 64, [100, 140, 64], 128),     # single-tile kernels
+                                                     (True, 64, [100, 300, 600], 384),   # any-length kernels
+                                                     (False, 16, [20, 50, 7], 32)])       # generic kernels
+def test_sequence_longer_than_max_seqlen_is_skipped_and_reported(mb, bf16, D, lengths, promised):
+    """An understated max_seqlen must not truncate silently: the sequences that fit are computed as usual, a
+    longer one is skipped (its rows of o and of the gradients untouched, its rows of lse NaN) and
+    mb_device_status reports MB_ERR_INVALID_ARG once, then MB_OK again."""
+    H = 2
+    L = max(lengths)
+    c = wl.random_attention_case(91, lengths, L, H, D, std=0.5, bf16=bf16)
+    B = len(lengths)
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(c["mask"]).cuda())
+    T, mx = mb.mb_read_meta(meta)
+    qkv = mb.mb_unpad(to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(B * L, 3 * H * D), bf16), indices,
+                      B * L, meta)[:T].view(T, 3, H, D)
+    dout = mb.mb_unpad(to_dev(c["do"].reshape(B * L, H * D), bf16), indices, B * L, meta)[:T].view(T, H, D)
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    mb.mb_device_status()                                     # clean before
+    o_ok, lse_ok = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, mx, slopes, c["scale"])
+    g_ok = torch.empty((T, 3, H, D), dtype=tdt, device="cuda")
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o_ok, lse_ok, cu, mx, slopes, c["scale"],
+                         dq=g_ok[:, 0], dk=g_ok[:, 1], dv=g_ok[:, 2])
+    mb.mb_device_status()                                     # a correct bound raises nothing
+    guard = 9.0
+    o = torch.full((T, H, D), guard, dtype=tdt, device="cuda")
+    lse = torch.full((H, T), guard, dtype=torch.float32, device="cuda")
+    mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, promised, slopes, c["scale"], out=o, lse=lse)
+    with pytest.raises(mb.MosaicAttnError) as e:
+        mb.mb_device_status()
+    assert e.value.status == mb.MB_ERR_INVALID_ARG and "max_seqlen" in str(e.value)
+    mb.mb_device_status()                                     # reading it cleared it
+    g = torch.full((T, 3, H, D), guard, dtype=tdt, device="cuda")
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o_ok, lse_ok, cu, promised, slopes, c["scale"],
+                         dq=g[:, 0], dk=g[:, 1], dv=g[:, 2])
+    with pytest.raises(mb.MosaicAttnError):
+        mb.mb_device_status()
+    cu_h = cu.tolist()
+    for b, n in enumerate(lengths):
+        sl = slice(cu_h[b], cu_h[b + 1])
+        if n <= promised:     # computed as with the right bound (possibly by the other kernel family: tolerance)
+            assert torch.allclose(o[sl].float(), o_ok[sl].float(), atol=2e-2, rtol=0)
+            assert torch.allclose(lse[:, sl], lse_ok[:, sl], atol=1e-3, rtol=0)
+            assert torch.allclose(g[sl].float(), g_ok[sl].float(), atol=2e-2, rtol=0)
+        else:                 # skipped, visibly
+            assert torch.all(o[sl] == guard) and torch.all(torch.isnan(lse[:, sl])) and torch.all(g[sl] == guard)
 
 
 def test_bf16_tile_boundary_lengths(mb):
@@ -367,7 +449,7 @@ def test_bf16_tile_boundary_lengths(mb):
     slopes = mb.mb_alibi_slopes(2)
     got = run_hip_path(mb, c, slopes, bf16=True)
     check_index_maps(got, c["mask"])
-    ref = run_oracle(c, slopes.double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 tile boundaries")
 
 
@@ -383,7 +465,7 @@ def test_bf16_many_sequences_through_the_any_length_kernels(mb, B):
     slopes = mb.mb_alibi_slopes(1)
     got = run_hip_path(mb, c, slopes, bf16=True)
     check_index_maps(got, c["mask"])
-    ref = run_oracle(c, slopes.double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 %d sequences" % B)
 
 
@@ -401,7 +483,7 @@ def test_bf16_random_shapes(mb, seed):
     slopes = mb.mb_alibi_slopes(H)
     got = run_hip_path(mb, c, slopes, bf16=True)
     check_index_maps(got, c["mask"])
-    ref = run_oracle(c, slopes.double().numpy())
+    ref = run_oracle(c, orc.alibi_slopes(len(slopes)))
     compare_attention(got, ref, c["mask"], BF16_TOL, 1e-3, "bf16 random %d" % seed)
 
 
@@ -430,7 +512,7 @@ def test_bf16_buffers_beyond_four_gigabytes(mb, n, B):
     mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, n, slopes, 0.125,
                          dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2])
     torch.cuda.synchronize()
-    s64 = slopes.double().cpu().numpy()
+    s64 = orc.alibi_slopes(H)
     ones = np.ones((1, n), dtype=np.int32)
     for b in (0, B // 2, B - 1):
         sl = slice(b * n, (b + 1) * n)
@@ -495,6 +577,8 @@ def test_whole_path_replays_from_a_hip_graph(mb, L):
     g_pad = torch.empty((cap, 3 * H * D), dtype=bf, device="cuda")
     lse = torch.empty((H, cap), dtype=torch.float32, device="cuda")
     ws = torch.empty(mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(max(16, mb.mb_alibi_attn_fwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16)), dtype=torch.uint8,
+                       device="cuda")
     seqlens = torch.empty(B, dtype=torch.int32, device="cuda")
     cu = torch.empty(B + 1, dtype=torch.int32, device="cuda")
     indices = torch.empty(cap, dtype=torch.int32, device="cuda")
@@ -506,7 +590,7 @@ def test_whole_path_replays_from_a_hip_graph(mb, L):
                                   meta.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
         mb.mb_unpad(qkv_p, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
         mb.mb_unpad(do_p, indices, cap, meta, out=dout.view(cap, H * D))
-        mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, c["scale"], out=o, lse=lse)
+        mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, c["scale"], out=o, lse=lse, workspace=ws_f)
         mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, L, slopes, c["scale"],
                              dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_pad)
