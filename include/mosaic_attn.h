@@ -18,7 +18,7 @@
  *   Pointers   "dev" = device (HBM) pointer, "host" = host pointer.  The caller allocates and owns
  *              every buffer; the library allocates nothing and never frees.  Device pointers must be
  *              16-byte aligned.  The only state kept between calls lives on the device: one sticky
- *              misuse word (see mb_device_status).
+ *              misuse word (see mb_device_status) and the fixed scratch array of mb_alibi_attn_bwd_static.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  All device
  *              work is enqueued on it; no call synchronises with the host except mb_read_meta and
  *              mb_device_status.  Calls
@@ -196,6 +196,27 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
                             size_t workspace_bytes, const int32_t* token_rows, void* stream);
+
+/*
+ * The backward attention for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, arguments, results
+ * (bit for bit) and errors as mb_alibi_attn_bwd, minus `workspace` / `workspace_bytes`: the scratch lives in a
+ * fixed array of MB_STATIC_SCRATCH_BYTES bytes inside the library's device image, one copy per GPU, held until
+ * the process ends.  The call allocates and frees nothing.
+ *   Limit    sizes whose mb_alibi_attn_bwd_workspace_bytes exceeds MB_STATIC_SCRATCH_BYTES are rejected with
+ *            MB_ERR_WORKSPACE before anything is launched (about H * T <= 4 million (head, token-row) pairs).
+ *   Sharing  every call on a GPU uses that GPU's one array, which keeps the previous call's contents; nothing
+ *            in it needs clearing (each word is written before it is read within a call).  Two such calls that
+ *            overlap in time on one GPU (different streams or threads) race on it: serialise them.
+ */
+#define MB_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+MB_API mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* k, const void* v,
+                            const void* o, const float* lse, int64_t do_row_stride,
+                            int64_t q_row_stride, int64_t k_row_stride, int64_t v_row_stride,
+                            int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
+                            int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
+                            mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
+                            int64_t dk_row_stride, int64_t dv_row_stride, const int32_t* token_rows, void* stream);
 
 /*
  * Reads and clears the current device's sticky misuse word.  Synchronises `stream`.

@@ -26,7 +26,7 @@ EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "
            "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
            "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling",
-           "mb_device_status")
+           "mb_alibi_attn_bwd_static", "mb_device_status")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -55,8 +55,13 @@ _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
                                    + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p])
+_lib.mb_alibi_attn_bwd_static.restype = c_int
+_lib.mb_alibi_attn_bwd_static.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5
+                                          + [c_void_p, c_float, c_int] + [c_void_p] * 3 + [c_int64] * 3
+                                          + [c_void_p, c_void_p])
 _lib.mb_device_status.restype = c_int
 _lib.mb_device_status.argtypes = [c_void_p]
+MB_STATIC_SCRATCH_BYTES = 16 << 20
 
 _lib.mb_add_layernorm_fwd.restype = c_int
 _lib.mb_add_layernorm_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_float, c_int,
@@ -232,6 +237,21 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale), _dtype_code(q),
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
                                   _ptr(workspace), workspace.numel(), _ptr(token_rows), _stream()))
+    return dq, dk, dv
+
+
+def mb_alibi_attn_bwd_static(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
+                             dq, dk, dv, token_rows=None, T=None):
+    """mb_alibi_attn_bwd on the library's static scratch array.  This wrapper allocates nothing either:
+    the outputs dq, dk, dv must be given."""
+    R, H, D = q.shape
+    T = R if T is None else T
+    B = cu_seqlens.numel() - 1
+    _check(_lib.mb_alibi_attn_bwd_static(_ptr(dout), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _row_stride(dout),
+                                         _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o),
+                                         _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
+                                         _dtype_code(q), _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq),
+                                         _row_stride(dk), _row_stride(dv), _ptr(token_rows), _stream()))
     return dq, dk, dv
 
 

@@ -8,10 +8,13 @@
 #include "common.h"
 
 // Device-resident state of the library (one copy per GPU, held until the process ends):
-//   g_misuse   sticky word set by an attention kernel that met a sequence longer than max_seqlen.
+//   g_misuse   sticky word set by an attention kernel that met a sequence longer than max_seqlen;
+//   scratch    the workspace of mb_alibi_attn_bwd_static, for callers that cannot allocate.
 // Host code never passes these names to a kernel (on the host they are stand-ins, not device addresses): it
 // asks the runtime for their device addresses once per device and uses those.
 __device__ int32_t g_misuse = 0;
+static constexpr size_t kStaticScratchBytes = MB_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace mb {
 namespace {
@@ -19,6 +22,7 @@ thread_local char g_error[512] = "";
 
 constexpr int kMaxDevices = 64;
 std::atomic<int32_t*> g_misuse_ptr[kMaxDevices];
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];
 }
 
 mb_status fail(mb_status code, const char* fmt, ...) {
@@ -48,6 +52,21 @@ mb_status misuse_flag_address(int32_t** flag) {
     g_misuse_ptr[dev].store(p, std::memory_order_release);
   }
   *flag = p;
+  return MB_OK;
+}
+
+// Device address of this GPU's copy of the static scratch array.
+static mb_status static_scratch_address(unsigned char** ptr) {
+  int dev = 0;
+  const mb_status st = current_device(&dev);
+  if (st != MB_OK) return st;
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) return fail(MB_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
   return MB_OK;
 }
 
@@ -340,7 +359,8 @@ size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, int H, in
   return attn_bwd_mfma_workspace_bytes(B, T, max_seqlen, H);          // Delta, then the work plan
 }
 
-// The backward after its workspace checks.
+// Shared by mb_alibi_attn_bwd (caller's workspace) and mb_alibi_attn_bwd_static (the library's static array):
+// everything but the workspace checks.
 static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k, const void* v, const void* o,
                                   const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
                                   int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
@@ -363,7 +383,7 @@ static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k
                                  dv_row_stride, (float*)workspace, (hipStream_t)stream);
 }
 
-// Host-side validation of the backward; *empty is set when there is nothing to do.
+// Host-side validation common to both backward entry points; *empty is set when there is nothing to do.
 static mb_status attn_bwd_validate(const void* dout, const void* q, const void* k, const void* v, const void* o,
                                    const float* lse, int64_t do_row_stride, int64_t q_row_stride, int64_t k_row_stride,
                                    int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
@@ -423,6 +443,33 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
   return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
                           cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
                           dk_row_stride, dv_row_stride, workspace, token_rows, stream);
+}
+
+mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* k, const void* v, const void* o,
+                                   const float* lse, int64_t do_row_stride, int64_t q_row_stride,
+                                   int64_t k_row_stride, int64_t v_row_stride, int64_t o_row_stride,
+                                   const int32_t* cu_seqlens, int B, int T, int max_seqlen, int H, int D,
+                                   const float* slopes, float softmax_scale, mb_dtype dt, void* dq, void* dk, void* dv,
+                                   int64_t dq_row_stride, int64_t dk_row_stride, int64_t dv_row_stride,
+                                   const int32_t* token_rows, void* stream) {
+  clear_error();
+  bool empty = false;
+  mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
+                                   o_row_stride, cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk,
+                                   dv, dq_row_stride, dk_row_stride, dv_row_stride, token_rows, &empty);
+  if (st != MB_OK || empty) return st;
+  const size_t need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
+  MB_REQUIRE(need <= kStaticScratchBytes, MB_ERR_WORKSPACE,
+             "these sizes need %zu bytes of scratch, the static array holds %zu: use mb_alibi_attn_bwd with a "
+             "workspace of the caller's", need, kStaticScratchBytes);
+  unsigned char* ws = nullptr;   // this GPU's copy of the array (never the array's name)
+  st = static_scratch_address(&ws);
+  if (st != MB_OK) return st;
+  // Nothing in the array has to start at zero: every word a kernel of this call reads (Delta of the real
+  // tokens, the sequence order) is written earlier in the same call.
+  return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
+                          cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
+                          dk_row_stride, dv_row_stride, ws, token_rows, stream);
 }
 
 mb_status mb_device_status(void* stream) {

@@ -103,6 +103,25 @@ def test_bwd_rejects_bad_arguments_without_launching(over, status, needle):
     assert needle in mb.mb_last_error()
 
 
+def static_bwd_args(**over):
+    a = bwd_args(**over)
+    return a[:26] + a[28:]          # the same list without workspace and workspace_bytes
+
+
+@pytest.mark.parametrize("over,status,needle", [
+    (dict(do=None), mb.MB_ERR_INVALID_ARG, "dout is NULL"),
+    (dict(dks=8), mb.MB_ERR_INVALID_ARG, "smaller than H*D"),
+    (dict(rows=A + 4), mb.MB_ERR_INVALID_ARG, "token_rows"),
+    # 16 heads x 300000 token rows of Delta = 19.2 MB: more than the static array holds
+    (dict(T=300000, H=16, qs=1024, ks=1024, vs=1024, os=1024, dos=1024, dqs=1024, dks=1024, dvs=1024, max_seqlen=512),
+     mb.MB_ERR_WORKSPACE, "static array holds"),
+])
+def test_static_bwd_rejects_bad_arguments_and_sizes_beyond_its_array_without_launching(over, status, needle):
+    assert lib.mb_alibi_attn_bwd_static(*static_bwd_args(**over)) == status
+    assert needle in mb.mb_last_error()
+    assert lib.mb_alibi_attn_bwd_static(*static_bwd_args(B=0, T=0, do=None)) == mb.MB_OK
+
+
 def test_degenerate_sizes_are_ok_and_touch_nothing():
     # T == 0 / B == 0: MB_OK before any pointer is looked at or anything is launched
     assert lib.mb_alibi_attn_fwd(*fwd_args(T=0, q=None, k=None, v=None, o=None, lse=None)) == mb.MB_OK
