@@ -6,6 +6,11 @@ One "step" is one pass of the whole path over one synthetic batch that is alread
   mb_pad(O), mb_pad(dQKV)    (no host synchronisation inside a step).
 Prints ONE JSON line.  `value` = attention flops on real tokens (14*H*D*sum(len^2): forward QK^T and PV,
 backward's five products including the recomputation of the scores) divided by the whole step time.
+
+Beside the headline (bert_base) the line carries, per call of the path, median / p10 / p90 times and the achieved
+HBM rate of the gathers and scatters (`calls`), and the attention forward / backward of the other workloads
+(`configs`: bert_large, long512, ragged2048 with five draws), each warm (same buffers) and cold (buffer sets in
+rotation), as TFLOP/s, % of the matrix-core peak and fraction of the roof that binds.
 """
 import argparse
 import json
@@ -18,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (2.5 PFLOP/s)
 PEAK_HBM_GBS = 8000.0
+MEASURED_COPY_GBS = 6000.0    # what a plain row copy of 1 GiB each way reaches on these boxes (bench.py --ceilings)
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # file (KiB per dispatch), each scaled by what the same counter reads for a plain row copy of known size
@@ -28,6 +34,8 @@ COPY_FACTOR_WRITE = 1.0
 MEASURED_TRAFFIC_KIB = {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE) KiB per dispatch
     "bert_base": {"attn_bwd_fused128_kernel": (102001.1, 121333.5), "attn_fwd_short_kernel": (60747.7, 41788.3)},
 }
+TRAFFIC_SOURCE = ("profiles/bert_base_attn_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                  "not measured in the run that prints this line")
 
 
 def measured_traffic_bytes(workload, kernel):
@@ -62,11 +70,20 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps, run a plain row copy of known size (128 MiB in, 128 MiB out, 5 launches of "
                          "gather_rows_kernel with 65536 rows) so that HBM counters of a profiler run can be scaled")
+    ap.add_argument("--no-configs", action="store_true", help="skip the other workloads (bert_large, long512, ragged2048)")
+    ap.add_argument("--cpu-baseline-child", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.cpu_baseline_child:      # the oracle leg, in a process of its own that never touches the GPU
+        print(json.dumps(cpu_baseline_child(args.workload, args.batch)))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no communication; every box has "
               "one GPU). --gpus %d is not supported." % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    # The oracle is timed first, in a child process started before this one initialises the GPU: it gets the
+    # host cores to itself (BLAS threads set before numpy is imported there) and cannot disturb the GPU timing.
+    cpu_line = None if args.no_cpu_baseline else run_cpu_baseline(args)
 
     import numpy as np
     import torch
@@ -105,6 +122,8 @@ def main():
     dqkv_padded = torch.empty((cap, 3 * H * D), dtype=tdt, device=dev)
     ws_bytes = mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16 if bf16 else mb.MB_F32)
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    ws_fwd = torch.empty(max(mb.mb_alibi_attn_fwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16 if bf16 else mb.MB_F32), 16),
+                         dtype=torch.uint8, device=dev)
     lse_buf = torch.empty(H * cap, dtype=torch.float32, device=dev)
     seqlens = torch.empty(B, dtype=torch.int32, device=dev)
     cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
@@ -118,43 +137,72 @@ def main():
     lse = lse_buf.view(H, cap)
 
     def step(record=None):
+        def mark(i):
+            if record is not None:
+                record[i].record(stream)
+        mark(0)
         st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
                                 meta.data_ptr(), sp)
         assert st == 0, mb.mb_last_error()
+        mark(1)
         # No host round trip: the token count stays on the device (meta); the attention calls get the
         # capacity B*L as their row count and L as the bound of the sequence length.
         # (the upstream gradient is unpadded right before the backward needs it, so that the packed Q/K/V
         # just written are still in cache when the forward reads them)
         mb.mb_unpad(qkv_padded, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
-        if record is not None:
-            record[0].record(stream)
-        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse)
-        if record is not None:
-            record[1].record(stream)
+        mark(2)
+        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse, workspace=ws_fwd)
+        mark(3)
         mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
-        if record is not None:
-            record[2].record(stream)
+        mark(4)
         mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
                              dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace)
-        if record is not None:
-            record[3].record(stream)
+        mark(5)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
+        mark(6)
         mb.mb_pad(dqkv.view(cap, 3 * H * D), indices, cap, meta, B, L, out=dqkv_padded)
+        mark(7)
 
+    # `value`: exactly `steps` passes between two host synchronisations, nothing else on the stream
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     T, max_seqlen = mb.mb_read_meta(meta)
     assert T == T_host and max_seqlen == int(lengths.max())
+    mb.mb_device_status()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    fwd_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    bwd_ms = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    # per call: the same passes again with an event on the launch stream before and after every call
+    # (the events cost a little, so these passes do not count towards `value`); median, p10, p90 over the steps
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    call_names = ("unpad_index", "unpad_qkv", "attn_fwd", "unpad_do", "attn_bwd", "pad_o", "pad_dqkv")
+    call_us = {name: np.array([e[i].elapsed_time(e[i + 1]) * 1e3 for e in events]) for i, name in enumerate(call_names)}
+
+    def stats(t):
+        return {"median": round(float(np.median(t)), 2), "p10": round(float(np.percentile(t, 10)), 2),
+                "p90": round(float(np.percentile(t, 90)), 2)}
+    fwd_ms = float(np.median(call_us["attn_fwd"])) * 1e-3
+    bwd_ms = float(np.median(call_us["attn_bwd"])) * 1e-3
+    esize = 2 if bf16 else 4
+    W1, W3 = H * D * esize, 3 * H * D * esize
+    call_bytes = {"unpad_qkv": 2 * T_host * W3, "unpad_do": 2 * T_host * W1, "pad_o": (T_host + cap) * W1,
+                  "pad_dqkv": (T_host + cap) * W3}
+    calls = {}
+    for name in call_names:
+        calls[name] = dict(stats(call_us[name]), unit="us")
+        if name in call_bytes:
+            gbs = call_bytes[name] / (float(np.median(call_us[name])) * 1e-6) * 1e-9
+            calls[name].update(algorithmic_bytes=call_bytes[name], GBs=round(gbs, 1),
+                               frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+    calls["note"] = ("inside the step (cold: a step touches 1.2 GB between two uses of a buffer); gather bytes = 2*T*W*e, "
+                     "scatter bytes = (T + B*L)*W*e")
 
     # The same path with the gather and the scatter done inside the attention kernels' own row loads and
     # stores (token_rows = indices): no packed copies at all; padding rows of the outputs are zeroed.
@@ -167,7 +215,8 @@ def main():
         st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
                                 meta.data_ptr(), sp)
         assert st == 0, mb.mb_last_error()
-        mb.mb_alibi_attn_fwd(qp_, kp_, vp_, cu, L, slopes, scale, out=op_, lse=lse, token_rows=indices, T=cap)
+        mb.mb_alibi_attn_fwd(qp_, kp_, vp_, cu, L, slopes, scale, out=op_, lse=lse, token_rows=indices, T=cap,
+                             workspace=ws_fwd)
         mb.mb_zero_padding(o_padded, indices, cap, meta, B, L)
         mb.mb_alibi_attn_bwd(dop_, qp_, kp_, vp_, op_, lse, cu, L, slopes, scale, dq=dqkvp_[:, 0], dk=dqkvp_[:, 1],
                              dv=dqkvp_[:, 2], workspace=workspace, token_rows=indices, T=cap)
@@ -185,7 +234,6 @@ def main():
     ms_fused = (time.perf_counter() - t0) * 1e3 / args.steps
 
     value = (f_fwd + f_bwd) / (ms_per_step * 1e-3) * 1e-12
-    esize = 2 if bf16 else 4
     # algorithmic HBM bytes of one backward launch: dO, Q, K, V, O read and dQ, dK, dV written once each
     # ([T,H,D] elements) plus the row log-sum-exp read ([H,T] float)
     bwd_bytes = 8 * T_host * H * D * esize + 4 * H * T_host
@@ -198,6 +246,9 @@ def main():
         "achieved": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
         "frac": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, 5),
         "algorithmic_bytes": bwd_bytes, "traffic": measured_traffic_bytes(w.name, bwd_kernel),
+        "traffic_source": TRAFFIC_SOURCE if measured_traffic_bytes(w.name, bwd_kernel) is not None else None,
+        "launch_us": stats(call_us["attn_bwd"]),
+        "frac_of_measured_copy_rate": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / MEASURED_COPY_GBS, 4),
     }
     roof_mfma = {
         "kernel": bwd_kernel, "bound": "mfma",
@@ -219,6 +270,7 @@ def main():
         "tokens_per_s": round(T_host / (ms_per_step * 1e-3), 1),
         "pct_of_bf16_mfma_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 3),
         "attention_only": {
+            "timing": "median over the steps of the event-bracketed calls inside the step (cold)",
             "fwd_ms": round(fwd_ms, 5), "bwd_ms": round(bwd_ms, 5),
             "fwd_tflops": round(f_fwd / (fwd_ms * 1e-3) * 1e-12, 2),
             "bwd_tflops": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2),
@@ -230,6 +282,7 @@ def main():
         # workload's arithmetic intensity (flops per algorithmic byte against the machine balance of
         # 2500 TFLOP/s : 8 TB/s = 312 flop/byte); `roofline_other` gives the other roof.
         "roofline": roof_primary, "roofline_other": roof_other,
+        "calls": calls,
         "gather_scatter_fused_into_attention": {
             "ms_per_step": round(ms_fused, 5), "value": round((f_fwd + f_bwd) / (ms_fused * 1e-3) * 1e-12, 3),
             "unit": "TFLOP/s", "tokens_per_s": round(T_host / (ms_fused * 1e-3), 1),
@@ -261,8 +314,11 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration"] = "5 x gather_rows_kernel grid=%d: reads 131072 KiB, writes 131072 KiB per launch" % (rows // 8)
 
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(batch, f_fwd + f_bwd)
+    if not args.no_configs and w.name == "bert_base" and args.batch is None and not args.full_length:
+        out["configs"] = {name: time_config(mb, wl, name, dev, seeds=5 if name == "ragged2048" else 1)
+                          for name in ("bert_large", "long512", "ragged2048")}
+    if cpu_line is not None:
+        out["cpu_baseline"] = cpu_line
     print(json.dumps(out))
 
 
@@ -388,8 +444,11 @@ def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
             ws = torch.empty(max(mb.mb_alibi_attn_bwd_workspace_bytes(B, n_tok, L, H, D, mb.MB_BF16), 16), dtype=torch.uint8,
                              device=dev)
 
+            ws_f = torch.empty(max(mb.mb_alibi_attn_fwd_workspace_bytes(B, n_tok, L, H, D, mb.MB_BF16), 16), dtype=torch.uint8,
+                               device=dev)
+
             def run():
-                mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, 0.125, out=o, lse=lse)
+                mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, 0.125, out=o, lse=lse, workspace=ws_f)
                 mb.mb_alibi_attn_bwd(do, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, L, slopes, 0.125, dq=dqkv[:, 0],
                                      dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
             for _ in range(3):
@@ -405,6 +464,87 @@ def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
         res["speedup_from_unpadding"] = round(res["padded_fwd_bwd_us"] / res["varlen_fwd_bwd_us"], 3)
         rows.append(res)
     return rows
+
+
+def time_config(mb, wl, name, dev, seeds=1, launches=60):
+    """Attention forward and backward of another workload, called the way the step calls them (packed buffers of
+    capacity B*L, max_seqlen = L, nothing read back from the device).  Per draw of the workload's recipe:
+    `launches` launches each bracketed by its own pair of events on the launch stream, median / p10 / p90;
+    warm = the same buffers every launch, cold = four independent buffer sets in rotation (for the small
+    ragged batch what a launch reads may still sit in the 256 MB Infinity Cache either way: both are given).
+    TFLOP/s by the 4*H*D*sum(len^2) / 10*H*D*sum(len^2) conventions; `roof` = min(matrix-core peak, flops per
+    algorithmic byte x 8 TB/s) for forward + backward together."""
+    import numpy as np
+    import torch
+    draws = []
+    for s_off in range(seeds):
+        batch = wl.make_batch(name, seed_offset=s_off)
+        w = batch["workload"]
+        B, L, H, D = w.B, w.L, w.H, w.D
+        cap = B * L
+        bf = torch.bfloat16
+        lengths = batch["lengths"]
+        T = int(lengths.sum())
+        f_fwd, f_bwd = wl.attention_flops(lengths, H, D)
+        mask = torch.from_numpy(batch["mask"]).to(dev)
+        seqlens, cu, indices, meta = mb.mb_unpad_index(mask)
+        slopes = mb.mb_alibi_slopes(H).to(dev)
+        qkv_padded = torch.from_numpy(np.concatenate([batch[x].reshape(cap, H * D) for x in ("q", "k", "v")], axis=1)).to(bf).to(dev)
+        do_padded = torch.from_numpy(np.ascontiguousarray(batch["do"].reshape(cap, H * D))).to(bf).to(dev)
+        sets = []
+        for _ in range(4):
+            qkv = mb.mb_unpad(qkv_padded, indices, cap, meta).view(cap, 3, H, D)
+            dout = mb.mb_unpad(do_padded, indices, cap, meta).view(cap, H, D)
+            sets.append((qkv, dout, torch.empty((cap, H, D), dtype=bf, device=dev), torch.empty_like(qkv)))
+        del qkv_padded, do_padded
+        lse = torch.empty((H, cap), dtype=torch.float32, device=dev)
+        ws_f = torch.empty(max(16, mb.mb_alibi_attn_fwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16)), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(max(16, mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16)), dtype=torch.uint8, device=dev)
+
+        def fwd(x, do_, o_, dx):
+            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu, L, slopes, batch["scale"], out=o_, lse=lse, workspace=ws_f)
+
+        def bwd(x, do_, o_, dx):
+            mb.mb_alibi_attn_bwd(do_, x[:, 0], x[:, 1], x[:, 2], o_, lse, cu, L, slopes, batch["scale"], dq=dx[:, 0],
+                                 dk=dx[:, 1], dv=dx[:, 2], workspace=ws_b)
+
+        def measure(fn, rotate):
+            for i in range(6):
+                fn(*sets[i % 4 if rotate else 0])
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(launches)]
+            for i, (a, b) in enumerate(evs):
+                a.record()
+                fn(*sets[i % 4 if rotate else 0])
+                b.record()
+            torch.cuda.synchronize()
+            t = np.array([a.elapsed_time(b) * 1e3 for a, b in evs])
+            return {"median": round(float(np.median(t)), 2), "p10": round(float(np.percentile(t, 10)), 2),
+                    "p90": round(float(np.percentile(t, 90)), 2)}
+        for st in sets:                      # every set holds its own forward results before any backward is timed
+            fwd(*st)
+        row = {"seed_offset": s_off, "T": T, "sum_len2": int((lengths.astype(np.int64) ** 2).sum()), "max_len": int(lengths.max())}
+        for temp, rotate in (("warm", False), ("cold", True)):
+            tf, tb = measure(fwd, rotate), measure(bwd, rotate)
+            row[temp] = {"fwd_us": tf, "bwd_us": tb,
+                         "fwd_tflops": round(f_fwd / tf["median"] * 1e-6, 1), "bwd_tflops": round(f_bwd / tb["median"] * 1e-6, 1),
+                         "fwd_bwd_tflops": round((f_fwd + f_bwd) / (tf["median"] + tb["median"]) * 1e-6, 1)}
+        mb.mb_device_status()
+        nbytes = 12 * T * H * D * 2 + 2 * T * H * 4
+        row["flop_per_byte"] = round((f_fwd + f_bwd) / nbytes, 1)
+        roof = min(PEAK_BF16_TFLOPS, (f_fwd + f_bwd) / nbytes * PEAK_HBM_GBS * 1e-3)
+        row["roof_tflops"] = round(roof, 1)
+        row["roof"] = "mfma" if roof >= PEAK_BF16_TFLOPS else "hbm"
+        for temp in ("warm", "cold"):
+            row[temp]["pct_of_bf16_mfma_peak"] = round(100.0 * row[temp]["fwd_bwd_tflops"] / PEAK_BF16_TFLOPS, 2)
+            row[temp]["frac_of_roof"] = round(row[temp]["fwd_bwd_tflops"] / roof, 4)
+        draws.append(row)
+        del sets
+    res = {"shape": "B=%d L=%d H=%d D=%d" % (B, L, H, D), "draws": draws}
+    if seeds > 1:
+        for temp in ("warm", "cold"):
+            res["mean_over_draws_" + temp] = {k: round(float(np.mean([d[temp][k] for d in draws])), 1)
+                                              for k in ("fwd_tflops", "bwd_tflops", "fwd_bwd_tflops", "pct_of_bf16_mfma_peak")}
+    return res
 
 
 def time_attention_over_seeds(mb, wl, args, dev):
@@ -433,7 +573,10 @@ def time_attention_over_seeds(mb, wl, args, dev):
         dq, dk, dv = (torch.empty_like(packed["q"]) for _ in range(3))
         ws = torch.empty(max(mb.mb_alibi_attn_bwd_workspace_bytes(B, T, L, H, D, mb.MB_BF16 if w.dtype == "bf16" else mb.MB_F32), 16),
                          dtype=torch.uint8, device=dev)
-        fwd = lambda: mb.mb_alibi_attn_fwd(packed["q"], packed["k"], packed["v"], cu, L, slopes, batch["scale"], out=o, lse=lse)
+        ws_f = torch.empty(max(mb.mb_alibi_attn_fwd_workspace_bytes(B, T, L, H, D, mb.MB_BF16 if w.dtype == "bf16" else mb.MB_F32), 16),
+                           dtype=torch.uint8, device=dev)
+        fwd = lambda: mb.mb_alibi_attn_fwd(packed["q"], packed["k"], packed["v"], cu, L, slopes, batch["scale"], out=o, lse=lse,
+                                           workspace=ws_f)
         bwd = lambda: mb.mb_alibi_attn_bwd(packed["do"], packed["q"], packed["k"], packed["v"], o, lse, cu, L, slopes,
                                            batch["scale"], dq=dq, dk=dk, dv=dv, workspace=ws)
         t_us = []
@@ -679,13 +822,40 @@ def time_each_call(mb, lib, env):
     return res
 
 
-def cpu_baseline(batch, flops):
-    """The CPU oracle, as it stands, on the same batch (the whole path: index maps, gather, attention
-    forward + backward, scatter), timed on this host: all sequences of the batch, 1 warm-up on a quarter of
-    it, then 3 repetitions, median."""
+def host_threads():
+    """Threads the oracle's BLAS may use: what the environment prescribes (the GPU machines export OMP_NUM_THREADS for
+    their CPU share), else every host core."""
+    try:
+        return max(1, int(os.environ.get("OMP_NUM_THREADS", "")))
+    except ValueError:
+        return os.cpu_count() or 1
+
+
+def run_cpu_baseline(args):
+    """Starts the oracle leg as a child process (this file with --cpu-baseline-child) and returns its JSON object."""
+    import subprocess
+    n = str(host_threads())
+    env = dict(os.environ, OMP_NUM_THREADS=n, OPENBLAS_NUM_THREADS=n, MKL_NUM_THREADS=n)
+    cmd = [sys.executable, os.path.abspath(__file__), "--cpu-baseline-child", "--workload", args.workload]
+    if args.batch is not None:
+        cmd += ["--batch", str(args.batch)]
+    out = subprocess.run(cmd, env=env, stdout=subprocess.PIPE, text=True, check=True).stdout
+    return json.loads(out.strip().splitlines()[-1])
+
+
+def cpu_baseline_child(workload, batch_override):
+    """The CPU oracle, as it stands, on the benchmark batch (the whole path: index maps, gather, attention
+    forward + backward, scatter), timed on this host with the BLAS thread count set by the parent before numpy
+    was imported: the first 256 sequences of the batch (all of bert_base), 1 warm-up on a quarter of them, then
+    3 repetitions, median.  `cores` = cpu time / wall time of the median run, i.e. the cores it really kept busy
+    (the oracle multiplies many small matrices, one (sequence, head) at a time, which BLAS does not spread)."""
     import numpy as np
     from oracle import mosaic_oracle as orc
+    from paper_2312_17482_amd import workloads as wl
+    batch = wl.make_batch(workload, batch=batch_override)
     w = batch["workload"]
+    f_fwd, f_bwd = wl.attention_flops(batch["lengths"], w.H, w.D)
+    flops = f_fwd + f_bwd
     sub = min(w.B, 256)            # bounded sample: the first `sub` sequences of the batch
     slopes = orc.alibi_slopes(w.H)
 
@@ -710,8 +880,10 @@ def cpu_baseline(batch, flops):
     frac = float((lengths ** 2).sum()) * 14.0 * w.H * w.D / flops
     cores = max(1, int(round(cpu / wall)))
     return {"value": round(flops * frac / wall * 1e-12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "first %d of %d sequences, whole path (fp64 numpy), median of 3 runs: %.1f s wall, %.1f s of cpu "
-                      "time each; host has %d cpus" % (sub, w.B, wall, cpu, os.cpu_count()),
+            "blas_threads_allowed": host_threads(), "host_cpus": os.cpu_count(),
+            "sample": "first %d of %d sequences of %s, whole path (fp64 numpy), median of 3 runs: %.1f s wall, %.1f s of "
+                      "cpu time each; BLAS allowed %d threads on a host of %d cpus" % (
+                          sub, w.B, w.name, wall, cpu, host_threads(), os.cpu_count()),
             "tokens_per_s": round(float(lengths.sum()) / wall, 1)}
 
 
