@@ -298,8 +298,8 @@ def main():
         out["next_rows"]["mlm_head_on_masked_rows"] = time_mlm_head(mb, T_host, H * D, dev)
     if args.detail:
         out["detail_us"] = time_each_call(mb, lib, locals())
-    if args.length_sweep:
-        out["length_sweep"] = time_length_sweep(mb, wl, dev)
+    if args.length_sweep or (not args.no_configs and w.name == "bert_base" and args.batch is None):
+        out["next_rows"]["length_sweep_padded_vs_varlen"] = time_length_sweep(mb, wl, dev)
     if args.seeds > 1:
         out["attention_over_seeds"] = time_attention_over_seeds(mb, wl, args, dev)
     if args.ceilings:
@@ -419,7 +419,8 @@ def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
     padded batch; its appendix on sequence length trains at 128 .. 2048).  For each max_len L: B = 32768 / L
     sequences, lengths by the bert_base recipe scaled to L (L with probability 0.6, else uniform in
     [L/8, L-1]; NumPy default_rng(20231217 + L)), Q, K, V ~ N(0,1)/8; forward + backward on the packed tokens
-    and on all B*L positions, 10 launches each between two events."""
+    (`varlen`) and on the padded batch with a key-padding mask (`padded`: all B*L positions are queries, key_lens =
+    the lengths), 10 launches each between two events."""
     import numpy as np
     import torch
     bf = torch.bfloat16
@@ -433,9 +434,10 @@ def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
         f_fwd, f_bwd = wl.attention_flops(lengths, H, D)
         slopes = mb.mb_alibi_slopes(H).to(dev)
         res = {"max_len": L, "B": B, "T": T, "fraction_real": round(T / positions, 4)}
-        for name, lens in (("varlen", lengths), ("padded", np.full(B, L, dtype=np.int32))):
+        for name, lens, klens in (("varlen", lengths, None), ("padded", np.full(B, L, dtype=np.int32), lengths)):
             n_tok = int(lens.sum())
             cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+            kl = None if klens is None else torch.from_numpy(klens).to(dev)
             qkv = (torch.randn(n_tok, 3, H, D, device=dev) * 0.125).to(bf)
             do = torch.randn(n_tok, H, D, device=dev).to(bf)
             o = torch.empty(n_tok, H, D, dtype=bf, device=dev)
@@ -443,14 +445,14 @@ def time_length_sweep(mb, wl, dev, H=12, D=64, positions=32768):
             dqkv = torch.empty_like(qkv)
             ws = torch.empty(max(mb.mb_alibi_attn_bwd_workspace_bytes(B, n_tok, L, H, D, mb.MB_BF16), 16), dtype=torch.uint8,
                              device=dev)
-
             ws_f = torch.empty(max(mb.mb_alibi_attn_fwd_workspace_bytes(B, n_tok, L, H, D, mb.MB_BF16), 16), dtype=torch.uint8,
                                device=dev)
 
             def run():
-                mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, 0.125, out=o, lse=lse, workspace=ws_f)
+                mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, L, slopes, 0.125, out=o, lse=lse, workspace=ws_f,
+                                     key_lens=kl)
                 mb.mb_alibi_attn_bwd(do, qkv[:, 0], qkv[:, 1], qkv[:, 2], o, lse, cu, L, slopes, 0.125, dq=dqkv[:, 0],
-                                     dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
+                                     dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws, key_lens=kl)
             for _ in range(3):
                 run()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -716,9 +718,10 @@ def time_geglu(mb, T, hidden, inter, dev):
 
 def time_padded_vs_varlen(mb, g):
     """What removing padding saves in attention itself: the same kernels on the same batch, once over the
-    packed real tokens (cu_seqlens from the mask) and once over every position of the padded [B, L] batch
-    as the paper's own code ran attention (all B*L positions computed).  Forward + backward, 30 launches
-    each between two events; outputs of the padded run are scratch."""
+    packed real tokens (cu_seqlens from the mask) and once over the padded [B, L] batch with a key-padding mask
+    as the paper's own code ran attention (every position a query, key_lens = the real lengths; parity of that
+    mode is a GPU test).  Forward + backward, 30 launches each between two events; outputs of the padded run are
+    scratch."""
     import torch
     B, L, H, D, cap = g["B"], g["L"], g["H"], g["D"], g["cap"]
     dev = g["dev"]
@@ -729,11 +732,13 @@ def time_padded_vs_varlen(mb, g):
     o, lse, dqkv, ws = g["o"], g["lse"], g["dqkv"], g["workspace"]
     slopes, scale = g["slopes"], g["scale"]
     res = {}
-    for name, x, do_, cu_ in (("varlen", qkv_packed, dout_packed, g["cu"]), ("padded", qkv_full, do_full, cu_full)):
+    for name, x, do_, cu_, kl in (("varlen", qkv_packed, dout_packed, g["cu"], None),
+                                  ("padded", qkv_full, do_full, cu_full, g["seqlens"])):
         def run():
-            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu_, L, slopes, scale, out=o, lse=lse)
+            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu_, L, slopes, scale, out=o, lse=lse, workspace=g["ws_fwd"],
+                                 key_lens=kl)
             mb.mb_alibi_attn_bwd(do_, x[:, 0], x[:, 1], x[:, 2], o, lse, cu_, L, slopes, scale,
-                                 dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws)
+                                 dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=ws, key_lens=kl)
         for _ in range(3):
             run()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

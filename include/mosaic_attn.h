@@ -148,6 +148,13 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *   workspace    dev, at least mb_alibi_attn_fwd_workspace_bytes(...) bytes, scratch (the work plan of the
  *                any-length kernels); may be NULL when that is 0 (max_seqlen <= 128, or a combination served by
  *                the generic kernels).
+ *   key_lens     dev, [B] int32, or NULL.  NULL: every token of a sequence is a key for every query of that
+ *                sequence (the packed computation).  Otherwise only the first min(key_lens[b], len_b) tokens of
+ *                sequence b act as keys; the others are masked out of every softmax (S_ij = -inf) while all len_b
+ *                tokens remain queries.  This is attention over a PADDED batch with a key-padding mask, what the
+ *                paper's own code ran (appendix on sequence length): cu_seqlens = 0, L, 2L, ... and key_lens = the
+ *                real lengths.  The backward gives masked tokens dK = dV = 0.  A sequence with key_lens[b] <= 0 is
+ *                skipped.  Matrix-core kernels only (MB_ERR_UNSUPPORTED with a combination the generic kernels serve).
  *   token_rows   dev, [>= cu_seqlens[B]] int32, or NULL.  NULL: token t is row t of q, k, v and o (packed
  *                buffers).  Otherwise token t is row token_rows[t] of all four buffers: passing the
  *                `indices` of mb_unpad_index lets the call read a padded [B*L, ...] batch directly and
@@ -165,8 +172,8 @@ MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, 
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens,
                             int B, int T, int max_seqlen, int H, int D, const float* slopes,
                             float softmax_scale, mb_dtype dt, void* o, int64_t o_row_stride,
-                            float* lse, void* workspace, size_t workspace_bytes, const int32_t* token_rows,
-                            void* stream);
+                            float* lse, void* workspace, size_t workspace_bytes, const int32_t* key_lens,
+                            const int32_t* token_rows, void* stream);
 
 /* Bytes of device workspace mb_alibi_attn_fwd / mb_alibi_attn_bwd need for these sizes (0 on invalid sizes; the
  * forward's is also 0 when it needs none). */
@@ -183,6 +190,7 @@ MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, in
  *   lse          dev, [H, T] float from the forward, read.
  *   dq, dk, dv   dev, [T, H, D] with row strides dq/dk/dv_row_stride, written (rows [0, T)).
  *   workspace    dev, at least mb_alibi_attn_bwd_workspace_bytes(...) bytes, scratch.
+ *   key_lens     as in the forward (NULL or [B]); tokens that are no keys get zero rows of dk and dv.
  *   token_rows   as in the forward; applies to dout, q, k, v, o, dq, dk and dv alike.
  * Deterministic: no atomics; two calls on the same inputs give identical bits.
  * A sequence longer than max_seqlen is skipped as in the forward (its rows of dq, dk, dv are left untouched, the
@@ -195,7 +203,8 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
-                            size_t workspace_bytes, const int32_t* token_rows, void* stream);
+                            size_t workspace_bytes, const int32_t* key_lens, const int32_t* token_rows,
+                            void* stream);
 
 /*
  * The backward attention for callers that cannot allocate device memory or bring a workspace: code under HIP
@@ -216,7 +225,8 @@ MB_API mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const
                             int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
-                            int64_t dk_row_stride, int64_t dv_row_stride, const int32_t* token_rows, void* stream);
+                            int64_t dk_row_stride, int64_t dv_row_stride, const int32_t* key_lens,
+                            const int32_t* token_rows, void* stream);
 
 /*
  * Reads and clears the current device's sticky misuse word.  Synchronises `stream`.

@@ -47,18 +47,18 @@ _lib.mb_zero_padding.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int,
 _lib.mb_alibi_attn_fwd.restype = c_int
 _lib.mb_alibi_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int, c_int,
                                    c_int, c_int, c_int, c_void_p, c_float, c_int, c_void_p, c_int64, c_void_p,
-                                   c_void_p, c_size_t, c_void_p, c_void_p]
+                                   c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
 _lib.mb_alibi_attn_fwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_fwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
-                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p])
+                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p, c_void_p])
 _lib.mb_alibi_attn_bwd_static.restype = c_int
 _lib.mb_alibi_attn_bwd_static.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5
                                           + [c_void_p, c_float, c_int] + [c_void_p] * 3 + [c_int64] * 3
-                                          + [c_void_p, c_void_p])
+                                          + [c_void_p, c_void_p, c_void_p])
 _lib.mb_device_status.restype = c_int
 _lib.mb_device_status.argtypes = [c_void_p]
 MB_STATIC_SCRATCH_BYTES = 16 << 20
@@ -192,7 +192,7 @@ def mb_zero_padding(padded: torch.Tensor, indices: torch.Tensor, T_cap: int, met
 
 
 def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None,
-                      token_rows=None, T=None, workspace=None):
+                      token_rows=None, T=None, workspace=None, key_lens=None):
     """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32).
     With token_rows the views are over a padded batch ([B*L, H, D]) and T (the lse pitch) must be given."""
     _, H, D = q.shape
@@ -208,7 +208,8 @@ def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scal
     _check(_lib.mb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                   _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
                                   _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _ptr(workspace),
-                                  0 if workspace is None else workspace.numel(), _ptr(token_rows), _stream()))
+                                  0 if workspace is None else workspace.numel(), _ptr(key_lens), _ptr(token_rows),
+                                  _stream()))
     return out, lse
 
 
@@ -221,7 +222,7 @@ def mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int
 
 
 def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
-                      dq=None, dk=None, dv=None, workspace=None, token_rows=None, T=None):
+                      dq=None, dk=None, dv=None, workspace=None, token_rows=None, T=None, key_lens=None):
     """Returns (dq, dk, dv), each [T, H, D] (padded-batch views when token_rows is given)."""
     R, H, D = q.shape
     T = R if T is None else T
@@ -236,12 +237,12 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o), _ptr(cu_seqlens),
                                   B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale), _dtype_code(q),
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
-                                  _ptr(workspace), workspace.numel(), _ptr(token_rows), _stream()))
+                                  _ptr(workspace), workspace.numel(), _ptr(key_lens), _ptr(token_rows), _stream()))
     return dq, dk, dv
 
 
 def mb_alibi_attn_bwd_static(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
-                             dq, dk, dv, token_rows=None, T=None):
+                             dq, dk, dv, token_rows=None, T=None, key_lens=None):
     """mb_alibi_attn_bwd on the library's static scratch array.  This wrapper allocates nothing either:
     the outputs dq, dk, dv must be given."""
     R, H, D = q.shape
@@ -251,7 +252,7 @@ def mb_alibi_attn_bwd_static(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int,
                                          _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o),
                                          _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
                                          _dtype_code(q), _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq),
-                                         _row_stride(dk), _row_stride(dv), _ptr(token_rows), _stream()))
+                                         _row_stride(dk), _row_stride(dv), _ptr(key_lens), _ptr(token_rows), _stream()))
     return dq, dk, dv
 
 

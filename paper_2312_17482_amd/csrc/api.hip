@@ -308,7 +308,7 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                             void* o, int64_t o_row_stride, float* lse, void* workspace, size_t workspace_bytes,
-                            const int32_t* token_rows, void* stream) {
+                            const int32_t* key_lens, const int32_t* token_rows, void* stream) {
   clear_error();
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
@@ -331,6 +331,9 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   const bool mfma = use_mfma(dt, D, softmax_scale);
   MB_REQUIRE(mfma || max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
              "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  MB_REQUIRE(key_lens == nullptr || mfma, MB_ERR_UNSUPPORTED,
+             "key_lens is served by the matrix-core kernels only (bf16, head_dim 64, softmax_scale > 0)");
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(key_lens) & 3u) == 0, MB_ERR_INVALID_ARG, "key_lens is not 4-byte aligned");
   const size_t need = mfma ? attn_fwd_mfma_workspace_bytes(B, max_seqlen, H) : 0;
   MB_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), MB_ERR_WORKSPACE,
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
@@ -338,7 +341,7 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
   st = misuse_flag_address(&misuse);
   if (st != MB_OK) return st;
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows, misuse};
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows, misuse};
   if (mfma)
     return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
                                 workspace, (hipStream_t)stream);
@@ -366,14 +369,18 @@ static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k
                                   int64_t v_row_stride, int64_t o_row_stride, const int32_t* cu_seqlens, int B, int T,
                                   int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                                   void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
-                                  int64_t dv_row_stride, void* workspace, const int32_t* token_rows, void* stream) {
+                                  int64_t dv_row_stride, void* workspace, const int32_t* key_lens,
+                                  const int32_t* token_rows, void* stream) {
   const bool mfma = use_mfma(dt, D, softmax_scale);
   MB_REQUIRE(mfma || max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
              "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
+  MB_REQUIRE(key_lens == nullptr || mfma, MB_ERR_UNSUPPORTED,
+             "key_lens is served by the matrix-core kernels only (bf16, head_dim 64, softmax_scale > 0)");
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(key_lens) & 3u) == 0, MB_ERR_INVALID_ARG, "key_lens is not 4-byte aligned");
   int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
   const mb_status st = misuse_flag_address(&misuse);
   if (st != MB_OK) return st;
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, token_rows, misuse};
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows, misuse};
   if (mfma)
     return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                 o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
@@ -429,7 +436,7 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                             void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
                             int64_t dv_row_stride, void* workspace, size_t workspace_bytes,
-                            const int32_t* token_rows, void* stream) {
+                            const int32_t* key_lens, const int32_t* token_rows, void* stream) {
   clear_error();
   bool empty = false;
   const mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
@@ -442,7 +449,7 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
   MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
   return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
                           cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
-                          dk_row_stride, dv_row_stride, workspace, token_rows, stream);
+                          dk_row_stride, dv_row_stride, workspace, key_lens, token_rows, stream);
 }
 
 mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* k, const void* v, const void* o,
@@ -451,7 +458,7 @@ mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* 
                                    const int32_t* cu_seqlens, int B, int T, int max_seqlen, int H, int D,
                                    const float* slopes, float softmax_scale, mb_dtype dt, void* dq, void* dk, void* dv,
                                    int64_t dq_row_stride, int64_t dk_row_stride, int64_t dv_row_stride,
-                                   const int32_t* token_rows, void* stream) {
+                                   const int32_t* key_lens, const int32_t* token_rows, void* stream) {
   clear_error();
   bool empty = false;
   mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
@@ -469,7 +476,7 @@ mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* 
   // tokens, the sequence order) is written earlier in the same call.
   return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
                           cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
-                          dk_row_stride, dv_row_stride, ws, token_rows, stream);
+                          dk_row_stride, dv_row_stride, ws, key_lens, token_rows, stream);
 }
 
 mb_status mb_device_status(void* stream) {

@@ -39,10 +39,11 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
                                                              float* __restrict__ delta,
                                                              const int32_t* __restrict__ rows, int max_seqlen,
                                                              int64_t plan_cap, int32_t* __restrict__ plan,
-                                                             int32_t* __restrict__ misuse) {
+                                                             int32_t* __restrict__ misuse,
+                                                             const int32_t* __restrict__ key_lens) {
   if (blockIdx.x < kPlanXcds) {
     __shared__ __attribute__((aligned(16))) PlanLds lds;
-    build_plan_list(cu, B, H, max_seqlen, plan_cap, plan, blockIdx.x, misuse, lds);
+    build_plan_list(cu, key_lens, B, H, max_seqlen, plan_cap, plan, blockIdx.x, misuse, lds);
   }
   const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
   const int sub = threadIdx.x & 7;
@@ -100,9 +101,18 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   __shared__ __attribute__((aligned(16))) float sL[2][kTileS];       // -lse in base-2 units (-inf past the end)
   __shared__ __attribute__((aligned(16))) float sD[2][kTileS];       // -Delta
 
-  int start, n, ktile, h;
-  if (!plan_fetch(plan, plan_cap, &start, &n, &ktile, &h)) return;   // this XCD's list is shorter
+  int start, n, nk, ktile, h;   // nk <= n: the sequence's first nk tokens are its keys
+  if (!plan_fetch(plan, plan_cap, &start, &n, &nk, &ktile, &h)) return;   // this XCD's list is shorter
   const int kv0 = ktile * kTile;   // < n by construction of the plan
+  if (kv0 >= nk) {   // a tile of tokens that are no keys (only when the call limits the keys): zero gradient rows
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    for (int j = kv0 + (int)(threadIdx.x >> 3); j < min(kv0 + kTile, n); j += 32) {
+      const int64_t gr = tok_row(rows, start + j);
+      *reinterpret_cast<u32x4*>(dk + gr * dks + h * kD + (threadIdx.x & 7) * 8) = zero;
+      *reinterpret_cast<u32x4*>(dv + gr * dvs + h * kD + (threadIdx.x & 7) * 8) = zero;
+    }
+    return;
+  }
   // first buffer row of the sequence, and whether its tokens sit in consecutive rows
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
   const bool contig =
@@ -113,7 +123,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps per-wave branches scalar
   const int c = lane & 31, g = lane >> 5;
   const int kw = kv0 + 32 * wave;
-  const bool wave_active = kw < n;
+  const bool wave_active = kw < nk;           // tokens at and beyond nk are no keys: their dK, dV are zero
   const int kj = kw + c;                      // this lane's key
   const int kblk = (kv0 >> 5) + wave;         // index of this wave's block of 32 keys
   const int ntiles = (n + kTileS - 1) / kTileS;
@@ -129,7 +139,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     for (int it = 0; it < 4; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       const int j = kv0 + 32 * it + st_row;
-      if (j < n) {
+      if (j < nk) {
         const int64_t gr = tok_row(rows, start + j);
         tk[it] = *reinterpret_cast<const u32x4*>(k + gr * ks + h * kD + st_col);
         tv[it] = *reinterpret_cast<const u32x4*>(v + gr * vs + h * kD + st_col);
@@ -291,10 +301,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
     if (it + 1 < ntiles) store_tile((it + 1) & 1);
   }
   __syncthreads();   // the buffers are free: they now carry the output rows
-  if (!wave_active) return;
+  const int orow = lane >> 3, ocol = (lane & 7) * 8;
+  if (!wave_active) {   // tokens that are no keys (only when the call limits the keys): zero gradient rows
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = 8 * it + orow;
+      if (kw + row < n) {
+        const int64_t gr = tok_row(rows, start + kw + row);
+        *reinterpret_cast<u32x4*>(dk + gr * dks + h * kD + ocol) = zero;
+        *reinterpret_cast<u32x4*>(dv + gr * dvs + h * kD + ocol) = zero;
+      }
+    }
+    return;
+  }
 
   uint16_t* slab = &smem[(32 * wave) * kPitch];   // 32 rows private to this wave
-  const int orow = lane >> 3, ocol = (lane & 7) * 8;
   auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride) {
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
@@ -309,7 +331,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int row = 8 * it + orow;
-      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      if (kw + row >= nk) w = u32x4{0u, 0u, 0u, 0u};   // a token that is no key
       if (kw + row < n) *reinterpret_cast<u32x4*>(out + tok_row(rows, start + kw + row) * stride + h * kD + ocol) = w;
     }
   };
@@ -330,8 +353,8 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
 
-  int start, n, qtile, h;
-  if (!plan_fetch(plan, plan_cap, &start, &n, &qtile, &h)) return;
+  int start, n, nk, qtile, h;   // nk <= n: the sequence's first nk tokens are its keys
+  if (!plan_fetch(plan, plan_cap, &start, &n, &nk, &qtile, &h)) return;
   const int q0 = qtile * kTile;
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
   const bool contig =
@@ -346,7 +369,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const int qi = qw + c;
   const bool q_ok = wave_active && qi < n;
   const int qblk = (q0 >> 5) + wave;
-  const int ntiles = (n + kTileS - 1) / kTileS;
+  const int ntiles = (nk + kTileS - 1) / kTileS;
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   const float cs = scale * kLog2e;
   const float k1 = slopes[h] / scale;
@@ -389,7 +412,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {
     if (contig) {
-      const int left = n - j0;      // > 0: rows j0 .. n-1 exist
+      const int left = nk - j0;     // > 0: key rows j0 .. nk-1 exist
       const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
           const_cast<uint16_t*>(k) + (int64_t)(row0 + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
@@ -405,7 +428,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     for (int it = 0; it < 2; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       const int j = j0 + 32 * it + st_row;
-      if (j < n) {
+      if (j < nk) {
         const int64_t gr = tok_row(rows, start + j);
         tk[it] = *reinterpret_cast<const u32x4*>(kh + gr * ks);
         tv[it] = *reinterpret_cast<const u32x4*>(vh + gr * vs);
@@ -487,7 +510,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     if (wave_active) {
       const uint16_t* sK = smem + (jt & 1) * kBuf;
       const uint16_t* sV = sK + kHalf;
-      const int rem = n - j0;
+      const int rem = nk - j0;
       kblock(sK, sV, j0, 0, rem);
       kblock(sK, sV, j0, 1, rem);
     }
@@ -537,7 +560,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows,
-    int32_t* __restrict__ misuse) {
+    int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
   __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
@@ -552,12 +575,16 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     raise_misuse(misuse);
     return;
   }
+  const int nk = key_lens ? min(key_lens[b], n) : n;   // the sequence's first nk tokens are its keys
+  if (nk <= 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
   const int kw = 32 * wave;
-  const int nblk = (n + 31) >> 5;
-  const bool wave_active = wave < nblk;
+  const int nblk = (n + 31) >> 5;        // blocks of 32 queries
+  const int nblk_k = (nk + 31) >> 5;     // blocks of 32 keys
+  const bool wave_active = wave < nblk;  // this wave's tokens exist: phase 2 (queries) and the gradient rows
+  const bool wave_keys = wave < nblk_k;  // ... and are keys: phase 1
   const int kj = kw + c;
   const float cs = scale * kLog2e;
 
@@ -590,7 +617,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
-      if (32 * it + st_row < n) {
+      if (32 * it + st_row < nk) {
         tk[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kh + gr[it] * ks));
         tv[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + gr[it] * vs));
       }
@@ -648,9 +675,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 
   // ---- phase 1
   f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows, this wave's keys along lanes
-  if (wave_active) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
+  for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
+  if (wave_keys) {
     // The S accumulator is pre-loaded with bias/scale = -(m_h/scale)|i-j| and the dP accumulator with
     // -Delta_i, so that after the matrix products  P = exp2(acc_S * c - lse2_i)  and  dS = P * acc_dP.
     const float k1 = slopes[h] / scale;
@@ -697,8 +724,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         // inf/NaN here (its score never entered lse) and phase 2 multiplies it with a zero K row, so it
         // must be an exact zero in LDS.
         u32x2 w;
-        w[0] = kj < n ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
-        w[1] = kj < n ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
+        w[0] = kj < nk ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
+        w[1] = kj < nk ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
         *reinterpret_cast<u32x2*>(&sDs[kj * kDsPitch + 32 * ib + 8 * r + 4 * g]) = w;
       }
 #pragma unroll
@@ -725,7 +752,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
   // of one wave complete in order, so no barrier is needed between its uses.
   uint16_t* slab = &sB[kw * kPitch];
   const int orow = lane >> 3, ocol = (lane & 7) * 8;
-  auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride) {
+  // (rows at and beyond `live` are written as zeros: tokens that are no keys have zero dK and dV)
+  auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride, int live) {
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -740,7 +768,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       const int row = 8 * it + orow;
-      const u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+      if (kw + row >= live) w = u32x4{0u, 0u, 0u, 0u};
       if (kw + row < n) {
         // written into the padded layout these rows are final results of the step: stream them out
         if (kRows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride));
@@ -751,9 +780,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 
   // ---- phase 2
   if (wave_active) {
-    store_rows(dkacc, scale, dk, dks);
-    store_rows(dvacc, 1.f, dv, dvs);
-    // K registers -> LDS over Q; rows of keys >= n are zeros because they were staged as zeros
+    store_rows(dkacc, scale, dk, dks, nk);
+    store_rows(dvacc, 1.f, dv, dvs, nk);
+  }
+  if (wave_keys) {
+    // K registers -> LDS over Q; rows of keys >= nk are zeros because they were staged as zeros
 #pragma unroll
     for (int s = 0; s < 4; ++s)
       *reinterpret_cast<u32x4*>(&sA[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
@@ -765,7 +796,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
 #pragma unroll
   for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
 #pragma unroll 1
-  for (int jb = 0; jb < nblk; ++jb) {
+  for (int jb = 0; jb < nblk_k; ++jb) {
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       const int krow = 32 * jb + 16 * kk + tr_row;
@@ -779,7 +810,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       }
     }
   }
-  store_rows(dqacc, scale, dq, dqs);
+  store_rows(dqacc, scale, dq, dqs, n);
 }
 
 }  // namespace
@@ -794,7 +825,7 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   hipLaunchKernelGGL(attn_bwd_fused128_kernel<R>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
                      (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs, \
                      ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv,     \
-                     dqs, dks, dvs, s.T, s.token_rows, s.misuse)
+                     dqs, dks, dvs, s.T, s.token_rows, s.misuse, s.key_lens)
     if (s.token_rows) MB_LAUNCH_FUSED(true);
     else MB_LAUNCH_FUSED(false);
 #undef MB_LAUNCH_FUSED
@@ -808,7 +839,7 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   const int64_t delta_blocks = (rows + 31) / 32;
   hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)(delta_blocks > kPlanXcds ? delta_blocks : kPlanXcds)),
                      dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens,
-                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, plan, s.misuse);
+                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, plan, s.misuse, s.key_lens);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   // buffer-load path: a sequence's rows within 2^31 bytes of its first

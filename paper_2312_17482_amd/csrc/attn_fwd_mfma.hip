@@ -42,12 +42,13 @@ __device__ __forceinline__ void poison_lse(float* __restrict__ row, int n, int32
 
 // The forward's own plan launch: workgroup c builds list c (see attn_plan.h); workgroup 0 then marks the
 // sequences the plan skipped (longer than max_seqlen) by setting their log-sum-exp rows to NaN.
-__global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(const int32_t* __restrict__ cu, int B, int H,
+__global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(const int32_t* __restrict__ cu,
+                                                                 const int32_t* __restrict__ key_lens, int B, int H,
                                                                  int max_seqlen, int64_t cap, int32_t* __restrict__ plan,
                                                                  int32_t* __restrict__ misuse, float* __restrict__ lse,
                                                                  int T) {
   __shared__ __attribute__((aligned(16))) PlanLds lds;
-  build_plan_list(cu, B, H, max_seqlen, cap, plan, blockIdx.x, misuse, lds);
+  build_plan_list(cu, key_lens, B, H, max_seqlen, cap, plan, blockIdx.x, misuse, lds);
   if (blockIdx.x != 0) return;
   for (int b = 0; b < B; ++b) {
     const int s0 = cu[b], len = cu[b + 1] - s0;
@@ -70,8 +71,8 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBufElems];   // 38 KB; also stages Q and O rows
 
-  int start, n, qtile, h;
-  if (!plan_fetch(plan, plan_cap, &start, &n, &qtile, &h)) return;   // this XCD's list is shorter
+  int start, n, nk, qtile, h;   // nk <= n: the sequence's first nk tokens are its keys
+  if (!plan_fetch(plan, plan_cap, &start, &n, &nk, &qtile, &h)) return;   // this XCD's list is shorter
   const int q0 = qtile * kBlockQ;   // < n by construction of the plan
   // first buffer row of the sequence, and whether its tokens sit in consecutive rows
   const int row0 = kMode == kRowsMaybeContiguous ? __builtin_amdgcn_readfirstlane(rows[start]) : start;
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const bool wave_active = qw < n;
   const int qi = qw + c;                  // this lane's query (position inside the sequence)
   const int qblk = (q0 >> 5) + wave;      // index of this wave's block of 32 queries
-  const int ntiles = (n + kTileK - 1) / kTileK;
+  const int ntiles = (nk + kTileK - 1) / kTileK;
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
   const uint16_t* kh = k + h * kD + st_col;
   const uint16_t* vh = v + h * kD + st_col;
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   const uint32_t voff = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)(h * kD + st_col)) * 2u;
   auto issue_tile = [&](int j0) {   // rows j0 + 32it + st_row of K and V -> registers (zeros past the end)
     if (contig) {
-      const int left = n - j0;      // > 0: rows j0 .. n-1 exist
+      const int left = nk - j0;     // > 0: key rows j0 .. nk-1 exist
       const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
           const_cast<uint16_t*>(k) + (int64_t)(row0 + j0) * ks, 0, left * (int)ks * 2, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
     for (int it = 0; it < 2; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
       const int j = j0 + 32 * it + st_row;
-      if (j < n) {
+      if (j < nk) {
         const int64_t gr = tok_row(rows, start + j);
         tk[it] = *reinterpret_cast<const u32x4*>(kh + gr * ks);
         tv[it] = *reinterpret_cast<const u32x4*>(vh + gr * vs);
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
   auto tile = [&](int j0, int jt) {
     const uint16_t* bufK = smem + (jt & 1) * kBufElems;
     const uint16_t* bufV = bufK + kTileK * kKStride;
-    const int rem = n - j0;
+    const int rem = nk - j0;
     float fi = (float)(qi - j0 - 4 * g);   // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
     asm volatile("" : "+v"(fi));
     f32x16 sacc[2];
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(256, 3) void attn_fwd_tiled_kernel(
         for (int i = 0; i < 16; ++i) sacc[jb][i] = fmaf((float)(jb * 32 + 8 * (i >> 2) + (i & 3)), sk, a);
       }
     }
-    if (rem < kTileK) {   // ragged end: keys >= n get -inf
+    if (rem < kTileK) {   // ragged end: keys that do not exist (or are masked out) get -inf
       const int lim = rem - 4 * g;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb)
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, int64_t qs,
     int64_t ks, int64_t vs, const int32_t* __restrict__ cu, const float* __restrict__ slopes, float scale,
     uint16_t* __restrict__ o, int64_t os, float* __restrict__ lse, int T, const int32_t* __restrict__ rows,
-    int32_t* __restrict__ misuse) {
+    int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens) {
   // Every global access is a full 128-byte row of one head shared by 8 lanes (16 bytes each); the
   // fragment layouts the matrix cores need are produced by passing through LDS:
   //   sV first carries the Q tile (rows -> Q^T fragments), then V;  after the S phase each wave reuses
@@ -313,11 +314,14 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     poison_lse(lse + (int64_t)h * T + start, n, misuse);
     return;
   }
+  const int nk = key_lens ? min(key_lens[b], n) : n;   // the sequence's first nk tokens are its keys
+  if (nk <= 0) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
   const int qi = 32 * wave + c;
-  const int nblk = (n + 31) >> 5;
+  const int nblk = (n + 31) >> 5;       // blocks of 32 queries
+  const int nblk_k = (nk + 31) >> 5;    // blocks of 32 keys
   const bool wave_active = wave < nblk;
 
   // ---- coalesced row loads: thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
@@ -339,8 +343,8 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
-      if (32 * it + st_row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(q + gr[it] * qs + h * kD + st_col);
+      if (32 * it + st_row < n) tq[it] = *reinterpret_cast<const u32x4*>(q + gr[it] * qs + h * kD + st_col);
+      if (32 * it + st_row < nk) {
         tk[it] = *reinterpret_cast<const u32x4*>(k + gr[it] * ks + h * kD + st_col);
         tv[it] = *reinterpret_cast<const u32x4*>(v + gr[it] * vs + h * kD + st_col);
       }
@@ -355,8 +359,8 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
-      if (32 * it + st_row < n) {
-        tq[it] = *reinterpret_cast<const u32x4*>(qh + qoff + (uint32_t)(32 * it) * (uint32_t)qs);
+      if (32 * it + st_row < n) tq[it] = *reinterpret_cast<const u32x4*>(qh + qoff + (uint32_t)(32 * it) * (uint32_t)qs);
+      if (32 * it + st_row < nk) {
         tk[it] = *reinterpret_cast<const u32x4*>(kh + koff + (uint32_t)(32 * it) * (uint32_t)ks);
         tv[it] = *reinterpret_cast<const u32x4*>(vh + voff + (uint32_t)(32 * it) * (uint32_t)vs);
       }
@@ -384,7 +388,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   const float k1 = slopes[h] / scale;   // bias in units of the raw dot product
   float fi = (float)(qi - 4 * g);       // i - j = fi - cj with cj = 32jb + 8*(v/4) + v%4
   asm volatile("" : "+v"(fi));          // keep the distance arithmetic in floating point
-  const int lim = n - 4 * g;            // key of (jb, v) is real iff cj < lim
+  const int lim = nk - 4 * g;           // key of (jb, v) is real iff cj < lim
 
   // ---- accumulators pre-loaded with the bias, then S^T = K Q^T on top
   f32x16 sacc[4];
@@ -392,7 +396,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   if (wave_active) {
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
-      if (jb < nblk) {
+      if (jb < nblk_k) {
         if (jb == wave) {   // the block that holds the diagonal
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
@@ -408,7 +412,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
             sacc[jb][i] = fmaf(cj, sk, a);
           }
         }
-        if (jb == nblk - 1 && (n & 31)) {   // ragged end: keys >= n get -inf
+        if (jb == nblk_k - 1 && (nk & 31)) {   // ragged end: keys >= nk get -inf
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int cj = jb * 32 + 8 * (i >> 2) + (i & 3);
@@ -423,7 +427,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
     // ---- row maximum of the raw accumulators
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
-      if (jb < nblk) {
+      if (jb < nblk_k) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) m = fmaxf(m, sacc[jb][i]);
       }
@@ -442,7 +446,7 @@ __global__ __launch_bounds__(256, 4) void attn_fwd_short_kernel(
   float l = 0.f;
 #pragma unroll
   for (int jb = 0; jb < 4; ++jb) {
-    if (jb < nblk) {
+    if (jb < nblk_k) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const float p = fast_exp2(fmaf(sacc[jb][i], cs, -mc));
@@ -510,18 +514,18 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
     if (s.token_rows)
       hipLaunchKernelGGL(attn_fwd_short_kernel<true>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse);
+                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse, s.key_lens);
     else
       hipLaunchKernelGGL(attn_fwd_short_kernel<false>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, qs, ks, vs, s.cu_seqlens, s.slopes, s.scale,
-                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse);
+                         (uint16_t*)o, os, lse, s.T, s.token_rows, s.misuse, s.key_lens);
     return check_launch("attn_fwd_short_kernel");
   }
   // any length: plan (8 small workgroups), then one workgroup per plan slot
   const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
   if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
   int32_t* plan = static_cast<int32_t*>(workspace);
-  hipLaunchKernelGGL(attn_plan_kernel, dim3(kPlanXcds), dim3(kPlanThreads), 0, stream, s.cu_seqlens, s.B, s.H,
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(kPlanXcds), dim3(kPlanThreads), 0, stream, s.cu_seqlens, s.key_lens, s.B, s.H,
                      s.max_seqlen, cap, plan, s.misuse, lse, s.T);
   mb_status st = check_launch("attn_plan_kernel");
   if (st != MB_OK) return st;

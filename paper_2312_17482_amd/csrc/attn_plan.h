@@ -27,9 +27,10 @@ static constexpr int kPlanXcds = 8;
 static constexpr int kPlanThreads = 256;    // workgroup size of the code that builds a plan
 static constexpr int kSortMaxB = 512;       // sequences ranked by length (also the ranks handled per pass)
 
-// One work item, 16 bytes: first packed token and length of the sequence, tile index and head.
+// One work item, 16 bytes: first packed token and length of the sequence, tile index and head, and how many of
+// the sequence's tokens act as keys (the length itself unless the call limits the keys).
 struct __attribute__((aligned(16))) PlanItem {
-  int32_t start, n, tile_head /* tile | head << 16 */, reserved;
+  int32_t start, n, tile_head /* tile | head << 16 */, nk;
 };
 
 // Number of pairs p in [0, n) dealt to XCD c:  p % 16 == c  or  p % 16 == 15 - c.
@@ -53,15 +54,18 @@ struct PlanLds {
   uint32_t keys[kSortMaxB + 16];
   int32_t start[kSortMaxB];
   int32_t len[kSortMaxB];
+  int32_t klen[kSortMaxB];
   int32_t off[kSortMaxB];
   int32_t wave_sum[kPlanThreads / 64];
   int32_t carry;
 };
 
 // Builds list `c` of the plan.  Called by all kPlanThreads threads of one workgroup (contains barriers).
-// A sequence longer than max_seqlen gets no items (it is skipped as a whole) and raises the misuse flag.
-__device__ inline void build_plan_list(const int32_t* __restrict__ cu, int B, int H, int max_seqlen, int64_t cap,
-                                       int32_t* __restrict__ plan, int c, int32_t* __restrict__ misuse, PlanLds& L) {
+// A sequence longer than max_seqlen gets no items (it is skipped as a whole) and raises the misuse flag; a
+// sequence without keys (key_lens[b] <= 0) gets none either.
+__device__ inline void build_plan_list(const int32_t* __restrict__ cu, const int32_t* __restrict__ key_lens, int B, int H,
+                                       int max_seqlen, int64_t cap, int32_t* __restrict__ plan, int c,
+                                       int32_t* __restrict__ misuse, PlanLds& L) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   PlanItem* __restrict__ items = reinterpret_cast<PlanItem*>(plan + 8) + (int64_t)c * cap;
   if (tid == 0) L.carry = 0;
@@ -84,14 +88,20 @@ __device__ inline void build_plan_list(const int32_t* __restrict__ cu, int B, in
           r += (k4.x > mine ? 1 : 0) + (k4.y > mine ? 1 : 0) + (k4.z > mine ? 1 : 0) + (k4.w > mine ? 1 : 0);
         }
         const int s0 = cu[cand];
+        const int len = cu[cand + 1] - s0;
+        const int kl = key_lens ? min(key_lens[cand], len) : len;
         L.start[r] = s0;
-        L.len[r] = cu[cand + 1] - s0;
+        L.len[r] = kl > 0 ? len : 0;   // no keys: nothing to compute
+        L.klen[r] = kl;
       }
     } else {
       for (int i = tid; i < nb; i += kPlanThreads) {
         const int s0 = cu[r0 + i];
+        const int len = cu[r0 + i + 1] - s0;
+        const int kl = key_lens ? min(key_lens[r0 + i], len) : len;
         L.start[i] = s0;
-        L.len[i] = cu[r0 + i + 1] - s0;
+        L.len[i] = kl > 0 ? len : 0;
+        L.klen[i] = kl;
       }
     }
     __syncthreads();
@@ -136,7 +146,7 @@ __device__ inline void build_plan_list(const int32_t* __restrict__ cu, int B, in
       PlanItem it;
       it.start = L.start[r - r0];
       it.n = len;
-      it.reserved = 0;
+      it.nk = L.klen[r - r0];
       for (int x = 0; x < tiles; ++x) {
         it.tile_head = x | (h << 16);
         items[at + x] = it;
@@ -148,8 +158,8 @@ __device__ inline void build_plan_list(const int32_t* __restrict__ cu, int B, in
 }
 
 // What a kernel's workgroup reads: its item, or nothing.  i = workgroup index of a launch of 8 * cap workgroups.
-__device__ __forceinline__ bool plan_fetch(const int32_t* __restrict__ plan, int64_t cap, int* start, int* n, int* tile,
-                                           int* head) {
+__device__ __forceinline__ bool plan_fetch(const int32_t* __restrict__ plan, int64_t cap, int* start, int* n, int* nk,
+                                           int* tile, int* head) {
   const int c = blockIdx.x & (kPlanXcds - 1);
   const int j = blockIdx.x >> 3;
   const int count = plan[c];
@@ -157,6 +167,7 @@ __device__ __forceinline__ bool plan_fetch(const int32_t* __restrict__ plan, int
   if (j >= count) return false;
   *start = __builtin_amdgcn_readfirstlane(it.x);
   *n = __builtin_amdgcn_readfirstlane(it.y);
+  *nk = __builtin_amdgcn_readfirstlane(it.w);
   *tile = __builtin_amdgcn_readfirstlane(it.z) & 0xffff;
   *head = (int)((uint32_t)__builtin_amdgcn_readfirstlane(it.z) >> 16);
   return true;

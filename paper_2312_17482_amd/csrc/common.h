@@ -21,6 +21,7 @@ struct AttnShape {
   const int32_t* cu_seqlens;
   const float* slopes;
   float scale;
+  const int32_t* key_lens;     // NULL, or [B]: only the first key_lens[b] tokens of sequence b act as keys
   const int32_t* token_rows;   // NULL, or [T]: row of token t inside the activation buffers
   int32_t* misuse;             // this device's sticky flag: set by a kernel that meets a sequence longer than max_seqlen
 };

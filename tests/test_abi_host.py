@@ -46,20 +46,20 @@ def test_slopes_against_fixture():
 
 def fwd_args(**over):
     a = dict(q=A, k=A, v=A, qs=768, ks=768, vs=768, cu=A, B=2, T=64, max_seqlen=32, H=12, D=64, slopes=A,
-             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, ws=None, wsb=0, rows=None, stream=None)
+             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, ws=None, wsb=0, klens=None, rows=None, stream=None)
     a.update(over)
     return [a[x] for x in ("q", "k", "v", "qs", "ks", "vs", "cu", "B", "T", "max_seqlen", "H", "D", "slopes", "scale",
-                           "dt", "o", "os", "lse", "ws", "wsb", "rows", "stream")]
+                           "dt", "o", "os", "lse", "ws", "wsb", "klens", "rows", "stream")]
 
 
 def bwd_args(**over):
     a = dict(do=A, q=A, k=A, v=A, o=A, lse=A, dos=768, qs=768, ks=768, vs=768, os=768, cu=A, B=2, T=64,
              max_seqlen=32, H=12, D=64, slopes=A, scale=0.125, dt=mb.MB_BF16, dq=A, dk=A, dv=A, dqs=768, dks=768,
-             dvs=768, ws=A, wsb=1 << 20, rows=None, stream=None)
+             dvs=768, ws=A, wsb=1 << 20, klens=None, rows=None, stream=None)
     a.update(over)
     return [a[x] for x in ("do", "q", "k", "v", "o", "lse", "dos", "qs", "ks", "vs", "os", "cu", "B", "T",
                            "max_seqlen", "H", "D", "slopes", "scale", "dt", "dq", "dk", "dv", "dqs", "dks", "dvs",
-                           "ws", "wsb", "rows", "stream")]
+                           "ws", "wsb", "klens", "rows", "stream")]
 
 
 @pytest.mark.parametrize("over,status,needle", [
@@ -82,6 +82,8 @@ def bwd_args(**over):
     (dict(max_seqlen=512, ws=A, wsb=64), mb.MB_ERR_WORKSPACE, "needed"),
     (dict(max_seqlen=512, ws=A + 4, wsb=1 << 20), mb.MB_ERR_INVALID_ARG, "workspace is not 16-byte"),
     (dict(max_seqlen=1 << 23), mb.MB_ERR_UNSUPPORTED, "2^22"),
+    (dict(klens=A + 2), mb.MB_ERR_INVALID_ARG, "key_lens is not 4-byte"),
+    (dict(klens=A, dt=mb.MB_F32, D=16, H=2, qs=32, ks=32, vs=32, os=32), mb.MB_ERR_UNSUPPORTED, "key_lens"),
 ])
 def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
     assert lib.mb_alibi_attn_fwd(*fwd_args(**over)) == status

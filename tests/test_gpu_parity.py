@@ -442,6 +442,53 @@ def test_sequence_longer_than_max_seqlen_is_skipped_and_reported(mb, bf16, D, le
             assert torch.all(o[sl] == guard) and torch.all(torch.isnan(lse[:, sl])) and torch.all(g[sl] == guard)
 
 
+@pytest.mark.parametrize("L,lengths", [(128, [128, 17, 64, 33, 1, 0, 96, 127]), (300, [300, 17, 150, 33, 1, 0, 129, 256]),
+                                       (64, [5, 64, 32, 31])])
+def test_padded_batch_with_key_mask_equals_the_oracle_on_real_tokens(mb, L, lengths):
+    """Attention over the PADDED batch with a key-padding mask (what the paper's own code ran: appendix on sequence
+    length): every sequence has L tokens (cu_seqlens = 0, L, 2L, ...), key_lens = the real lengths.  No unpadding
+    anywhere.  On the real tokens O, lse, dQ, dK, dV equal the oracle's padded-with-mask result; padding tokens get
+    zero dK and dV; padding content (large values) does not leak.  The upstream gradient is zero at padding rows,
+    as in a training step whose loss ignores them."""
+    H, D = 2, 64
+    c = wl.random_attention_case(95, lengths, L, H, D, std=0.5, bf16=True)
+    B = len(lengths)
+    pad = c["mask"] == 0
+    for key in ("q", "k", "v"):
+        c[key][pad] = 60.0                       # garbage at padding positions must not leak
+    c["do"][pad] = 0.0
+    x = to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(B * L, 3, H, D), True)
+    do = to_dev(c["do"].reshape(B * L, H, D), True)
+    cu = torch.arange(0, B * L + 1, L, dtype=torch.int32, device="cuda")
+    klens = torch.tensor(lengths, dtype=torch.int32, device="cuda")
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    guard = 5.0
+    o = torch.full((B * L, H, D), guard, dtype=torch.bfloat16, device="cuda")
+    lse = torch.full((H, B * L), guard, dtype=torch.float32, device="cuda")
+    mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu, L, slopes, c["scale"], out=o, lse=lse, key_lens=klens)
+    g = torch.full((B * L, 3, H, D), guard, dtype=torch.bfloat16, device="cuda")
+    mb.mb_alibi_attn_bwd(do, x[:, 0], x[:, 1], x[:, 2], o, lse, cu, L, slopes, c["scale"], dq=g[:, 0], dk=g[:, 1],
+                         dv=g[:, 2], key_lens=klens)
+    mb.mb_device_status()
+    ref = run_oracle(c, orc.alibi_slopes(H))
+    real = c["mask"] != 0
+    got = {"o": o.double().cpu().numpy().reshape(B, L, H, D)}
+    gg = g.double().cpu().numpy().reshape(B, L, 3, H, D)
+    got.update(dq=gg[:, :, 0], dk=gg[:, :, 1], dv=gg[:, :, 2])
+    for key in ("o", "dq", "dk", "dv"):
+        assert np.all(np.isfinite(got[key])), key
+        ma, rf = err_stats(got[key][real], ref[key][real])
+        assert ma <= BF16_TOL[0] and rf <= BF16_TOL[1], "padded+mask %s: %.3e %.3e" % (key, ma, rf)
+    lse_got = lse.double().cpu().numpy().reshape(H, B, L).transpose(1, 0, 2)        # [B, H, L]
+    realh = np.broadcast_to(real[:, None, :], lse_got.shape)
+    assert np.max(np.abs(lse_got[realh] - ref["lse"][realh])) <= 1e-3
+    for b, n in enumerate(lengths):
+        if n == 0:       # a sequence without keys is skipped: nothing written
+            assert np.all(got["o"][b] == guard) and np.all(gg[b] == guard)
+        else:            # padding tokens are no keys: zero dK, dV; zero upstream gradient: zero dQ
+            assert np.all(got["dk"][b, n:] == 0) and np.all(got["dv"][b, n:] == 0) and np.all(got["dq"][b, n:] == 0)
+
+
 def test_bf16_tile_boundary_lengths(mb):
     """Lengths on both sides of every tile boundary of the any-length kernels (32, 64, 128) in one batch."""
     lengths = [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 2, 0]
