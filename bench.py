@@ -124,6 +124,9 @@ def main():
     workspace = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
     ws_fwd = torch.empty(max(mb.mb_alibi_attn_fwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16 if bf16 else mb.MB_F32), 16),
                          dtype=torch.uint8, device=dev)
+    # the any-length kernels (max_len > 128) follow a work plan: built once per step, used by forward and backward
+    use_plan = bf16 and D == 64 and L > 128
+    plan = torch.empty(max(mb.mb_attn_plan_bytes(B, L, H), 16), dtype=torch.uint8, device=dev) if use_plan else None
     lse_buf = torch.empty(H * cap, dtype=torch.float32, device=dev)
     seqlens = torch.empty(B, dtype=torch.int32, device=dev)
     cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
@@ -144,6 +147,8 @@ def main():
         st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
                                 meta.data_ptr(), sp)
         assert st == 0, mb.mb_last_error()
+        if use_plan:
+            mb.mb_attn_plan(cu, L, H, plan=plan)
         mark(1)
         # No host round trip: the token count stays on the device (meta); the attention calls get the
         # capacity B*L as their row count and L as the bound of the sequence length.
@@ -151,12 +156,12 @@ def main():
         # just written are still in cache when the forward reads them)
         mb.mb_unpad(qkv_padded, indices, cap, meta, out=qkv.view(cap, 3 * H * D))
         mark(2)
-        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse, workspace=ws_fwd)
+        mb.mb_alibi_attn_fwd(q_, k_, v_, cu, L, slopes, scale, out=o, lse=lse, workspace=ws_fwd, plan=plan)
         mark(3)
         mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
         mark(4)
         mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
-                             dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace)
+                             dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace, plan=plan)
         mark(5)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
         mark(6)
@@ -194,6 +199,9 @@ def main():
     W1, W3 = H * D * esize, 3 * H * D * esize
     call_bytes = {"unpad_qkv": 2 * T_host * W3, "unpad_do": 2 * T_host * W1, "pad_o": (T_host + cap) * W1,
                   "pad_dqkv": (T_host + cap) * W3}
+    if use_plan:
+        call_names = ("unpad_index_and_plan",) + call_names[1:]
+        call_us["unpad_index_and_plan"] = call_us.pop("unpad_index")
     calls = {}
     for name in call_names:
         calls[name] = dict(stats(call_us[name]), unit="us")
@@ -215,11 +223,13 @@ def main():
         st = lib.mb_unpad_index(mask.data_ptr(), B, L, seqlens.data_ptr(), cu.data_ptr(), indices.data_ptr(),
                                 meta.data_ptr(), sp)
         assert st == 0, mb.mb_last_error()
+        if use_plan:
+            mb.mb_attn_plan(cu, L, H, plan=plan)
         mb.mb_alibi_attn_fwd(qp_, kp_, vp_, cu, L, slopes, scale, out=op_, lse=lse, token_rows=indices, T=cap,
-                             workspace=ws_fwd)
+                             workspace=ws_fwd, plan=plan)
         mb.mb_zero_padding(o_padded, indices, cap, meta, B, L)
         mb.mb_alibi_attn_bwd(dop_, qp_, kp_, vp_, op_, lse, cu, L, slopes, scale, dq=dqkvp_[:, 0], dk=dqkvp_[:, 1],
-                             dv=dqkvp_[:, 2], workspace=workspace, token_rows=indices, T=cap)
+                             dv=dqkvp_[:, 2], workspace=workspace, token_rows=indices, T=cap, plan=plan)
         mb.mb_zero_padding(dqkv_padded, indices, cap, meta, B, L)
 
     ref_o, ref_g = o_padded.clone(), dqkv_padded.clone()
@@ -503,12 +513,17 @@ def time_config(mb, wl, name, dev, seeds=1, launches=60):
         ws_f = torch.empty(max(16, mb.mb_alibi_attn_fwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16)), dtype=torch.uint8, device=dev)
         ws_b = torch.empty(max(16, mb.mb_alibi_attn_bwd_workspace_bytes(B, cap, L, H, D, mb.MB_BF16)), dtype=torch.uint8, device=dev)
 
+        # the any-length kernels' work plan is built once per batch (it serves every attention call on the batch:
+        # all layers, forward and backward); its own time is reported beside the calls
+        plan = mb.mb_attn_plan(cu, L, H) if L > 128 else None
+
         def fwd(x, do_, o_, dx):
-            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu, L, slopes, batch["scale"], out=o_, lse=lse, workspace=ws_f)
+            mb.mb_alibi_attn_fwd(x[:, 0], x[:, 1], x[:, 2], cu, L, slopes, batch["scale"], out=o_, lse=lse, workspace=ws_f,
+                                 plan=plan)
 
         def bwd(x, do_, o_, dx):
             mb.mb_alibi_attn_bwd(do_, x[:, 0], x[:, 1], x[:, 2], o_, lse, cu, L, slopes, batch["scale"], dq=dx[:, 0],
-                                 dk=dx[:, 1], dv=dx[:, 2], workspace=ws_b)
+                                 dk=dx[:, 1], dv=dx[:, 2], workspace=ws_b, plan=plan)
 
         def measure(fn, rotate):
             for i in range(6):
@@ -525,6 +540,8 @@ def time_config(mb, wl, name, dev, seeds=1, launches=60):
         for st in sets:                      # every set holds its own forward results before any backward is timed
             fwd(*st)
         row = {"seed_offset": s_off, "T": T, "sum_len2": int((lengths.astype(np.int64) ** 2).sum()), "max_len": int(lengths.max())}
+        if plan is not None:
+            row["plan_once_per_batch_us"] = measure(lambda *a: mb.mb_attn_plan(cu, L, H, plan=plan), False)
         for temp, rotate in (("warm", False), ("cold", True)):
             tf, tb = measure(fwd, rotate), measure(bwd, rotate)
             row[temp] = {"fwd_us": tf, "bwd_us": tb,

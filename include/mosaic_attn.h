@@ -128,6 +128,20 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
                                  mb_dtype dt, void* padded, void* stream);
 
 /*
+ * Work plan of the any-length attention kernels (max_seqlen > 128 on the matrix cores): which workgroup computes
+ * which (sequence, head, 128 tokens), dealt evenly to the chip's XCDs, longest sequences first.  It depends on
+ * cu_seqlens, key_lens, B, max_seqlen and H only.  mb_alibi_attn_fwd and mb_alibi_attn_bwd build one themselves
+ * on every call (the forward with a small launch of its own); a caller that runs several attention calls on the
+ * same batch (every layer of an encoder, forward and backward) builds it once here and passes it as `plan`.
+ *   cu_seqlens, key_lens, B, max_seqlen, H   exactly as they will be passed to the attention calls.
+ *   plan   dev, at least mb_attn_plan_bytes(B, max_seqlen, H) bytes, 16-byte aligned, written.
+ * Sequences longer than max_seqlen get no work (they are skipped) and raise the misuse word, see mb_device_status.
+ */
+MB_API size_t mb_attn_plan_bytes(int B, int max_seqlen, int H);
+MB_API mb_status mb_attn_plan(const int32_t* cu_seqlens, const int32_t* key_lens, int B, int max_seqlen, int H,
+                              void* plan, size_t plan_bytes, void* stream);
+
+/*
  * Forward attention, Eq. 1:  for every sequence b, head h and tokens i, j of that sequence
  *   S_ij = softmax_scale * q_i . k_j - slopes[h] * |i - j|,   P = softmax_j(S),   O_i = sum_j P_ij v_j,
  *   lse_i = log sum_j exp(S_ij).
@@ -147,7 +161,10 @@ MB_API mb_status mb_zero_padding(const int32_t* indices, int T_cap, const int32_
  *   lse          dev, [H, T] float, written.
  *   workspace    dev, at least mb_alibi_attn_fwd_workspace_bytes(...) bytes, scratch (the work plan of the
  *                any-length kernels); may be NULL when that is 0 (max_seqlen <= 128, or a combination served by
- *                the generic kernels).
+ *                the generic kernels) or when `plan` is given.
+ *   plan         dev, NULL or a plan built by mb_attn_plan for these very cu_seqlens, key_lens, B, max_seqlen, H
+ *                (read only; ignored by kernels that need none).  With a plan of the caller's the log-sum-exp rows
+ *                of a sequence longer than max_seqlen are left untouched instead of being set to NaN.
  *   key_lens     dev, [B] int32, or NULL.  NULL: every token of a sequence is a key for every query of that
  *                sequence (the packed computation).  Otherwise only the first min(key_lens[b], len_b) tokens of
  *                sequence b act as keys; the others are masked out of every softmax (S_ij = -inf) while all len_b
@@ -173,7 +190,7 @@ MB_API mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, 
                             int B, int T, int max_seqlen, int H, int D, const float* slopes,
                             float softmax_scale, mb_dtype dt, void* o, int64_t o_row_stride,
                             float* lse, void* workspace, size_t workspace_bytes, const int32_t* key_lens,
-                            const int32_t* token_rows, void* stream);
+                            const int32_t* token_rows, const void* plan, void* stream);
 
 /* Bytes of device workspace mb_alibi_attn_fwd / mb_alibi_attn_bwd need for these sizes (0 on invalid sizes; the
  * forward's is also 0 when it needs none). */
@@ -191,6 +208,8 @@ MB_API size_t mb_alibi_attn_bwd_workspace_bytes(int B, int T, int max_seqlen, in
  *   dq, dk, dv   dev, [T, H, D] with row strides dq/dk/dv_row_stride, written (rows [0, T)).
  *   workspace    dev, at least mb_alibi_attn_bwd_workspace_bytes(...) bytes, scratch.
  *   key_lens     as in the forward (NULL or [B]); tokens that are no keys get zero rows of dk and dv.
+ *   plan         as in the forward (NULL or from mb_attn_plan); the workspace then only needs the [H, T] floats
+ *                of Delta.
  *   token_rows   as in the forward; applies to dout, q, k, v, o, dq, dk and dv alike.
  * Deterministic: no atomics; two calls on the same inputs give identical bits.
  * A sequence longer than max_seqlen is skipped as in the forward (its rows of dq, dk, dv are left untouched, the
@@ -204,7 +223,7 @@ MB_API mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* 
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, void* workspace,
                             size_t workspace_bytes, const int32_t* key_lens, const int32_t* token_rows,
-                            void* stream);
+                            const void* plan, void* stream);
 
 /*
  * The backward attention for callers that cannot allocate device memory or bring a workspace: code under HIP
@@ -226,7 +245,7 @@ MB_API mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale,
                             mb_dtype dt, void* dq, void* dk, void* dv, int64_t dq_row_stride,
                             int64_t dk_row_stride, int64_t dv_row_stride, const int32_t* key_lens,
-                            const int32_t* token_rows, void* stream);
+                            const int32_t* token_rows, const void* plan, void* stream);
 
 /*
  * Reads and clears the current device's sticky misuse word.  Synchronises `stream`.

@@ -26,7 +26,7 @@ EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "
            "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
            "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling",
-           "mb_alibi_attn_bwd_static", "mb_device_status")
+           "mb_alibi_attn_bwd_static", "mb_device_status", "mb_attn_plan_bytes", "mb_attn_plan")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -47,18 +47,23 @@ _lib.mb_zero_padding.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int,
 _lib.mb_alibi_attn_fwd.restype = c_int
 _lib.mb_alibi_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int, c_int,
                                    c_int, c_int, c_int, c_void_p, c_float, c_int, c_void_p, c_int64, c_void_p,
-                                   c_void_p, c_size_t, c_void_p, c_void_p, c_void_p]
+                                   c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.mb_attn_plan_bytes.restype = c_size_t
+_lib.mb_attn_plan_bytes.argtypes = [c_int, c_int, c_int]
+_lib.mb_attn_plan.restype = c_int
+_lib.mb_attn_plan.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_size_t, c_void_p]
 _lib.mb_alibi_attn_fwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_fwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd_workspace_bytes.restype = c_size_t
 _lib.mb_alibi_attn_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
 _lib.mb_alibi_attn_bwd.restype = c_int
 _lib.mb_alibi_attn_bwd.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5 + [c_void_p, c_float, c_int]
-                                   + [c_void_p] * 3 + [c_int64] * 3 + [c_void_p, c_size_t, c_void_p, c_void_p, c_void_p])
+                                   + [c_void_p] * 3 + [c_int64] * 3
+                                   + [c_void_p, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p])
 _lib.mb_alibi_attn_bwd_static.restype = c_int
 _lib.mb_alibi_attn_bwd_static.argtypes = ([c_void_p] * 6 + [c_int64] * 5 + [c_void_p] + [c_int] * 5
                                           + [c_void_p, c_float, c_int] + [c_void_p] * 3 + [c_int64] * 3
-                                          + [c_void_p, c_void_p, c_void_p])
+                                          + [c_void_p, c_void_p, c_void_p, c_void_p])
 _lib.mb_device_status.restype = c_int
 _lib.mb_device_status.argtypes = [c_void_p]
 MB_STATIC_SCRATCH_BYTES = 16 << 20
@@ -192,7 +197,7 @@ def mb_zero_padding(padded: torch.Tensor, indices: torch.Tensor, T_cap: int, met
 
 
 def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float, out=None, lse=None,
-                      token_rows=None, T=None, workspace=None, key_lens=None):
+                      token_rows=None, T=None, workspace=None, key_lens=None, plan=None):
     """q, k, v: [T, H, D] views (token stride free).  Returns (o [T, H, D], lse [H, T] float32).
     With token_rows the views are over a padded batch ([B*L, H, D]) and T (the lse pitch) must be given."""
     _, H, D = q.shape
@@ -202,15 +207,29 @@ def mb_alibi_attn_fwd(q, k, v, cu_seqlens, max_seqlen: int, slopes, softmax_scal
         out = torch.empty((q.shape[0], H, D), dtype=q.dtype, device=q.device)
     if lse is None:
         lse = torch.empty((H, T), dtype=torch.float32, device=q.device)
-    need = mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, _dtype_code(q))
+    need = 0 if plan is not None else mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, _dtype_code(q))
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     _check(_lib.mb_alibi_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _row_stride(q), _row_stride(k), _row_stride(v),
                                   _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
                                   _dtype_code(q), _ptr(out), _row_stride(out), _ptr(lse), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _ptr(key_lens), _ptr(token_rows),
-                                  _stream()))
+                                  _ptr(plan), _stream()))
     return out, lse
+
+
+def mb_attn_plan_bytes(B: int, max_seqlen: int, H: int) -> int:
+    return int(_lib.mb_attn_plan_bytes(B, max_seqlen, H))
+
+
+def mb_attn_plan(cu_seqlens, max_seqlen: int, H: int, key_lens=None, plan=None):
+    """Builds the work plan of the any-length attention kernels once for a batch; returns the plan buffer."""
+    B = cu_seqlens.numel() - 1
+    need = mb_attn_plan_bytes(B, max_seqlen, H)
+    if plan is None:
+        plan = torch.empty(max(need, 16), dtype=torch.uint8, device=cu_seqlens.device)
+    _check(_lib.mb_attn_plan(_ptr(cu_seqlens), _ptr(key_lens), B, max_seqlen, H, _ptr(plan), plan.numel(), _stream()))
+    return plan
 
 
 def mb_alibi_attn_fwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int:
@@ -222,7 +241,7 @@ def mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dtype_code) -> int
 
 
 def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
-                      dq=None, dk=None, dv=None, workspace=None, token_rows=None, T=None, key_lens=None):
+                      dq=None, dk=None, dv=None, workspace=None, token_rows=None, T=None, key_lens=None, plan=None):
     """Returns (dq, dk, dv), each [T, H, D] (padded-batch views when token_rows is given)."""
     R, H, D = q.shape
     T = R if T is None else T
@@ -237,12 +256,13 @@ def mb_alibi_attn_bwd(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes
                                   _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o), _ptr(cu_seqlens),
                                   B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale), _dtype_code(q),
                                   _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq), _row_stride(dk), _row_stride(dv),
-                                  _ptr(workspace), workspace.numel(), _ptr(key_lens), _ptr(token_rows), _stream()))
+                                  _ptr(workspace), workspace.numel(), _ptr(key_lens), _ptr(token_rows), _ptr(plan),
+                                  _stream()))
     return dq, dk, dv
 
 
 def mb_alibi_attn_bwd_static(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int, slopes, softmax_scale: float,
-                             dq, dk, dv, token_rows=None, T=None, key_lens=None):
+                             dq, dk, dv, token_rows=None, T=None, key_lens=None, plan=None):
     """mb_alibi_attn_bwd on the library's static scratch array.  This wrapper allocates nothing either:
     the outputs dq, dk, dv must be given."""
     R, H, D = q.shape
@@ -252,7 +272,8 @@ def mb_alibi_attn_bwd_static(dout, q, k, v, o, lse, cu_seqlens, max_seqlen: int,
                                          _row_stride(q), _row_stride(k), _row_stride(v), _row_stride(o),
                                          _ptr(cu_seqlens), B, T, max_seqlen, H, D, _ptr(slopes), float(softmax_scale),
                                          _dtype_code(q), _ptr(dq), _ptr(dk), _ptr(dv), _row_stride(dq),
-                                         _row_stride(dk), _row_stride(dv), _ptr(key_lens), _ptr(token_rows), _stream()))
+                                         _row_stride(dk), _row_stride(dv), _ptr(key_lens), _ptr(token_rows), _ptr(plan),
+                                         _stream()))
     return dq, dk, dv
 
 

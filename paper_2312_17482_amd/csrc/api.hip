@@ -304,11 +304,37 @@ mb_status mb_add_layernorm_bwd(const void* dy, const void* s, const void* gamma,
                                   (float*)workspace, dy_rows, (hipStream_t)stream);
 }
 
+size_t mb_attn_plan_bytes(int B, int max_seqlen, int H) {
+  if (B < 0 || max_seqlen < 0 || H <= 0 || H > 65535 || (int64_t)B * H >= ((int64_t)1 << 30) || max_seqlen >= (1 << 22)) return 0;
+  return attn_plan_workspace_bytes(B, max_seqlen, H);
+}
+
+mb_status mb_attn_plan(const int32_t* cu_seqlens, const int32_t* key_lens, int B, int max_seqlen, int H, void* plan,
+                       size_t plan_bytes, void* stream) {
+  clear_error();
+  MB_REQUIRE(B >= 0 && max_seqlen >= 0, MB_ERR_INVALID_ARG, "negative size (B=%d max_seqlen=%d)", B, max_seqlen);
+  MB_REQUIRE(H > 0, MB_ERR_INVALID_ARG, "H=%d must be positive", H);
+  MB_REQUIRE(H <= 65535 && B <= 65535, MB_ERR_UNSUPPORTED, "B=%d or H=%d exceeds 65535", B, H);
+  MB_REQUIRE((int64_t)B * H < ((int64_t)1 << 30), MB_ERR_UNSUPPORTED, "B*H=%lld exceeds 2^30", (long long)B * H);
+  MB_REQUIRE(max_seqlen < (1 << 22), MB_ERR_UNSUPPORTED, "max_seqlen=%d exceeds 2^22", max_seqlen);
+  const size_t need = attn_plan_workspace_bytes(B, max_seqlen, H);
+  MB_REQUIRE(plan != nullptr && plan_bytes >= need, MB_ERR_WORKSPACE, "plan of %zu bytes given, %zu needed",
+             plan ? plan_bytes : (size_t)0, need);
+  MB_REQUIRE(aligned16(plan), MB_ERR_INVALID_ARG, "plan is not 16-byte aligned");
+  MB_CHECK_PTR(cu_seqlens);
+  MB_REQUIRE((reinterpret_cast<uintptr_t>(key_lens) & 3u) == 0, MB_ERR_INVALID_ARG, "key_lens is not 4-byte aligned");
+  int32_t* misuse = nullptr;
+  const mb_status st = misuse_flag_address(&misuse);
+  if (st != MB_OK) return st;
+  const AttnShape s{B, 0, max_seqlen, H, 64, cu_seqlens, nullptr, 0.f, key_lens, nullptr, nullptr, misuse};
+  return launch_attn_plan(s, static_cast<int32_t*>(plan), nullptr, (hipStream_t)stream);
+}
+
 mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t q_row_stride,
                             int64_t k_row_stride, int64_t v_row_stride, const int32_t* cu_seqlens, int B, int T,
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                             void* o, int64_t o_row_stride, float* lse, void* workspace, size_t workspace_bytes,
-                            const int32_t* key_lens, const int32_t* token_rows, void* stream) {
+                            const int32_t* key_lens, const int32_t* token_rows, const void* plan, void* stream) {
   clear_error();
   mb_status st = check_attn_dims(B, T, max_seqlen, H, D, dt);
   if (st != MB_OK) return st;
@@ -334,14 +360,16 @@ mb_status mb_alibi_attn_fwd(const void* q, const void* k, const void* v, int64_t
   MB_REQUIRE(key_lens == nullptr || mfma, MB_ERR_UNSUPPORTED,
              "key_lens is served by the matrix-core kernels only (bf16, head_dim 64, softmax_scale > 0)");
   MB_REQUIRE((reinterpret_cast<uintptr_t>(key_lens) & 3u) == 0, MB_ERR_INVALID_ARG, "key_lens is not 4-byte aligned");
-  const size_t need = mfma ? attn_fwd_mfma_workspace_bytes(B, max_seqlen, H) : 0;
+  MB_REQUIRE(plan == nullptr || aligned16(plan), MB_ERR_INVALID_ARG, "plan is not 16-byte aligned");
+  const size_t need = (mfma && plan == nullptr) ? attn_fwd_mfma_workspace_bytes(B, max_seqlen, H) : 0;
   MB_REQUIRE(need == 0 || (workspace != nullptr && workspace_bytes >= need), MB_ERR_WORKSPACE,
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   MB_REQUIRE(need == 0 || aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
   int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
   st = misuse_flag_address(&misuse);
   if (st != MB_OK) return st;
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows, misuse};
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows,
+                    static_cast<const int32_t*>(plan), misuse};
   if (mfma)
     return launch_attn_fwd_mfma(s, q, k, v, q_row_stride, k_row_stride, v_row_stride, o, o_row_stride, lse,
                                 workspace, (hipStream_t)stream);
@@ -370,7 +398,7 @@ static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k
                                   int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                                   void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
                                   int64_t dv_row_stride, void* workspace, const int32_t* key_lens,
-                                  const int32_t* token_rows, void* stream) {
+                                  const int32_t* token_rows, const void* plan, void* stream) {
   const bool mfma = use_mfma(dt, D, softmax_scale);
   MB_REQUIRE(mfma || max_seqlen <= kGenericMaxSeqlen, MB_ERR_UNSUPPORTED,
              "max_seqlen=%d exceeds %d for this dtype/head_dim", max_seqlen, kGenericMaxSeqlen);
@@ -380,7 +408,8 @@ static mb_status attn_bwd_checked(const void* dout, const void* q, const void* k
   int32_t* misuse = nullptr;   // (first thing that touches the GPU: everything above is testable without one)
   const mb_status st = misuse_flag_address(&misuse);
   if (st != MB_OK) return st;
-  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows, misuse};
+  const AttnShape s{B, T, max_seqlen, H, D, cu_seqlens, slopes, softmax_scale, key_lens, token_rows,
+                    static_cast<const int32_t*>(plan), misuse};
   if (mfma)
     return launch_attn_bwd_mfma(s, dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                 o_row_stride, dq, dk, dv, dq_row_stride, dk_row_stride, dv_row_stride,
@@ -436,20 +465,22 @@ mb_status mb_alibi_attn_bwd(const void* dout, const void* q, const void* k, cons
                             int max_seqlen, int H, int D, const float* slopes, float softmax_scale, mb_dtype dt,
                             void* dq, void* dk, void* dv, int64_t dq_row_stride, int64_t dk_row_stride,
                             int64_t dv_row_stride, void* workspace, size_t workspace_bytes,
-                            const int32_t* key_lens, const int32_t* token_rows, void* stream) {
+                            const int32_t* key_lens, const int32_t* token_rows, const void* plan, void* stream) {
   clear_error();
   bool empty = false;
   const mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                          o_row_stride, cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq,
                                          dk, dv, dq_row_stride, dk_row_stride, dv_row_stride, token_rows, &empty);
   if (st != MB_OK || empty) return st;
-  const size_t need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
+  MB_REQUIRE(plan == nullptr || aligned16(plan), MB_ERR_INVALID_ARG, "plan is not 16-byte aligned");
+  // with a plan of the caller's only Delta needs room
+  const size_t need = plan ? attn_bwd_delta_bytes(H, T) : mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
   MB_REQUIRE(workspace != nullptr && workspace_bytes >= need, MB_ERR_WORKSPACE,
              "workspace of %zu bytes given, %zu needed", workspace ? workspace_bytes : (size_t)0, need);
   MB_REQUIRE(aligned16(workspace), MB_ERR_INVALID_ARG, "workspace is not 16-byte aligned");
   return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
                           cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
-                          dk_row_stride, dv_row_stride, workspace, key_lens, token_rows, stream);
+                          dk_row_stride, dv_row_stride, workspace, key_lens, token_rows, plan, stream);
 }
 
 mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* k, const void* v, const void* o,
@@ -458,14 +489,15 @@ mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* 
                                    const int32_t* cu_seqlens, int B, int T, int max_seqlen, int H, int D,
                                    const float* slopes, float softmax_scale, mb_dtype dt, void* dq, void* dk, void* dv,
                                    int64_t dq_row_stride, int64_t dk_row_stride, int64_t dv_row_stride,
-                                   const int32_t* key_lens, const int32_t* token_rows, void* stream) {
+                                   const int32_t* key_lens, const int32_t* token_rows, const void* plan, void* stream) {
   clear_error();
   bool empty = false;
   mb_status st = attn_bwd_validate(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride,
                                    o_row_stride, cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk,
                                    dv, dq_row_stride, dk_row_stride, dv_row_stride, token_rows, &empty);
   if (st != MB_OK || empty) return st;
-  const size_t need = mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
+  MB_REQUIRE(plan == nullptr || aligned16(plan), MB_ERR_INVALID_ARG, "plan is not 16-byte aligned");
+  const size_t need = plan ? attn_bwd_delta_bytes(H, T) : mb_alibi_attn_bwd_workspace_bytes(B, T, max_seqlen, H, D, dt);
   MB_REQUIRE(need <= kStaticScratchBytes, MB_ERR_WORKSPACE,
              "these sizes need %zu bytes of scratch, the static array holds %zu: use mb_alibi_attn_bwd with a "
              "workspace of the caller's", need, kStaticScratchBytes);
@@ -476,7 +508,7 @@ mb_status mb_alibi_attn_bwd_static(const void* dout, const void* q, const void* 
   // tokens, the sequence order) is written earlier in the same call.
   return attn_bwd_checked(dout, q, k, v, o, lse, do_row_stride, q_row_stride, k_row_stride, v_row_stride, o_row_stride,
                           cu_seqlens, B, T, max_seqlen, H, D, slopes, softmax_scale, dt, dq, dk, dv, dq_row_stride,
-                          dk_row_stride, dv_row_stride, ws, key_lens, token_rows, stream);
+                          dk_row_stride, dv_row_stride, ws, key_lens, token_rows, plan, stream);
 }
 
 mb_status mb_device_status(void* stream) {

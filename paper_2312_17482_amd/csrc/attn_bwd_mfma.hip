@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __r
                                                              int64_t plan_cap, int32_t* __restrict__ plan,
                                                              int32_t* __restrict__ misuse,
                                                              const int32_t* __restrict__ key_lens) {
-  if (blockIdx.x < kPlanXcds) {
+  if (plan != nullptr && blockIdx.x < kPlanXcds) {   // (NULL: the caller brought a plan)
     __shared__ __attribute__((aligned(16))) PlanLds lds;
     build_plan_list(cu, key_lens, B, H, max_seqlen, plan_cap, plan, blockIdx.x, misuse, lds);
   }
@@ -835,11 +835,13 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   // the work plan sits behind Delta in the workspace
   const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
   if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
-  int32_t* plan = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T));
+  int32_t* own_plan = s.plan ? nullptr
+                             : reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T));
+  const int32_t* plan = s.plan ? s.plan : own_plan;
   const int64_t delta_blocks = (rows + 31) / 32;
   hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)(delta_blocks > kPlanXcds ? delta_blocks : kPlanXcds)),
                      dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens,
-                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, plan, s.misuse, s.key_lens);
+                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, own_plan, s.misuse, s.key_lens);
   mb_status st = check_launch("attn_bwd_delta_kernel");
   if (st != MB_OK) return st;
   // buffer-load path: a sequence's rows within 2^31 bytes of its first

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kPlanThreads) void attn_plan_kernel(const int32_t* 
                                                                  int T) {
   __shared__ __attribute__((aligned(16))) PlanLds lds;
   build_plan_list(cu, key_lens, B, H, max_seqlen, cap, plan, blockIdx.x, misuse, lds);
-  if (blockIdx.x != 0) return;
+  if (blockIdx.x != 0 || lse == nullptr) return;
   for (int b = 0; b < B; ++b) {
     const int s0 = cu[b], len = cu[b + 1] - s0;
     if (len > max_seqlen)
@@ -524,11 +524,12 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
   // any length: plan (8 small workgroups), then one workgroup per plan slot
   const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
   if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
-  int32_t* plan = static_cast<int32_t*>(workspace);
-  hipLaunchKernelGGL(attn_plan_kernel, dim3(kPlanXcds), dim3(kPlanThreads), 0, stream, s.cu_seqlens, s.key_lens, s.B, s.H,
-                     s.max_seqlen, cap, plan, s.misuse, lse, s.T);
-  mb_status st = check_launch("attn_plan_kernel");
-  if (st != MB_OK) return st;
+  const int32_t* plan = s.plan;
+  if (plan == nullptr) {   // no plan of the caller's: build one in the workspace
+    const mb_status st = launch_attn_plan(s, static_cast<int32_t*>(workspace), lse, stream);
+    if (st != MB_OK) return st;
+    plan = static_cast<const int32_t*>(workspace);
+  }
   // buffer-load path: a sequence's K / V rows within 2^31 bytes of its first
   const int64_t span = (int64_t)s.max_seqlen * (ks > vs ? ks : vs) * 2;
 #define MB_LAUNCH_TILED(M)                                                                                         \
@@ -544,6 +545,14 @@ mb_status launch_attn_fwd_mfma(const AttnShape& s, const void* q, const void* k,
 
 size_t attn_fwd_mfma_workspace_bytes(int B, int max_seqlen, int H) {
   return max_seqlen <= kBlockK ? 0 : attn_plan_bytes(B, max_seqlen, H);
+}
+
+size_t attn_plan_workspace_bytes(int B, int max_seqlen, int H) { return attn_plan_bytes(B, max_seqlen, H); }
+
+mb_status launch_attn_plan(const AttnShape& s, int32_t* plan, float* lse, hipStream_t stream) {
+  hipLaunchKernelGGL(attn_plan_kernel, dim3(kPlanXcds), dim3(kPlanThreads), 0, stream, s.cu_seqlens, s.key_lens, s.B, s.H,
+                     s.max_seqlen, attn_plan_cap(s.B, s.max_seqlen, s.H), plan, s.misuse, lse, s.T);
+  return check_launch("attn_plan_kernel");
 }
 
 }  // namespace mb

@@ -73,26 +73,38 @@ __device__ inline void build_plan_list(const int32_t* __restrict__ cu, const int
     const int nb = min(kSortMaxB, B - r0);
     __syncthreads();   // previous pass is done with the staging arrays; L.carry is visible
     if (B <= kSortMaxB) {
-      // rank by (length, reversed index): longest first, ties by index
+      // rank by (length, reversed index): longest first, ties by index.  Global memory is read once (all loads of
+      // a thread in flight together); the ranking then works from LDS and registers.
       const int Bp = (B + 15) & ~15;
-      for (int i = tid; i < Bp; i += kPlanThreads) {
-        const int s0 = cu[min(i, B)], s1 = cu[min(i + 1, B)];
-        L.keys[i] = i < B ? ((uint32_t)min(s1 - s0, (1 << 22)) << 9) | (uint32_t)(kSortMaxB - 1 - i) : 0u;
+      int my_s0[kSortMaxB / kPlanThreads], my_len[kSortMaxB / kPlanThreads], my_kl[kSortMaxB / kPlanThreads];
+#pragma unroll
+      for (int u = 0; u < kSortMaxB / kPlanThreads; ++u) {
+        const int i = tid + u * kPlanThreads;
+        my_s0[u] = my_len[u] = my_kl[u] = 0;
+        if (i < Bp) {
+          const int s0 = cu[min(i, B)], s1 = cu[min(i + 1, B)];
+          const int kl = (key_lens && i < B) ? key_lens[i] : (1 << 30);
+          my_s0[u] = s0;
+          my_len[u] = s1 - s0;
+          my_kl[u] = min(kl, s1 - s0);
+          L.keys[i] = i < B ? ((uint32_t)min(s1 - s0, (1 << 22)) << 9) | (uint32_t)(kSortMaxB - 1 - i) : 0u;
+        }
       }
       __syncthreads();
-      for (int cand = tid; cand < B; cand += kPlanThreads) {
-        const uint32_t mine = L.keys[cand];
-        int r = 0;
-        for (int other = 0; other < Bp; other += 4) {
-          const uint4 k4 = *reinterpret_cast<const uint4*>(&L.keys[other]);
-          r += (k4.x > mine ? 1 : 0) + (k4.y > mine ? 1 : 0) + (k4.z > mine ? 1 : 0) + (k4.w > mine ? 1 : 0);
+#pragma unroll
+      for (int u = 0; u < kSortMaxB / kPlanThreads; ++u) {
+        const int cand = tid + u * kPlanThreads;
+        if (cand < B) {
+          const uint32_t mine = L.keys[cand];
+          int r = 0;
+          for (int other = 0; other < Bp; other += 4) {
+            const uint4 k4 = *reinterpret_cast<const uint4*>(&L.keys[other]);
+            r += (k4.x > mine ? 1 : 0) + (k4.y > mine ? 1 : 0) + (k4.z > mine ? 1 : 0) + (k4.w > mine ? 1 : 0);
+          }
+          L.start[r] = my_s0[u];
+          L.len[r] = my_kl[u] > 0 ? my_len[u] : 0;   // no keys: nothing to compute
+          L.klen[r] = my_kl[u];
         }
-        const int s0 = cu[cand];
-        const int len = cu[cand + 1] - s0;
-        const int kl = key_lens ? min(key_lens[cand], len) : len;
-        L.start[r] = s0;
-        L.len[r] = kl > 0 ? len : 0;   // no keys: nothing to compute
-        L.klen[r] = kl;
       }
     } else {
       for (int i = tid; i < nb; i += kPlanThreads) {

@@ -23,6 +23,7 @@ struct AttnShape {
   float scale;
   const int32_t* key_lens;     // NULL, or [B]: only the first key_lens[b] tokens of sequence b act as keys
   const int32_t* token_rows;   // NULL, or [T]: row of token t inside the activation buffers
+  const int32_t* plan;         // NULL, or a work plan the caller built with mb_attn_plan for these very arguments
   int32_t* misuse;             // this device's sticky flag: set by a kernel that meets a sequence longer than max_seqlen
 };
 
@@ -57,6 +58,10 @@ __host__ __device__ inline size_t attn_bwd_delta_bytes(int H, int T) {
 }
 size_t attn_fwd_mfma_workspace_bytes(int B, int max_seqlen, int H);
 size_t attn_bwd_mfma_workspace_bytes(int B, int T, int max_seqlen, int H);
+// The work plan of the any-length kernels (see attn_plan.h): its size, and the launch that builds it.  `lse` non-NULL:
+// the log-sum-exp rows ([H, T]) of sequences the plan skips as longer than max_seqlen are set to NaN.
+size_t attn_plan_workspace_bytes(int B, int max_seqlen, int H);
+mb_status launch_attn_plan(const AttnShape& s, int32_t* plan, float* lse, hipStream_t stream);
 
 // ---- launchers (each enqueues on `stream`, returns MB_OK or MB_ERR_HIP) ----
 mb_status launch_unpad_index(const int32_t* mask, int B, int L, int32_t* seqlens, int32_t* cu_seqlens,

@@ -46,20 +46,21 @@ def test_slopes_against_fixture():
 
 def fwd_args(**over):
     a = dict(q=A, k=A, v=A, qs=768, ks=768, vs=768, cu=A, B=2, T=64, max_seqlen=32, H=12, D=64, slopes=A,
-             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, ws=None, wsb=0, klens=None, rows=None, stream=None)
+             scale=0.125, dt=mb.MB_BF16, o=A, os=768, lse=A, ws=None, wsb=0, klens=None, rows=None, plan=None,
+             stream=None)
     a.update(over)
     return [a[x] for x in ("q", "k", "v", "qs", "ks", "vs", "cu", "B", "T", "max_seqlen", "H", "D", "slopes", "scale",
-                           "dt", "o", "os", "lse", "ws", "wsb", "klens", "rows", "stream")]
+                           "dt", "o", "os", "lse", "ws", "wsb", "klens", "rows", "plan", "stream")]
 
 
 def bwd_args(**over):
     a = dict(do=A, q=A, k=A, v=A, o=A, lse=A, dos=768, qs=768, ks=768, vs=768, os=768, cu=A, B=2, T=64,
              max_seqlen=32, H=12, D=64, slopes=A, scale=0.125, dt=mb.MB_BF16, dq=A, dk=A, dv=A, dqs=768, dks=768,
-             dvs=768, ws=A, wsb=1 << 20, klens=None, rows=None, stream=None)
+             dvs=768, ws=A, wsb=1 << 20, klens=None, rows=None, plan=None, stream=None)
     a.update(over)
     return [a[x] for x in ("do", "q", "k", "v", "o", "lse", "dos", "qs", "ks", "vs", "os", "cu", "B", "T",
                            "max_seqlen", "H", "D", "slopes", "scale", "dt", "dq", "dk", "dv", "dqs", "dks", "dvs",
-                           "ws", "wsb", "klens", "rows", "stream")]
+                           "ws", "wsb", "klens", "rows", "plan", "stream")]
 
 
 @pytest.mark.parametrize("over,status,needle", [
@@ -83,6 +84,7 @@ def bwd_args(**over):
     (dict(max_seqlen=512, ws=A + 4, wsb=1 << 20), mb.MB_ERR_INVALID_ARG, "workspace is not 16-byte"),
     (dict(max_seqlen=1 << 23), mb.MB_ERR_UNSUPPORTED, "2^22"),
     (dict(klens=A + 2), mb.MB_ERR_INVALID_ARG, "key_lens is not 4-byte"),
+    (dict(plan=A + 8), mb.MB_ERR_INVALID_ARG, "plan is not 16-byte"),
     (dict(klens=A, dt=mb.MB_F32, D=16, H=2, qs=32, ks=32, vs=32, os=32), mb.MB_ERR_UNSUPPORTED, "key_lens"),
 ])
 def test_fwd_rejects_bad_arguments_without_launching(over, status, needle):
@@ -131,6 +133,21 @@ def test_degenerate_sizes_are_ok_and_touch_nothing():
     assert mb.mb_last_error() == ""
     assert lib.mb_unpad(None, None, 0, None, 768, mb.MB_BF16, None, None) == mb.MB_OK
     assert lib.mb_pad(None, None, 0, None, 0, 128, 768, mb.MB_BF16, None, None) == mb.MB_OK
+
+
+def test_plan_rejects_bad_arguments_without_launching():
+    need = mb.mb_attn_plan_bytes(64, 512, 12)
+    assert need >= 64 * 12 * 4 * 16 and need % 256 == 0 and mb.mb_attn_plan_bytes(64, 512, 0) == 0
+    assert need == mb.mb_alibi_attn_fwd_workspace_bytes(64, 32768, 512, 12, 64, mb.MB_BF16)
+    for args, status, needle in (((None, None, 64, 512, 12, A, need, None), mb.MB_ERR_INVALID_ARG, "cu_seqlens is NULL"),
+                                 ((A, None, 64, 512, 12, None, need, None), mb.MB_ERR_WORKSPACE, "needed"),
+                                 ((A, None, 64, 512, 12, A, need - 1, None), mb.MB_ERR_WORKSPACE, "needed"),
+                                 ((A, None, 64, 512, 12, A + 8, need, None), mb.MB_ERR_INVALID_ARG, "16-byte"),
+                                 ((A, A + 2, 64, 512, 12, A, need, None), mb.MB_ERR_INVALID_ARG, "key_lens"),
+                                 ((A, None, 64, 512, 0, A, need, None), mb.MB_ERR_INVALID_ARG, "positive"),
+                                 ((A, None, -1, 512, 12, A, need, None), mb.MB_ERR_INVALID_ARG, "negative")):
+        assert lib.mb_attn_plan(*args) == status
+        assert needle in mb.mb_last_error()
 
 
 def test_workspace_query():

@@ -489,6 +489,43 @@ def test_padded_batch_with_key_mask_equals_the_oracle_on_real_tokens(mb, L, leng
             assert np.all(got["dk"][b, n:] == 0) and np.all(got["dv"][b, n:] == 0) and np.all(got["dq"][b, n:] == 0)
 
 
+@pytest.mark.parametrize("limit_keys", [False, True])
+def test_plan_built_once_gives_the_same_bits_as_plans_built_per_call(mb, limit_keys):
+    """mb_attn_plan once per batch, then forward and backward with `plan`: bit for bit what the calls give when
+    each builds its own plan (any-length kernels; with and without key_lens), with no forward workspace and a
+    backward workspace that only holds Delta."""
+    lengths = [700, 129, 300, 64, 1, 0, 512, 257, 640]
+    L, H, D = 700, 3, 64
+    c = wl.random_attention_case(97, lengths, L, H, D, std=0.5, bf16=True)
+    B = len(lengths)
+    seqlens, cu, indices, meta = mb.mb_unpad_index(torch.from_numpy(c["mask"]).cuda())
+    T, mx = mb.mb_read_meta(meta)
+    qkv = mb.mb_unpad(to_dev(np.stack([c["q"], c["k"], c["v"]], axis=2).reshape(B * L, 3 * H * D), True), indices,
+                      B * L, meta)[:T].view(T, 3, H, D)
+    dout = mb.mb_unpad(to_dev(c["do"].reshape(B * L, H * D), True), indices, B * L, meta)[:T].view(T, H, D)
+    slopes = mb.mb_alibi_slopes(H).cuda()
+    klens = torch.tensor([max(1, n // 2) for n in lengths], dtype=torch.int32, device="cuda") if limit_keys else None
+    o1, lse1 = mb.mb_alibi_attn_fwd(qkv[:, 0], qkv[:, 1], qkv[:, 2], cu, mx, slopes, c["scale"], key_lens=klens)
+    g1 = torch.zeros((T, 3, H, D), dtype=torch.bfloat16, device="cuda")
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o1, lse1, cu, mx, slopes, c["scale"], dq=g1[:, 0],
+                         dk=g1[:, 1], dv=g1[:, 2], key_lens=klens)
+    plan = mb.mb_attn_plan(cu, mx, H, key_lens=klens)
+    lib = mb.raw()
+    o2 = torch.zeros_like(o1)
+    lse2 = torch.zeros_like(lse1)
+    st = lib.mb_alibi_attn_fwd(qkv[:, 0].data_ptr(), qkv[:, 1].data_ptr(), qkv[:, 2].data_ptr(), 3 * H * D, 3 * H * D,
+                               3 * H * D, cu.data_ptr(), B, T, mx, H, D, slopes.data_ptr(), float(c["scale"]), mb.MB_BF16,
+                               o2.data_ptr(), H * D, lse2.data_ptr(), None, 0, None if klens is None else klens.data_ptr(),
+                               None, plan.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert st == mb.MB_OK, mb.mb_last_error()       # no workspace at all
+    g2 = torch.zeros_like(g1)
+    ws = torch.empty(H * T * 4 + 256, dtype=torch.uint8, device="cuda")               # Delta only
+    mb.mb_alibi_attn_bwd(dout, qkv[:, 0], qkv[:, 1], qkv[:, 2], o2, lse2, cu, mx, slopes, c["scale"], dq=g2[:, 0],
+                         dk=g2[:, 1], dv=g2[:, 2], key_lens=klens, plan=plan, workspace=ws)
+    mb.mb_device_status()
+    assert torch.equal(o1, o2) and torch.equal(lse1, lse2) and torch.equal(g1, g2)
+
+
 def test_bf16_tile_boundary_lengths(mb):
     """Lengths on both sides of every tile boundary of the any-length kernels (32, 64, 128) in one batch."""
     lengths = [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 2, 0]

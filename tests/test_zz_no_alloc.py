@@ -37,7 +37,7 @@ def _both(mb, c, cu, T, mx, qkv, dout, H):
         dout.data_ptr(), qkv[:, 0].data_ptr(), qkv[:, 1].data_ptr(), qkv[:, 2].data_ptr(), o.data_ptr(), lse.data_ptr(),
         H * 64, 3 * H * 64, 3 * H * 64, 3 * H * 64, H * 64, cu.data_ptr(), B, T, mx, H, 64, slopes.data_ptr(),
         float(c["scale"]), mb.MB_BF16, got[:, 0].data_ptr(), got[:, 1].data_ptr(), got[:, 2].data_ptr(),
-        3 * H * 64, 3 * H * 64, 3 * H * 64, None, None, torch.cuda.current_stream().cuda_stream)
+        3 * H * 64, 3 * H * 64, 3 * H * 64, None, None, None, torch.cuda.current_stream().cuda_stream)
     assert st == mb.MB_OK, mb.mb_last_error()
     torch.cuda.synchronize()
     assert torch.equal(got, ref), "static-scratch backward differs from the workspace backward"
