@@ -6,15 +6,15 @@
 //   Delta_i = dO_i . O_i,  P_ij = exp(S_ij - lse_i),  dV_j = sum_i P_ij dO_i,  dP_ij = dO_i . v_j,
 //   dS_ij = P_ij (dP_ij - Delta_i),  dQ_i = scale sum_j dS_ij k_j,  dK_j = scale sum_i dS_ij q_i.
 //
-// Three kernels, no atomics (results are bitwise reproducible):
-//   delta : Delta = rowsum(dO * O), [H, T] float.
+// Two kernels for any length, no atomics (results are bitwise reproducible):
+//   dq    : one workgroup per (sequence, head, 128 queries); wave w owns 32 queries and streams all keys.
+//           Transposed scores S^T = K Q^T (as in the forward) so that dS^T is directly the B operand
+//           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.  It runs first and also
+//           computes Delta = rowsum(dO * O) of its queries (it holds their dO rows anyway) into [H, T] floats.
 //   dkv   : one workgroup per (sequence, head, 128 keys); wave w owns 32 keys and streams all queries.
 //           Scores in natural orientation S = Q K^T (queries along accumulator rows, keys along
 //           lanes) so that P and dS, rounded to bf16, are directly the B operands of
-//           dV^T += dO^T P and dK^T += Q^T dS.
-//   dq    : one workgroup per (sequence, head, 128 queries); wave w owns 32 queries and streams all keys.
-//           Transposed scores S^T = K Q^T (as in the forward) so that dS^T is directly the B operand
-//           of dQ^T += K^T dS^T, and lse_i / Delta_i are per-lane scalars.
+//           dV^T += dO^T P and dK^T += Q^T dS.  Reads the Delta the first kernel left.
 // Masking costs nothing: rows beyond the sequence end are staged as zeros and their lse as +inf
 // (P = 0); zero K/V rows make the products with out-of-range keys vanish.
 #include "attn_plan.h"
@@ -28,52 +28,11 @@ constexpr int kD = 64;
 constexpr int kTile = 128;
 constexpr int kPitch = 72;   // LDS row pitch in bf16 (144 B)
 
-// ------------------------------------------------------------------------------------------------ delta
-// 8 lanes per (token, head) row: 16 bytes of dO and O each, then a 3-step butterfly.
-//
-// The first eight workgroups also build the work plan of the two kernels that follow (one list each; see
-// attn_plan.h) before they take their share of rows.
-__global__ __launch_bounds__(256) void attn_bwd_delta_kernel(const uint16_t* __restrict__ dout,
-                                                             const uint16_t* __restrict__ o, int64_t dos, int64_t os,
-                                                             int T, int H, const int32_t* __restrict__ cu, int B,
-                                                             float* __restrict__ delta,
-                                                             const int32_t* __restrict__ rows, int max_seqlen,
-                                                             int64_t plan_cap, int32_t* __restrict__ plan,
-                                                             int32_t* __restrict__ misuse,
-                                                             const int32_t* __restrict__ key_lens) {
-  if (plan != nullptr && blockIdx.x < kPlanXcds) {   // (NULL: the caller brought a plan)
-    __shared__ __attribute__((aligned(16))) PlanLds lds;
-    build_plan_list(cu, key_lens, B, H, max_seqlen, plan_cap, plan, blockIdx.x, misuse, lds);
-  }
-  const int64_t row = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3);   // row = t * H + h
-  const int sub = threadIdx.x & 7;
-  float acc = 0.f;
-  const bool ok = row < (int64_t)min(T, cu[B]) * H;   // T may be a capacity; only real tokens are touched
-  int t = 0, h = 0;
-  if (ok) {
-    t = (int)(row / H);
-    h = (int)(row - (int64_t)t * H);
-    const int64_t gr = tok_row(rows, t);
-    const u32x4 a = *reinterpret_cast<const u32x4*>(dout + gr * dos + h * kD + 8 * sub);
-    const u32x4 b = *reinterpret_cast<const u32x4*>(o + gr * os + h * kD + 8 * sub);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc = fmaf(__uint_as_float(a[i] << 16), __uint_as_float(b[i] << 16), acc);
-      acc = fmaf(__uint_as_float(a[i] & 0xffff0000u), __uint_as_float(b[i] & 0xffff0000u), acc);
-    }
-  }
-  acc += __shfl_xor(acc, 1, 64);
-  acc += __shfl_xor(acc, 2, 64);
-  acc += __shfl_xor(acc, 4, 64);
-  if (ok && sub == 0) delta[(int64_t)h * T + t] = acc;
-}
-
 // ------------------------------------------------------------------------------------------------ any length
 // Both kernels below stream their second operand in tiles of 64 rows through two LDS buffers: while
 // one tile is consumed the next travels HBM -> registers -> the other buffer (one barrier per tile).
 // Global memory is touched only as full 128-byte rows of one head; fragments and output rows pass
-// through LDS.  Workgroups are dispatched longest sequence first (`order`, written by the delta kernel;
-// NULL: in the order given).
+// through LDS.  Which workgroup does what is read from the work plan (attn_plan.h).
 constexpr int kTileS = 64;                          // rows of a streamed tile
 constexpr int kHalf = kTileS * kPitch;              // elements of one streamed operand tile (4608)
 constexpr int kBuf = 2 * kHalf;                     // one buffer: two operand tiles (= 128 rows of pitch 72)
@@ -346,12 +305,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dkv_kernel(
 template <int kMode>
 __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-    const uint16_t* __restrict__ v, const float* __restrict__ lse, const float* __restrict__ delta, int64_t dos,
-    int64_t qs, int64_t ks, int64_t vs, const float* __restrict__ slopes,
-    float scale, uint16_t* __restrict__ dq, int64_t dqs, int T, const int32_t* __restrict__ token_rows,
-    const int32_t* __restrict__ plan, int64_t plan_cap) {
+    const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse,
+    float* __restrict__ delta, int64_t dos, int64_t qs, int64_t ks, int64_t vs, int64_t os,
+    const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, int64_t dqs, int T,
+    const int32_t* __restrict__ token_rows, const int32_t* __restrict__ plan, int64_t plan_cap) {
   const int32_t* rows = kMode == kRowsIdentity ? nullptr : token_rows;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kBuf];   // per buffer: K tile, V tile
+  __shared__ __attribute__((aligned(16))) float sDelta[kTile];       // -Delta of this workgroup's queries
 
   int start, n, nk, qtile, h;   // nk <= n: the sequence's first nk tokens are its keys
   if (!plan_fetch(plan, plan_cap, &start, &n, &nk, &qtile, &h)) return;
@@ -374,24 +334,41 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
   const float cs = scale * kLog2e;
   const float k1 = slopes[h] / scale;
 
-  // ---- Q, dO rows of this workgroup's 128 queries (coalesced) -> LDS -> Q^T, dO^T fragments
+  // ---- Q, dO rows of this workgroup's 128 queries (coalesced) -> LDS -> Q^T, dO^T fragments; the O rows
+  //      only serve Delta_i = dO_i . O_i (8 lanes per row, 8 elements each), kept in LDS for this kernel and
+  //      written to [H, T] for the dK/dV kernel
   bf16x8 bq[4], bg[4];
   {
-    u32x4 tq[4], tg[4];
+    u32x4 tq[4], tg[4], to[4];
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      tq[it] = tg[it] = u32x4{0u, 0u, 0u, 0u};
+      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
       const int i = q0 + 32 * it + st_row;
       if (i < n) {
         const int64_t gr = tok_row(rows, start + i);
         tq[it] = *reinterpret_cast<const u32x4*>(q + gr * qs + h * kD + st_col);
         tg[it] = *reinterpret_cast<const u32x4*>(dout + gr * dos + h * kD + st_col);
+        to[it] = *reinterpret_cast<const u32x4*>(o + gr * os + h * kD + st_col);
       }
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       *reinterpret_cast<u32x4*>(&smem[(32 * it + st_row) * kPitch + st_col]) = tq[it];
       *reinterpret_cast<u32x4*>(&smem[kBuf + (32 * it + st_row) * kPitch + st_col]) = tg[it];
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = fmaf(__uint_as_float(tg[it][e] << 16), __uint_as_float(to[it][e] << 16), acc);
+        acc = fmaf(__uint_as_float(tg[it][e] & 0xffff0000u), __uint_as_float(to[it][e] & 0xffff0000u), acc);
+      }
+      acc += __shfl_xor(acc, 1, 64);
+      acc += __shfl_xor(acc, 2, 64);
+      acc += __shfl_xor(acc, 4, 64);
+      const int i = q0 + 32 * it + st_row;
+      if ((tid & 7) == 0) {
+        sDelta[32 * it + st_row] = -acc;
+        if (i < n) delta[(int64_t)h * T + start + i] = acc;
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -402,7 +379,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
     __syncthreads();
   }
   const float nlse2 = q_ok ? -lse[(int64_t)h * T + start + qi] * kLog2e : -INFINITY;   // -inf: P = 0
-  const float ndlt = q_ok ? -delta[(int64_t)h * T + start + qi] : 0.f;
+  const float ndlt = q_ok ? sDelta[32 * wave + c] : 0.f;
 
   // ---- streamed K / V tiles
   const uint16_t* kh = k + h * kD + st_col;
@@ -831,25 +808,34 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
 #undef MB_LAUNCH_FUSED
     return check_launch("attn_bwd_fused128_kernel");
   }
-  const int64_t rows = (int64_t)s.T * s.H;
-  // the work plan sits behind Delta in the workspace
+  // the work plan: the caller's, or built behind Delta in the workspace
   const int64_t cap = attn_plan_cap(s.B, s.max_seqlen, s.H);
   if (cap * kPlanXcds >= ((int64_t)1 << 31)) return fail(MB_ERR_UNSUPPORTED, "B * H * max_seqlen is too large for one launch");
-  int32_t* own_plan = s.plan ? nullptr
-                             : reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T));
-  const int32_t* plan = s.plan ? s.plan : own_plan;
-  const int64_t delta_blocks = (rows + 31) / 32;
-  hipLaunchKernelGGL(attn_bwd_delta_kernel, dim3((unsigned)(delta_blocks > kPlanXcds ? delta_blocks : kPlanXcds)),
-                     dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)o, dos, os, s.T, s.H, s.cu_seqlens,
-                     s.B, delta_ws, s.token_rows, s.max_seqlen, cap, own_plan, s.misuse, s.key_lens);
-  mb_status st = check_launch("attn_bwd_delta_kernel");
-  if (st != MB_OK) return st;
+  const int32_t* plan = s.plan;
+  mb_status st = MB_OK;
+  if (plan == nullptr) {
+    int32_t* own = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(delta_ws) + attn_bwd_delta_bytes(s.H, s.T));
+    st = launch_attn_plan(s, own, nullptr, stream);
+    if (st != MB_OK) return st;
+    plan = own;
+  }
   // buffer-load path: a sequence's rows within 2^31 bytes of its first
   int64_t widest = qs > ks ? qs : ks;
   widest = widest > vs ? widest : vs;
   widest = widest > dos ? widest : dos;
   const bool narrow = (int64_t)s.max_seqlen * widest * 2 < ((int64_t)1 << 31);
   const dim3 grid((unsigned)(cap * kPlanXcds));
+  // dQ first: it also leaves Delta for the dK/dV kernel
+#define MB_LAUNCH_DQ(R)                                                                                            \
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, grid, dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)q,  \
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, delta_ws, dos, qs, ks, vs,    \
+                     os, s.slopes, s.scale, (uint16_t*)dq, dqs, s.T, s.token_rows, plan, cap)
+  if (!narrow) MB_LAUNCH_DQ(kRowsPerLane);
+  else if (s.token_rows) MB_LAUNCH_DQ(kRowsMaybeContiguous);
+  else MB_LAUNCH_DQ(kRowsIdentity);
+#undef MB_LAUNCH_DQ
+  st = check_launch("attn_bwd_dq_kernel");
+  if (st != MB_OK) return st;
 #define MB_LAUNCH_DKV(R)                                                                                           \
   hipLaunchKernelGGL(attn_bwd_dkv_kernel<R>, grid, dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)q, \
                      (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs, s.slopes, s.scale,     \
@@ -858,17 +844,7 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
   else if (s.token_rows) MB_LAUNCH_DKV(kRowsMaybeContiguous);
   else MB_LAUNCH_DKV(kRowsIdentity);
 #undef MB_LAUNCH_DKV
-  st = check_launch("attn_bwd_dkv_kernel");
-  if (st != MB_OK) return st;
-#define MB_LAUNCH_DQ(R)                                                                                            \
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<R>, grid, dim3(256), 0, stream, (const uint16_t*)dout, (const uint16_t*)q,  \
-                     (const uint16_t*)k, (const uint16_t*)v, lse, delta_ws, dos, qs, ks, vs, s.slopes, s.scale,     \
-                     (uint16_t*)dq, dqs, s.T, s.token_rows, plan, cap)
-  if (!narrow) MB_LAUNCH_DQ(kRowsPerLane);
-  else if (s.token_rows) MB_LAUNCH_DQ(kRowsMaybeContiguous);
-  else MB_LAUNCH_DQ(kRowsIdentity);
-#undef MB_LAUNCH_DQ
-  return check_launch("attn_bwd_dq_kernel");
+  return check_launch("attn_bwd_dkv_kernel");
 }
 
 size_t attn_bwd_mfma_workspace_bytes(int B, int T, int max_seqlen, int H) {
