@@ -139,7 +139,7 @@ def main():
     q_, k_, v_ = qkv[:, 0], qkv[:, 1], qkv[:, 2]
     lse = lse_buf.view(H, cap)
 
-    def step(record=None):
+    def step(record=None, traffic_probe=False):
         def mark(i):
             if record is not None:
                 record[i].record(stream)
@@ -160,8 +160,11 @@ def main():
         mark(3)
         mb.mb_unpad(do_padded, indices, cap, meta, out=dout.view(cap, H * D))
         mark(4)
-        mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
-                             dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace, plan=plan)
+        if traffic_probe:   # the backward's bytes in its access pattern, no arithmetic (dqkv becomes meaningless)
+            mb.mb_probe_bwd_traffic(qkv, dout, o, dqkv, cu)
+        else:
+            mb.mb_alibi_attn_bwd(dout, q_, k_, v_, o, lse, cu, L, slopes, scale,
+                                 dq=dqkv[:, 0], dk=dqkv[:, 1], dv=dqkv[:, 2], workspace=workspace, plan=plan)
         mark(5)
         mb.mb_pad(o.view(cap, H * D), indices, cap, meta, B, L, out=o_padded)
         mark(6)
@@ -187,6 +190,17 @@ def main():
     for i in range(args.steps):
         step(events[i])
     torch.cuda.synchronize()
+    # ... and once more with the traffic-only twin of the single-tile backward in its place: the same bytes in the
+    # same access pattern and cache state, no arithmetic -- the ceiling of that pattern on this machine
+    pattern_us = None
+    if bf16 and D == 64 and L <= 128:
+        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            step(ev2[i], traffic_probe=True)
+        torch.cuda.synchronize()
+        pattern_us = np.array([e[4].elapsed_time(e[5]) * 1e3 for e in ev2])
+        step()          # leaves real gradients in the buffers again
+        torch.cuda.synchronize()
     call_names = ("unpad_index", "unpad_qkv", "attn_fwd", "unpad_do", "attn_bwd", "pad_o", "pad_dqkv")
     call_us = {name: np.array([e[i].elapsed_time(e[i + 1]) * 1e3 for e in events]) for i, name in enumerate(call_names)}
 
@@ -260,6 +274,12 @@ def main():
         "launch_us": stats(call_us["attn_bwd"]),
         "frac_of_measured_copy_rate": round(bwd_bytes / (bwd_ms * 1e-3) * 1e-9 / MEASURED_COPY_GBS, 4),
     }
+    if pattern_us is not None:
+        pat = float(np.median(pattern_us))
+        roof_hbm["traffic_only_twin"] = {
+            "what": "mb_probe_bwd_traffic in the backward's place inside the step: same bytes, same 8 row streams, no arithmetic",
+            "launch_us": stats(pattern_us), "GBs": round(bwd_bytes / (pat * 1e-6) * 1e-9, 1),
+            "kernel_frac_of_it": round(pat * 1e-3 / bwd_ms, 4)}
     roof_mfma = {
         "kernel": bwd_kernel, "bound": "mfma",
         "achieved": round(f_bwd / (bwd_ms * 1e-3) * 1e-12, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -368,6 +368,19 @@ MB_API mb_status mb_gelu_gate(const void* h, const void* gate, int64_t row_strid
  */
 MB_API mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_launch, void* stream);
 
+/*
+ * Ceiling probe for the memory traffic of the backward attention at sequence lengths <= 128 (the kernel the
+ * benchmark's roofline is about): one launch that moves exactly that kernel's bytes in its access pattern and does
+ * no arithmetic.  Per (sequence, head) a workgroup reads the Q, K, V rows of a fused [T, 3, H, 64] buffer and the
+ * dO and O rows of [T, H, 64] buffers (128 bytes per row and tensor), passes them once through LDS, and writes the
+ * three row sets of a fused [T, 3, H, 64] gradient buffer.  Eight concurrent row streams (5 in, 3 out) reach less
+ * than a plain copy; the caller times the launch and prices the real kernel against it.
+ *   qkv, dout, o  dev, bf16, read.    dqkv  dev, [T, 3, H, 64] bf16, OVERWRITTEN with meaningless values.
+ *   cu_seqlens    dev, [B+1] int32 (sequences longer than 128 are cut at 128).
+ */
+MB_API mb_status mb_probe_bwd_traffic(const void* qkv, const void* dout, const void* o, void* dqkv,
+                                      const int32_t* cu_seqlens, int B, int H, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

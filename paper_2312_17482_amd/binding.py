@@ -26,7 +26,7 @@ EXPORTS = ("mb_last_error", "mb_version", "mb_alibi_slopes", "mb_unpad_index", "
            "mb_alibi_attn_bwd_workspace_bytes",
            "mb_alibi_attn_bwd", "mb_add_layernorm_fwd", "mb_add_layernorm_bwd_workspace_bytes",
            "mb_add_layernorm_bwd", "mb_geglu_fwd", "mb_geglu_bwd_workspace_bytes", "mb_geglu_bwd", "mb_linear_fwd", "mb_gelu_gate", "mb_probe_ceiling",
-           "mb_alibi_attn_bwd_static", "mb_device_status", "mb_attn_plan_bytes", "mb_attn_plan")
+           "mb_alibi_attn_bwd_static", "mb_device_status", "mb_attn_plan_bytes", "mb_attn_plan", "mb_probe_bwd_traffic")
 
 _lib.mb_last_error.restype = c_char_p
 _lib.mb_last_error.argtypes = []
@@ -81,6 +81,8 @@ _lib.mb_geglu_bwd_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int]
 _lib.mb_geglu_bwd.restype = c_int
 _lib.mb_geglu_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_int, c_int, c_int,
                               c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.mb_probe_bwd_traffic.restype = c_int
+_lib.mb_probe_bwd_traffic.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_void_p]
 _lib.mb_probe_ceiling.restype = c_int
 _lib.mb_probe_ceiling.argtypes = [c_int, c_int, c_void_p, c_void_p, c_void_p]
 _lib.mb_linear_fwd.restype = c_int
@@ -367,6 +369,15 @@ def mb_probe_ceiling(kind: int, iters: int, out) -> float:
     work = ctypes.c_double(0.0)
     _check(_lib.mb_probe_ceiling(kind, iters, _ptr(out), ctypes.byref(work), _stream()))
     return work.value
+
+
+def mb_probe_bwd_traffic(qkv, dout, o, dqkv, cu_seqlens) -> None:
+    """Enqueues the traffic-only twin of the single-tile backward: qkv [T, 3, H, 64], dout / o [T, H, 64] read,
+    dqkv [T, 3, H, 64] overwritten with meaningless values."""
+    H = dout.shape[1]
+    assert qkv.is_contiguous() and dout.is_contiguous() and o.is_contiguous() and dqkv.is_contiguous()
+    _check(_lib.mb_probe_bwd_traffic(_ptr(qkv), _ptr(dout), _ptr(o), _ptr(dqkv), _ptr(cu_seqlens),
+                                     cu_seqlens.numel() - 1, H, _stream()))
 
 
 def mb_geglu_bwd_workspace_bytes(T_cap: int, hidden: int, inter: int, dtype_code: int = MB_BF16) -> int:

@@ -597,6 +597,20 @@ mb_status mb_probe_ceiling(int kind, int iters, float* out, double* work_per_lau
   return launch_probe(kind, iters, out, work_per_launch, (hipStream_t)stream);
 }
 
+mb_status mb_probe_bwd_traffic(const void* qkv, const void* dout, const void* o, void* dqkv, const int32_t* cu_seqlens,
+                               int B, int H, void* stream) {
+  clear_error();
+  MB_REQUIRE(B >= 0 && B <= 65535, MB_ERR_INVALID_ARG, "B=%d must be in [0, 65535]", B);
+  MB_REQUIRE(H > 0 && H <= 65535, MB_ERR_INVALID_ARG, "H=%d must be in [1, 65535]", H);
+  if (B == 0) return MB_OK;
+  MB_CHECK_PTR(qkv);
+  MB_CHECK_PTR(dout);
+  MB_CHECK_PTR(o);
+  MB_CHECK_PTR(dqkv);
+  MB_CHECK_PTR(cu_seqlens);
+  return launch_probe_bwd_traffic(qkv, dout, o, dqkv, cu_seqlens, B, H, (hipStream_t)stream);
+}
+
 static mb_status check_geglu_bwd(int T_cap, int hidden, int inter, mb_dtype dt) {
   MB_REQUIRE(dt == MB_F32 || dt == MB_BF16, MB_ERR_INVALID_ARG, "unknown dtype %d", (int)dt);
   MB_REQUIRE(T_cap >= 0, MB_ERR_INVALID_ARG, "T_cap must be >= 0 (got %d)", T_cap);

@@ -527,267 +527,316 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
 //   phase 2  dK, dV leave through the (now free) dO tile; the K registers go back to LDS over the Q
 //            tile; wave w then owns queries 32w.. and accumulates dQ^T += K^T dS^T, both operands read
 //            with transposing LDS reads.
+// The kernel is bound by memory latency, not arithmetic: with 73 KB of LDS and about 170 registers only two
+// workgroups fit a compute unit, and a workgroup spends half its life waiting for its first rows (measured with
+// timestamps: 6.2 of 12.9 us at n = 128), while a traffic-only kernel with the same access pattern runs 1.4x as
+// fast in the same place.  With kUnits = 2 a workgroup handles two consecutive (sequence, head) units and requests
+// the second unit's rows at the start of phase 2 of the first, when the dK / dV accumulators and the K fragments
+// have left their registers: the rows travel while dQ is computed and stored.  (Requesting them earlier, during
+// phase 1, needs more registers than there are: the compiler then spills, and a spill reload waits for every
+// load in flight, which undoes the overlap.  Measured inside the benchmark step: 76 -> 70 us.)
 constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
 
 // kRows: the activation buffers are a padded batch and token t sits at row rows[t].
-template <bool kRows>
+// kUnits: (sequence, head) units per workgroup, 1 or 2.
+template <bool kRows, int kUnits>
 __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse, int64_t dos,
     int64_t qs, int64_t ks, int64_t vs, int64_t os, const int32_t* __restrict__ cu,
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows,
-    int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens) {
+    int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens, int H, int n_units) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
   __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
   __shared__ __attribute__((aligned(16))) float sLse[kTile];                // -lse, base-2 units
   __shared__ __attribute__((aligned(16))) float sDelta[kTile];              // -Delta
 
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int start = cu[b];
-  const int n = cu[b + 1] - start;
-  if (n <= 0) return;
-  if (n > kTile) {   // the caller promised max_seqlen <= 128: skipped, never truncated
-    raise_misuse(misuse);
-    return;
-  }
-  const int nk = key_lens ? min(key_lens[b], n) : n;   // the sequence's first nk tokens are its keys
-  if (nk <= 0) return;
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 31, g = lane >> 5;
   const int kw = 32 * wave;
-  const int nblk = (n + 31) >> 5;        // blocks of 32 queries
-  const int nblk_k = (nk + 31) >> 5;     // blocks of 32 keys
-  const bool wave_active = wave < nblk;  // this wave's tokens exist: phase 2 (queries) and the gradient rows
-  const bool wave_keys = wave < nblk_k;  // ... and are keys: phase 1
   const int kj = kw + c;
   const float cs = scale * kLog2e;
-
-  // Token r of the sequence sits at buffer row row_of(r).  With token_rows, rows listed in ascending
-  // order whose first and last differ by n - 1 are consecutive (the usual case: padding is a suffix of
-  // each batch row); then no per-token index load is needed.
-  int64_t row0 = start;
-  bool contig = true;
-  if (kRows) {
-    row0 = rows[start];
-    contig = rows[start + n - 1] - (int)row0 == n - 1;
-  }
-  auto row_of = [&](int r) -> int64_t { return contig ? row0 + r : (int64_t)rows[start + r]; };
-
-  // ---- phase 0: coalesced row loads; thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96
   const int st_row = tid >> 3, st_col = (tid & 7) * 8;
-  u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
-  {
-    // buffer row of the 4 tokens this thread moves
-    int64_t gr[4];
-#pragma unroll
-    for (int it = 0; it < 4; ++it) gr[it] = 32 * it + st_row < n ? row_of(32 * it + st_row) : 0;
-    const uint16_t* kh = k + h * kD + st_col;
-    const uint16_t* vh = v + h * kD + st_col;
-    const uint16_t* qh = q + h * kD + st_col;
-    const uint16_t* gh = dout + h * kD + st_col;
-    const uint16_t* oh = o + h * kD + st_col;
-    // The backward is the last reader of the forward's activations: non-temporal loads keep this one-pass
-    // stream from evicting what other kernels of the step still need from L2 / the memory-side cache.
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
-      if (32 * it + st_row < nk) {
-        tk[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kh + gr[it] * ks));
-        tv[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vh + gr[it] * vs));
-      }
-    }
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
-      if (32 * it + st_row < n) {
-        tq[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qh + gr[it] * qs));
-        tg[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gh + gr[it] * dos));
-        to[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(oh + gr[it] * os));
-      }
-    }
-  }
-  // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there)
-  if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + start + tid] * kLog2e : -INFINITY;
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    if (it < nblk) {   // rows n..32*nblk-1 are zeros; rows >= 32*nblk are never read
-      *reinterpret_cast<u32x4*>(&sA[(32 * it + st_row) * kPitch + st_col]) = tk[it];
-      *reinterpret_cast<u32x4*>(&sB[(32 * it + st_row) * kPitch + st_col]) = tv[it];
-    }
-  }
-  __syncthreads();
-  bf16x8 bk[4], bv[4];   // K^T, V^T fragments (B operands): lane = key column, 8 consecutive d per k-step
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    bk[s] = lds_read8(&sA[kj * kPitch + 16 * s + 8 * g]);
-    bv[s] = lds_read8(&sB[kj * kPitch + 16 * s + 8 * g]);
-  }
-  __syncthreads();   // K, V have been read by everyone
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = 32 * it + st_row;
-    if (it < nblk) {
-      *reinterpret_cast<u32x4*>(&sA[row * kPitch + st_col]) = tq[it];
-      *reinterpret_cast<u32x4*>(&sB[row * kPitch + st_col]) = tg[it];
-    }
-    float acc = 0.f;   // Delta = rowsum(dO * O): 8 lanes per row, 8 elements each
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      acc = fmaf(__uint_as_float(tg[it][i] << 16), __uint_as_float(to[it][i] << 16), acc);
-      acc = fmaf(__uint_as_float(tg[it][i] & 0xffff0000u), __uint_as_float(to[it][i] & 0xffff0000u), acc);
-    }
-    acc += __shfl_xor(acc, 1, 64);
-    acc += __shfl_xor(acc, 2, 64);
-    acc += __shfl_xor(acc, 4, 64);
-    if ((tid & 7) == 0) sDelta[row] = -acc;
-  }
-  __syncthreads();
-
   const int tr_i = lane & 15, tr_q = lane >> 4;
   const int tr_row = (tr_i >> 2) + 4 * (tr_q >> 1);
   const int tr_col = 16 * (tr_q & 1) + 4 * (tr_i & 3);
-
-  // ---- phase 1
-  f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows, this wave's keys along lanes
-#pragma unroll
-  for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
-  if (wave_keys) {
-    // The S accumulator is pre-loaded with bias/scale = -(m_h/scale)|i-j| and the dP accumulator with
-    // -Delta_i, so that after the matrix products  P = exp2(acc_S * c - lse2_i)  and  dS = P * acc_dP.
-    const float k1 = slopes[h] / scale;
-    float fj = (float)(kj - 4 * g);   // i - j = ci - fj with ci = 32ib + 8*(v/4) + v%4
-    asm volatile("" : "+v"(fj));
-#pragma unroll 1
-    for (int ib = 0; ib < nblk; ++ib) {
-      f32x16 sacc, pacc;
-      const float d0 = (float)(32 * ib) - fj;
-      if (ib == wave) {   // block with the diagonal
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
-      } else {            // |i-j| = +-(ci - fj) on the whole block
-        const float sk = ib < wave ? k1 : -k1;
-        const float a = sk * d0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
-      }
-      float nl[16];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
-        const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
-        nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
-        pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
-      }
-      const uint16_t* qrow = &sA[(32 * ib + c) * kPitch + 8 * g];
-      const uint16_t* grow = &sB[(32 * ib + c) * kPitch + 8 * g];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
-        pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
-      }
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * r + e;
-          const float p = fast_exp2(fmaf(sacc[i], cs, nl[i]));
-          sacc[i] = p;
-          pacc[i] = p * pacc[i];
-        }
-        // dS of queries 32ib + 8r + 4g + 0..3 for this lane's key.  A key past the sequence end may hold
-        // inf/NaN here (its score never entered lse) and phase 2 multiplies it with a zero K row, so it
-        // must be an exact zero in LDS.
-        u32x2 w;
-        w[0] = kj < nk ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
-        w[1] = kj < nk ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
-        *reinterpret_cast<u32x2*>(&sDs[kj * kDsPitch + 32 * ib + 8 * r + 4 * g]) = w;
-      }
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
-                                sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
-        const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
-                                pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
-        const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
-#pragma unroll
-        for (int db = 0; db < 2; ++db) {
-          const bf16x8 ag = join_tr(lds_read_tr4(&sB[roff + 32 * db]), lds_read_tr4(&sB[roff + 32 * db + 8 * kPitch]));
-          dvacc[db] = mfma32(ag, bp, dvacc[db]);
-          const bf16x8 aq = join_tr(lds_read_tr4(&sA[roff + 32 * db]), lds_read_tr4(&sA[roff + 32 * db + 8 * kPitch]));
-          dkacc[db] = mfma32(aq, bs, dkacc[db]);
-        }
-      }
-    }
-  }
-  __syncthreads();   // Q and dO have been read by everyone, all of dS is written
-
-  // Accumulators (lane = token, 4 consecutive d per register group) -> this wave's 32 rows of sB ->
-  // full rows of 128 bytes to global memory.  The slab is private to the wave, and the LDS operations
-  // of one wave complete in order, so no barrier is needed between its uses.
-  uint16_t* slab = &sB[kw * kPitch];
   const int orow = lane >> 3, ocol = (lane & 7) * 8;
-  // (rows at and beyond `live` are written as zeros: tokens that are no keys have zero dK and dV)
-  auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride, int live) {
-#pragma unroll
-    for (int db = 0; db < 2; ++db) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        u32x2 w;
-        w[0] = pack_bf16(acc[db][4 * r + 0] * mul, acc[db][4 * r + 1] * mul);
-        w[1] = pack_bf16(acc[db][4 * r + 2] * mul, acc[db][4 * r + 3] * mul);
-        *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
-      }
+
+  // A unit: head h of the sequence that starts at packed token `start` and has n tokens, the first nk of which
+  // are keys (n = 0: nothing to do).  Token r of the sequence sits at buffer row row_of(r).  With token_rows, rows listed in ascending
+  // order whose first and last differ by n - 1 are consecutive (the usual case: padding is a suffix of each
+  // batch row); then no per-token index load is needed.
+  struct Unit {
+    int h, start, n, nk;
+    int64_t row0;
+    bool contig;
+  };
+  auto find_unit = [&](int u) -> Unit {
+    Unit U{0, 0, 0, 0, 0, true};
+    if (u >= n_units) return U;
+    const int b = u / H;
+    U.h = u - b * H;
+    U.start = cu[b];
+    U.n = cu[b + 1] - U.start;
+    if (U.n > kTile) {   // the caller promised max_seqlen <= 128: skipped, never truncated
+      raise_misuse(misuse);
+      U.n = 0;
     }
-    uint16_t* oh = out + h * kD + ocol;
+    U.nk = key_lens ? min(key_lens[b], U.n) : U.n;
+    if (U.n <= 0 || U.nk <= 0) {   // empty, or no keys: skipped
+      U.n = 0;
+      return U;
+    }
+    U.row0 = U.start;
+    if (kRows) {
+      U.row0 = rows[U.start];
+      U.contig = rows[U.start + U.n - 1] - (int)U.row0 == U.n - 1;
+    }
+    return U;
+  };
+  auto row_of = [&](const Unit& U, int r) -> int64_t { return U.contig ? U.row0 + r : (int64_t)rows[U.start + r]; };
+
+  // ---- coalesced row loads; thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96.
+  // The backward is the last reader of the forward's activations: non-temporal loads keep this one-pass
+  // stream from evicting what other kernels of the step still need from L2 / the memory-side cache.
+  u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
+  auto issue_kv = [&](const Unit& U) {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = 8 * it + orow;
-      u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
-      if (kw + row >= live) w = u32x4{0u, 0u, 0u, 0u};
-      if (kw + row < n) {
-        // written into the padded layout these rows are final results of the step: stream them out
-        if (kRows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride));
-        else *reinterpret_cast<u32x4*>(oh + row_of(kw + row) * stride) = w;
+      tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < U.nk) {
+        const int64_t gr = row_of(U, 32 * it + st_row);
+        tk[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(k + gr * ks + U.h * kD + st_col));
+        tv[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(v + gr * vs + U.h * kD + st_col));
+      }
+    }
+  };
+  auto issue_qgo = [&](const Unit& U) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
+      if (32 * it + st_row < U.n) {
+        const int64_t gr = row_of(U, 32 * it + st_row);
+        tq[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(q + gr * qs + U.h * kD + st_col));
+        tg[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dout + gr * dos + U.h * kD + st_col));
+        to[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(o + gr * os + U.h * kD + st_col));
       }
     }
   };
 
-  // ---- phase 2
-  if (wave_active) {
-    store_rows(dkacc, scale, dk, dks, nk);
-    store_rows(dvacc, 1.f, dv, dvs, nk);
-  }
-  if (wave_keys) {
-    // K registers -> LDS over Q; rows of keys >= nk are zeros because they were staged as zeros
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-      *reinterpret_cast<u32x4*>(&sA[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
-  }
-  __syncthreads();
-  if (!wave_active) return;   // queries 32*wave.. do not exist
+  Unit nxt = find_unit(kUnits * blockIdx.x);
+  issue_kv(nxt);
+  issue_qgo(nxt);
 
-  f32x16 dqacc[2];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
+  for (int iu = 0; iu < kUnits; ++iu) {
+    const Unit U = nxt;
+    const bool more = iu + 1 < kUnits;
+    if (more) nxt = find_unit(kUnits * blockIdx.x + iu + 1);
+    // n, h and nblk are uniform over the workgroup: every thread takes the same branches around the barriers
+    const int n = U.n, nk = U.nk, h = U.h;
+    const int nblk = (n + 31) >> 5;        // blocks of 32 queries
+    const int nblk_k = (nk + 31) >> 5;     // blocks of 32 keys
+    const bool wave_active = wave < nblk;  // this wave's tokens exist: phase 2 (queries) and the gradient rows
+    const bool wave_keys = wave < nblk_k;  // ... and are keys: phase 1
+    bf16x8 bk[4], bv[4];   // K^T, V^T fragments (B operands): lane = key column, 8 consecutive d per k-step
+
+    if (n > 0) {
+      // ---- phase 0
+      // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there)
+      if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + U.start + tid] * kLog2e : -INFINITY;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        if (it < nblk) {   // rows n..32*nblk-1 are zeros; rows >= 32*nblk are never read
+          *reinterpret_cast<u32x4*>(&sA[(32 * it + st_row) * kPitch + st_col]) = tk[it];
+          *reinterpret_cast<u32x4*>(&sB[(32 * it + st_row) * kPitch + st_col]) = tv[it];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        bk[s] = lds_read8(&sA[kj * kPitch + 16 * s + 8 * g]);
+        bv[s] = lds_read8(&sB[kj * kPitch + 16 * s + 8 * g]);
+      }
+      __syncthreads();   // K, V have been read by everyone
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = 32 * it + st_row;
+        if (it < nblk) {
+          *reinterpret_cast<u32x4*>(&sA[row * kPitch + st_col]) = tq[it];
+          *reinterpret_cast<u32x4*>(&sB[row * kPitch + st_col]) = tg[it];
+        }
+        float acc = 0.f;   // Delta = rowsum(dO * O): 8 lanes per row, 8 elements each
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          acc = fmaf(__uint_as_float(tg[it][i] << 16), __uint_as_float(to[it][i] << 16), acc);
+          acc = fmaf(__uint_as_float(tg[it][i] & 0xffff0000u), __uint_as_float(to[it][i] & 0xffff0000u), acc);
+        }
+        acc += __shfl_xor(acc, 1, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        acc += __shfl_xor(acc, 4, 64);
+        if ((tid & 7) == 0) sDelta[row] = -acc;
+      }
+      __syncthreads();
+    }
+    if (n <= 0) {
+      if (more) {
+        issue_kv(nxt);
+        issue_qgo(nxt);
+      }
+      continue;
+    }
+
+    // ---- phase 1
+    f32x16 dkacc[2], dvacc[2];   // dK^T, dV^T: d along accumulator rows, this wave's keys along lanes
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { dkacc[0][i] = dkacc[1][i] = dvacc[0][i] = dvacc[1][i] = 0.f; }
+    if (wave_keys) {
+      // The S accumulator is pre-loaded with bias/scale = -(m_h/scale)|i-j| and the dP accumulator with
+      // -Delta_i, so that after the matrix products  P = exp2(acc_S * c - lse2_i)  and  dS = P * acc_dP.
+      const float k1 = slopes[h] / scale;
+      float fj = (float)(kj - 4 * g);   // i - j = ci - fj with ci = 32ib + 8*(v/4) + v%4
+      asm volatile("" : "+v"(fj));
 #pragma unroll 1
-  for (int jb = 0; jb < nblk_k; ++jb) {
+      for (int ib = 0; ib < nblk; ++ib) {
+        f32x16 sacc, pacc;
+        const float d0 = (float)(32 * ib) - fj;
+        if (ib == wave) {   // block with the diagonal
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-      const int krow = 32 * jb + 16 * kk + tr_row;
-      const bf16x8 bs = join_tr(lds_read_tr4(&sDs[krow * kDsPitch + kw + tr_col]),
-                                lds_read_tr4(&sDs[(krow + 8) * kDsPitch + kw + tr_col]));
+          for (int i = 0; i < 16; ++i) sacc[i] = -k1 * fabsf(d0 + (float)(8 * (i >> 2) + (i & 3)));
+        } else {            // |i-j| = +-(ci - fj) on the whole block
+          const float sk = ib < wave ? k1 : -k1;
+          const float a = sk * d0;
 #pragma unroll
-      for (int db = 0; db < 2; ++db) {
-        const bf16x8 ak = join_tr(lds_read_tr4(&sA[krow * kPitch + tr_col + 32 * db]),
-                                  lds_read_tr4(&sA[(krow + 8) * kPitch + tr_col + 32 * db]));
-        dqacc[db] = mfma32(ak, bs, dqacc[db]);
+          for (int i = 0; i < 16; ++i) sacc[i] = fmaf((float)(8 * (i >> 2) + (i & 3)), sk, a);
+        }
+        float nl[16];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * ib + 8 * r + 4 * g]);
+          const float4 d4 = *reinterpret_cast<const float4*>(&sDelta[32 * ib + 8 * r + 4 * g]);
+          nl[4 * r + 0] = l4.x; nl[4 * r + 1] = l4.y; nl[4 * r + 2] = l4.z; nl[4 * r + 3] = l4.w;
+          pacc[4 * r + 0] = d4.x; pacc[4 * r + 1] = d4.y; pacc[4 * r + 2] = d4.z; pacc[4 * r + 3] = d4.w;
+        }
+        const uint16_t* qrow = &sA[(32 * ib + c) * kPitch + 8 * g];
+        const uint16_t* grow = &sB[(32 * ib + c) * kPitch + 8 * g];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          sacc = mfma32(lds_read8(qrow + 16 * s), bk[s], sacc);
+          pacc = mfma32(lds_read8(grow + 16 * s), bv[s], pacc);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * r + e;
+            const float p = fast_exp2(fmaf(sacc[i], cs, nl[i]));
+            sacc[i] = p;
+            pacc[i] = p * pacc[i];
+          }
+          // dS of queries 32ib + 8r + 4g + 0..3 for this lane's key.  A key past the sequence end may hold
+          // inf/NaN here (its score never entered lse) and phase 2 multiplies it with a zero K row, so it
+          // must be an exact zero in LDS.
+          u32x2 w;
+          w[0] = kj < nk ? pack_bf16(pacc[4 * r + 0], pacc[4 * r + 1]) : 0u;
+          w[1] = kj < nk ? pack_bf16(pacc[4 * r + 2], pacc[4 * r + 3]) : 0u;
+          *reinterpret_cast<u32x2*>(&sDs[kj * kDsPitch + 32 * ib + 8 * r + 4 * g]) = w;
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          const bf16x8 bp = pack8(sacc[8 * kk + 0], sacc[8 * kk + 1], sacc[8 * kk + 2], sacc[8 * kk + 3],
+                                  sacc[8 * kk + 4], sacc[8 * kk + 5], sacc[8 * kk + 6], sacc[8 * kk + 7]);
+          const bf16x8 bs = pack8(pacc[8 * kk + 0], pacc[8 * kk + 1], pacc[8 * kk + 2], pacc[8 * kk + 3],
+                                  pacc[8 * kk + 4], pacc[8 * kk + 5], pacc[8 * kk + 6], pacc[8 * kk + 7]);
+          const int roff = (32 * ib + 16 * kk + tr_row) * kPitch + tr_col;
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const bf16x8 ag = join_tr(lds_read_tr4(&sB[roff + 32 * db]), lds_read_tr4(&sB[roff + 32 * db + 8 * kPitch]));
+            dvacc[db] = mfma32(ag, bp, dvacc[db]);
+            const bf16x8 aq = join_tr(lds_read_tr4(&sA[roff + 32 * db]), lds_read_tr4(&sA[roff + 32 * db + 8 * kPitch]));
+            dkacc[db] = mfma32(aq, bs, dkacc[db]);
+          }
+        }
       }
     }
+    __syncthreads();   // Q and dO have been read by everyone, all of dS is written
+
+    // Accumulators (lane = token, 4 consecutive d per register group) -> this wave's 32 rows of sB ->
+    // full rows of 128 bytes to global memory.  The slab is private to the wave, and the LDS operations
+    // of one wave complete in order, so no barrier is needed between its uses.
+    uint16_t* slab = &sB[kw * kPitch];
+    // (rows at and beyond `live` are written as zeros: tokens that are no keys have zero dK and dV)
+    auto store_rows = [&](const f32x16(&acc)[2], float mul, uint16_t* __restrict__ out, int64_t stride, int live) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          u32x2 w;
+          w[0] = pack_bf16(acc[db][4 * r + 0] * mul, acc[db][4 * r + 1] * mul);
+          w[1] = pack_bf16(acc[db][4 * r + 2] * mul, acc[db][4 * r + 3] * mul);
+          *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
+        }
+      }
+      uint16_t* oh = out + h * kD + ocol;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int row = 8 * it + orow;
+        u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+        if (kw + row >= live) w = u32x4{0u, 0u, 0u, 0u};
+        if (kw + row < n) {
+          // written into the padded layout these rows are final results of the step: stream them out
+          if (kRows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(U, kw + row) * stride));
+          else *reinterpret_cast<u32x4*>(oh + row_of(U, kw + row) * stride) = w;
+        }
+      }
+    };
+
+    // ---- phase 2
+    if (wave_active) {
+      store_rows(dkacc, scale, dk, dks, nk);
+      store_rows(dvacc, 1.f, dv, dvs, nk);
+    }
+    if (wave_keys) {
+      // K registers -> LDS over Q; rows of keys >= nk are zeros because they were staged as zeros
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        *reinterpret_cast<u32x4*>(&sA[kj * kPitch + 16 * s + 8 * g]) = __builtin_bit_cast(u32x4, bk[s]);
+    }
+    // dK, dV and the K fragments have left their registers: room for the next unit's rows, which travel while
+    // dQ is computed and stored (the fences keep the compiler from moving the loads further up, where the
+    // registers are still taken)
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) {
+      issue_kv(nxt);
+      issue_qgo(nxt);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    if (wave_active) {   // (queries 32*wave.. exist)
+      f32x16 dqacc[2];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
+#pragma unroll 1
+      for (int jb = 0; jb < nblk_k; ++jb) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          const int krow = 32 * jb + 16 * kk + tr_row;
+          const bf16x8 bs = join_tr(lds_read_tr4(&sDs[krow * kDsPitch + kw + tr_col]),
+                                    lds_read_tr4(&sDs[(krow + 8) * kDsPitch + kw + tr_col]));
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const bf16x8 ak = join_tr(lds_read_tr4(&sA[krow * kPitch + tr_col + 32 * db]),
+                                      lds_read_tr4(&sA[(krow + 8) * kPitch + tr_col + 32 * db]));
+            dqacc[db] = mfma32(ak, bs, dqacc[db]);
+          }
+        }
+      }
+      store_rows(dqacc, scale, dq, dqs, n);
+    }
+    if (more) __syncthreads();   // the next unit's phase 0 overwrites sA, sB, sLse and sDelta
   }
-  store_rows(dqacc, scale, dq, dqs, n);
 }
 
 }  // namespace
@@ -798,13 +847,15 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
                                float* delta_ws, hipStream_t stream) {
   if (s.B > 65535) return fail(MB_ERR_UNSUPPORTED, "B=%d exceeds 65535 sequences per call", s.B);
   if (s.max_seqlen <= kTile) {
-#define MB_LAUNCH_FUSED(R)                                                                                        \
-  hipLaunchKernelGGL(attn_bwd_fused128_kernel<R>, dim3(s.H, s.B), dim3(256), 0, stream, (const uint16_t*)dout,    \
-                     (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)o, lse, dos, qs, \
-                     ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, (uint16_t*)dk, (uint16_t*)dv,     \
-                     dqs, dks, dvs, s.T, s.token_rows, s.misuse, s.key_lens)
-    if (s.token_rows) MB_LAUNCH_FUSED(true);
-    else MB_LAUNCH_FUSED(false);
+    const int64_t units = (int64_t)s.B * s.H;   // (sequence, head) pairs, head fastest; < 2^30 (checked by the caller)
+#define MB_LAUNCH_FUSED(R, U)                                                                                        \
+  hipLaunchKernelGGL((attn_bwd_fused128_kernel<R, U>), dim3((unsigned)((units + U - 1) / U)), dim3(256), 0,       \
+                     stream, (const uint16_t*)dout, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,    \
+                     (const uint16_t*)o, lse, dos, qs, ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, \
+                     (uint16_t*)dk, (uint16_t*)dv, dqs, dks, dvs, s.T, s.token_rows, s.misuse, s.key_lens, s.H,    \
+                     (int)units)
+    if (s.token_rows) MB_LAUNCH_FUSED(true, 2);
+    else MB_LAUNCH_FUSED(false, 2);
 #undef MB_LAUNCH_FUSED
     return check_launch("attn_bwd_fused128_kernel");
   }

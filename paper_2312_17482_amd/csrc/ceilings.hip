@@ -67,7 +67,63 @@ __global__ __launch_bounds__(256) void probe_exp_kernel(int iters, float* __rest
   if (s == 12345.678f) out[0] = s;
 }
 
+// The memory traffic of the single-tile backward attention with its arithmetic taken out: per (sequence, head)
+// unit one workgroup reads five tiles of n rows x 128 bytes (Q, K, V rows of a fused [T, 3, H, 64] buffer, dO and
+// O rows of [T, H, 64] buffers), passes them once through LDS with one barrier, and writes three tiles (the rows
+// of a fused [T, 3, H, 64] gradient buffer).  What this reaches is the ceiling of that access pattern on the
+// machine: eight concurrent row streams, 5 in and 3 out, which is below what a plain two-stream copy reaches.
+__global__ __launch_bounds__(256) void probe_bwd_traffic_kernel(const uint16_t* __restrict__ qkv,
+                                                                const uint16_t* __restrict__ dout,
+                                                                const uint16_t* __restrict__ o,
+                                                                uint16_t* __restrict__ dqkv,
+                                                                const int32_t* __restrict__ cu, int H) {
+  __shared__ u32x4 stage[3 * 4 * 256];   // 48 KB: three workgroups per compute unit
+  const int h = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int start = cu[b], n = min(cu[b + 1] - start, 128);
+  const int st_row = tid >> 3, st_col = (tid & 7) * 8;
+  const int64_t s3 = 3 * (int64_t)H * 64, s1 = (int64_t)H * 64;
+  u32x4 t[5][4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+#pragma unroll
+    for (int x = 0; x < 5; ++x) t[x][it] = u32x4{0u, 0u, 0u, 0u};
+    const int r = 32 * it + st_row;
+    if (r < n) {
+      const int64_t row = start + r;
+#pragma unroll
+      for (int x = 0; x < 3; ++x)
+        t[x][it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qkv + row * s3 + (x * H + h) * 64 + st_col));
+      t[3][it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dout + row * s1 + h * 64 + st_col));
+      t[4][it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(o + row * s1 + h * 64 + st_col));
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    stage[(0 * 4 + it) * 256 + tid] = t[0][it] ^ t[3][it];
+    stage[(1 * 4 + it) * 256 + tid] = t[1][it] ^ t[4][it];
+    stage[(2 * 4 + it) * 256 + tid] = t[2][it] + t[3][it];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int r = 32 * it + st_row;
+    if (r < n) {
+      const int64_t row = start + r;
+#pragma unroll
+      for (int x = 0; x < 3; ++x)
+        *reinterpret_cast<u32x4*>(dqkv + row * s3 + (x * H + h) * 64 + st_col) = stage[(x * 4 + it) * 256 + (tid ^ 8)];
+    }
+  }
+}
+
 }  // namespace
+
+mb_status launch_probe_bwd_traffic(const void* qkv, const void* dout, const void* o, void* dqkv, const int32_t* cu,
+                                   int B, int H, hipStream_t stream) {
+  hipLaunchKernelGGL(probe_bwd_traffic_kernel, dim3(H, B), dim3(256), 0, stream, (const uint16_t*)qkv,
+                     (const uint16_t*)dout, (const uint16_t*)o, (uint16_t*)dqkv, cu, H);
+  return check_launch("probe_bwd_traffic_kernel");
+}
 
 mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch, hipStream_t stream) {
   const double lanes = (double)kProbeBlocks * kProbeThreads;

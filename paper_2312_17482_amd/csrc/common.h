@@ -78,6 +78,8 @@ mb_status launch_zero_padding(const int32_t* indices, int T_cap, const int32_t* 
 static constexpr int kLayerNormMaxParts = 1024;
 // Ceiling probes (kind 0: bf16 matrix cores, 1: vector fused multiply-add, 2: vector exponential).
 mb_status launch_probe(int kind, int iters, float* out, double* work_per_launch, hipStream_t stream);
+mb_status launch_probe_bwd_traffic(const void* qkv, const void* dout, const void* o, void* dqkv, const int32_t* cu,
+                                   int B, int H, hipStream_t stream);
 
 // GeGLU feed-forward, forward (bf16; hidden a multiple of 256, inter a multiple of 128).
 mb_status launch_geglu_fwd(const void* x, const void* w1v, const void* w2, int T_cap, const int32_t* meta,

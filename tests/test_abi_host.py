@@ -250,6 +250,12 @@ def test_linear_and_gelu_gate_reject_bad_arguments():
     assert g(None, None, 3072, 0, None, 3072, mb.MB_BF16, None, None) == mb.MB_OK
 
 
+def test_traffic_probe_rejects_bad_arguments():
+    assert lib.mb_probe_bwd_traffic(A, A, A, None, A, 4, 12, None) == mb.MB_ERR_INVALID_ARG and "dqkv is NULL" in mb.mb_last_error()
+    assert lib.mb_probe_bwd_traffic(A, A, A, A, A, 4, 0, None) == mb.MB_ERR_INVALID_ARG
+    assert lib.mb_probe_bwd_traffic(None, None, None, None, None, 0, 12, None) == mb.MB_OK
+
+
 def test_probe_rejects_bad_arguments():
     w = ctypes.c_double(0.0)
     assert lib.mb_probe_ceiling(3, 10, A, ctypes.byref(w), None) == mb.MB_ERR_INVALID_ARG
