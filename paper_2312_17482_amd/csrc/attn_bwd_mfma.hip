@@ -531,15 +531,24 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
 // workgroups fit a compute unit, and a workgroup spends half its life waiting for its first rows (measured with
 // timestamps: 6.2 of 12.9 us at n = 128), while a traffic-only kernel with the same access pattern runs 1.4x as
 // fast in the same place.  With kUnits = 2 a workgroup handles two consecutive (sequence, head) units and requests
-// the second unit's rows at the start of phase 2 of the first, when the dK / dV accumulators and the K fragments
+// the second unit's rows in phase 2 of the first, when the dK / dV accumulators and the K fragments
 // have left their registers: the rows travel while dQ is computed and stored.  (Requesting them earlier, during
 // phase 1, needs more registers than there are: the compiler then spills, and a spill reload waits for every
-// load in flight, which undoes the overlap.  Measured inside the benchmark step: 76 -> 70 us.)
+// load in flight, which undoes the overlap.  Measured inside the benchmark step: 76 -> 70 us.)  With packed tokens
+// the 40 loads of a thread are not issued in one burst, during which the wave can do nothing else (timestamps: 2.5 us
+// for the burst), but five at a time between the four steps of the dQ loop (another 1.1 us off).
 constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
 
-// kRows: the activation buffers are a padded batch and token t sits at row rows[t].
+// kMode (see kRowsIdentity .. in common.h): a unit whose tokens sit in consecutive buffer rows moves all its rows with
+// buffer instructions: one descriptor per tensor and unit that starts at the unit's first row and ends with its last
+// (built with scalar arithmetic) and one per-lane byte offset per tensor that is the same for every unit, to which
+// the step from one group of rows to the next is added (the whole offset must be the vector operand: the scalar
+// offset of a buffer instruction takes no part in its range check).  Rows past the unit's end then read as zeros and
+// are dropped on a store without a compare, and forming an address is one 32-bit add.  (With per-lane 64-bit
+// addresses every row access costs a 64-bit multiply, three quarter-rate vector instructions: a tenth of all vector
+// instructions of this kernel were address arithmetic.)
 // kUnits: (sequence, head) units per workgroup, 1 or 2.
-template <bool kRows, int kUnits>
+template <int kMode, int kUnits>
 __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const uint16_t* __restrict__ dout, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ o, const float* __restrict__ lse, int64_t dos,
@@ -547,6 +556,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     const float* __restrict__ slopes, float scale, uint16_t* __restrict__ dq, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int64_t dqs, int64_t dks, int64_t dvs, int T, const int32_t* __restrict__ rows,
     int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens, int H, int n_units) {
+  constexpr bool kRows = kMode != kRowsIdentity;   // token t may sit at another row than t
+  if (kMode == kRowsIdentity) rows = nullptr;
   __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
   __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
   __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
@@ -574,35 +585,54 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     bool contig;
   };
   auto find_unit = [&](int u) -> Unit {
-    Unit U{0, 0, 0, 0, 0, true};
+    Unit U{0, 0, 0, 0, 0, kMode != kRowsPerLane};
     if (u >= n_units) return U;
     const int b = u / H;
     U.h = u - b * H;
-    U.start = cu[b];
-    U.n = cu[b + 1] - U.start;
+    U.start = __builtin_amdgcn_readfirstlane(cu[b]);
+    U.n = __builtin_amdgcn_readfirstlane(cu[b + 1]) - U.start;
     if (U.n > kTile) {   // the caller promised max_seqlen <= 128: skipped, never truncated
       raise_misuse(misuse);
       U.n = 0;
     }
-    U.nk = key_lens ? min(key_lens[b], U.n) : U.n;
+    U.nk = key_lens ? min(__builtin_amdgcn_readfirstlane(key_lens[b]), U.n) : U.n;
     if (U.n <= 0 || U.nk <= 0) {   // empty, or no keys: skipped
       U.n = 0;
       return U;
     }
     U.row0 = U.start;
-    if (kRows) {
-      U.row0 = rows[U.start];
-      U.contig = rows[U.start + U.n - 1] - (int)U.row0 == U.n - 1;
+    if (kMode == kRowsMaybeContiguous) {
+      const int r0 = __builtin_amdgcn_readfirstlane(rows[U.start]);
+      U.row0 = r0;
+      U.contig = __builtin_amdgcn_readfirstlane(rows[U.start + U.n - 1]) - r0 == U.n - 1;
     }
     return U;
   };
-  auto row_of = [&](const Unit& U, int r) -> int64_t { return U.contig ? U.row0 + r : (int64_t)rows[U.start + r]; };
+  // (only for units that are not moved with buffer instructions)
+  auto row_of = [&](const Unit& U, int r) -> int64_t { return tok_row(rows, U.start + r); };
+  // descriptor of head h of rows row0 .. row0 + cnt - 1 of a tensor with `stride` elements per row (cnt <= 0: of nothing)
+  auto unit_rsrc = [&](const uint16_t* base, int64_t stride, const Unit& U, int cnt) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base) + (U.row0 * stride + U.h * kD), 0,
+                                             cnt > 0 ? ((cnt - 1) * (int)stride + kD) * 2 : 0, kRsrcFlags);
+  };
+  constexpr int kNt = 2;   // cache policy of a buffer instruction: non-temporal
 
   // ---- coalesced row loads; thread (st_row, st_col) moves 16 bytes of rows st_row, +32, +64, +96.
   // The backward is the last reader of the forward's activations: non-temporal loads keep this one-pass
   // stream from evicting what other kernels of the step still need from L2 / the memory-side cache.
   u32x4 tk[4], tv[4], tq[4], tg[4], to[4];
   auto issue_kv = [&](const Unit& U) {
+    if (kMode != kRowsPerLane && U.contig) {
+      const __amdgpu_buffer_rsrc_t kr = unit_rsrc(k, ks, U, U.nk), vr = unit_rsrc(v, vs, U, U.nk);
+      const uint32_t ko = ((uint32_t)st_row * (uint32_t)ks + (uint32_t)st_col) * 2u;
+      const uint32_t vo = ((uint32_t)st_row * (uint32_t)vs + (uint32_t)st_col) * 2u;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, ko + (uint32_t)(it * 64) * (uint32_t)ks, 0, kNt);
+        tv[it] = __builtin_amdgcn_raw_buffer_load_b128(vr, vo + (uint32_t)(it * 64) * (uint32_t)vs, 0, kNt);
+      }
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tk[it] = tv[it] = u32x4{0u, 0u, 0u, 0u};
@@ -614,6 +644,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     }
   };
   auto issue_qgo = [&](const Unit& U) {
+    if (kMode != kRowsPerLane && U.contig) {
+      const __amdgpu_buffer_rsrc_t qr = unit_rsrc(q, qs, U, U.n), gr = unit_rsrc(dout, dos, U, U.n),
+                                   orr = unit_rsrc(o, os, U, U.n);
+      const uint32_t qo = ((uint32_t)st_row * (uint32_t)qs + (uint32_t)st_col) * 2u;
+      const uint32_t go = ((uint32_t)st_row * (uint32_t)dos + (uint32_t)st_col) * 2u;
+      const uint32_t oo = ((uint32_t)st_row * (uint32_t)os + (uint32_t)st_col) * 2u;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        tq[it] = __builtin_amdgcn_raw_buffer_load_b128(qr, qo + (uint32_t)(it * 64) * (uint32_t)qs, 0, kNt);
+        tg[it] = __builtin_amdgcn_raw_buffer_load_b128(gr, go + (uint32_t)(it * 64) * (uint32_t)dos, 0, kNt);
+        to[it] = __builtin_amdgcn_raw_buffer_load_b128(orr, oo + (uint32_t)(it * 64) * (uint32_t)os, 0, kNt);
+      }
+      return;
+    }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       tq[it] = tg[it] = to[it] = u32x4{0u, 0u, 0u, 0u};
@@ -624,6 +668,20 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         to[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(o + gr * os + U.h * kD + st_col));
       }
     }
+  };
+
+  // rows 32 it + st_row of all five tensors of a unit that is moved with buffer instructions
+  auto issue_group = [&](const Unit& U, int it) {
+    const __amdgpu_buffer_rsrc_t kr = unit_rsrc(k, ks, U, U.nk), vr = unit_rsrc(v, vs, U, U.nk);
+    const __amdgpu_buffer_rsrc_t qr = unit_rsrc(q, qs, U, U.n), gr = unit_rsrc(dout, dos, U, U.n),
+                                 orr = unit_rsrc(o, os, U, U.n);
+    const uint32_t r = (uint32_t)(32 * it + st_row);
+    const uint32_t c2 = (uint32_t)st_col * 2u;
+    tk[it] = __builtin_amdgcn_raw_buffer_load_b128(kr, r * (uint32_t)ks * 2u + c2, 0, kNt);
+    tv[it] = __builtin_amdgcn_raw_buffer_load_b128(vr, r * (uint32_t)vs * 2u + c2, 0, kNt);
+    tq[it] = __builtin_amdgcn_raw_buffer_load_b128(qr, r * (uint32_t)qs * 2u + c2, 0, kNt);
+    tg[it] = __builtin_amdgcn_raw_buffer_load_b128(gr, r * (uint32_t)dos * 2u + c2, 0, kNt);
+    to[it] = __builtin_amdgcn_raw_buffer_load_b128(orr, r * (uint32_t)os * 2u + c2, 0, kNt);
   };
 
   Unit nxt = find_unit(kUnits * blockIdx.x);
@@ -779,6 +837,18 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
           *reinterpret_cast<u32x2*>(&slab[c * kPitch + 32 * db + 8 * r + 4 * g]) = w;
         }
       }
+      if (kMode != kRowsPerLane && U.contig) {
+        const __amdgpu_buffer_rsrc_t wr = unit_rsrc(out, stride, U, n);   // rows at and beyond n are dropped
+        const uint32_t wo = ((uint32_t)(kw + orow) * (uint32_t)stride + (uint32_t)ocol) * 2u;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int row = 8 * it + orow;
+          u32x4 w = *reinterpret_cast<const u32x4*>(&slab[row * kPitch + ocol]);
+          if (kw + row >= live) w = u32x4{0u, 0u, 0u, 0u};
+          __builtin_amdgcn_raw_buffer_store_b128(w, wr, wo + (uint32_t)(it * 16) * (uint32_t)stride, 0, kRows ? kNt : 0);
+        }
+        return;
+      }
       uint16_t* oh = out + h * kD + ocol;
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
@@ -787,7 +857,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         if (kw + row >= live) w = u32x4{0u, 0u, 0u, 0u};
         if (kw + row < n) {
           // written into the padded layout these rows are final results of the step: stream them out
-          if (kRows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(U, kw + row) * stride));
+          if (rows) __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(oh + row_of(U, kw + row) * stride));
           else *reinterpret_cast<u32x4*>(oh + row_of(U, kw + row) * stride) = w;
         }
       }
@@ -807,19 +877,25 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     // dK, dV and the K fragments have left their registers: room for the next unit's rows, which travel while
     // dQ is computed and stored (the fences keep the compiler from moving the loads further up, where the
     // registers are still taken)
+    // packed tokens: the next unit's loads go out in four groups between the steps of the dQ loop (with token_rows
+    // the compiler runs out of registers for that: there they go out in one burst, before the loop)
+    const bool spread = more && kMode == kRowsIdentity;
     __builtin_amdgcn_sched_barrier(0);
-    if (more) {
+    if (more && !spread) {
       issue_kv(nxt);
       issue_qgo(nxt);
     }
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    if (wave_active) {   // (queries 32*wave.. exist)
+    {
       f32x16 dqacc[2];
 #pragma unroll
       for (int i = 0; i < 16; ++i) { dqacc[0][i] = 0.f; dqacc[1][i] = 0.f; }
-#pragma unroll 1
-      for (int jb = 0; jb < nblk_k; ++jb) {
+#pragma unroll
+      for (int jb = 0; jb < 4; ++jb) {
+        if (spread) issue_group(nxt, jb);
+        __builtin_amdgcn_sched_barrier(0);
+        if (wave_active && jb < nblk_k)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
           const int krow = 32 * jb + 16 * kk + tr_row;
@@ -832,8 +908,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
             dqacc[db] = mfma32(ak, bs, dqacc[db]);
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      store_rows(dqacc, scale, dq, dqs, n);
+      if (wave_active) store_rows(dqacc, scale, dq, dqs, n);
     }
     if (more) __syncthreads();   // the next unit's phase 0 overwrites sA, sB, sLse and sDelta
   }
@@ -854,8 +931,13 @@ mb_status launch_attn_bwd_mfma(const AttnShape& s, const void* dout, const void*
                      (const uint16_t*)o, lse, dos, qs, ks, vs, os, s.cu_seqlens, s.slopes, s.scale, (uint16_t*)dq, \
                      (uint16_t*)dk, (uint16_t*)dv, dqs, dks, dvs, s.T, s.token_rows, s.misuse, s.key_lens, s.H,    \
                      (int)units)
-    if (s.token_rows) MB_LAUNCH_FUSED(true, 2);
-    else MB_LAUNCH_FUSED(false, 2);
+    // buffer instructions: the 128 rows a unit can have must lie within 2^31 bytes in every tensor
+    int64_t widest = 0;
+    for (const int64_t st : {dos, qs, ks, vs, os, dqs, dks, dvs}) widest = st > widest ? st : widest;
+    const bool narrow = (int64_t)kTile * widest * 2 < ((int64_t)1 << 31);
+    if (!narrow) MB_LAUNCH_FUSED(kRowsPerLane, 2);
+    else if (s.token_rows) MB_LAUNCH_FUSED(kRowsMaybeContiguous, 2);
+    else MB_LAUNCH_FUSED(kRowsIdentity, 2);
 #undef MB_LAUNCH_FUSED
     return check_launch("attn_bwd_fused128_kernel");
   }

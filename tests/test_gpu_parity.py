@@ -613,6 +613,47 @@ def test_bf16_buffers_beyond_four_gigabytes(mb, n, B):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("lengths,L", [([70, 128, 1], 128), ([130, 5], 140)])
+def test_bf16_rows_sixteen_megabytes_apart(mb, lengths, L):
+    """Row strides of 2^23 elements: a sequence's rows no longer lie within 2^31 bytes of its first, so both kernel
+    families must form every row address per lane in 64 bits instead of using 32-bit buffer offsets.  The results
+    are the bits of the same case in dense tensors, which is checked against the oracle."""
+    H, D, stride = 2, 64, 1 << 23
+    print("wide rows lengths=%s" % lengths, flush=True)
+    c = wl.random_attention_case(321, lengths, L, H, D, std=0.5, bf16=True)
+    ref = run_oracle(c, orc.alibi_slopes(H))
+    mask = c["mask"] != 0
+    T = int(mask.sum())
+    dev, bf = "cuda", torch.bfloat16
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lengths)]), dtype=torch.int32, device=dev)
+    slopes = mb.mb_alibi_slopes(H).to(dev)
+    dense = {k: torch.from_numpy(c[k][mask]).to(bf).to(dev) for k in ("q", "k", "v", "do")}   # [T, H, D]
+
+    def wide(src=None):
+        buf = torch.empty(T * stride, dtype=bf, device=dev)
+        view = buf.as_strided((T, H, D), (stride, D, 1))
+        if src is not None:
+            view.copy_(src)
+        return view
+    res = {}
+    for kind in ("dense", "wide"):
+        t = dense if kind == "dense" else {k: wide(x) for k, x in dense.items()}
+        mk = (lambda: torch.empty((T, H, D), dtype=bf, device=dev)) if kind == "dense" else wide
+        o, dq, dk, dv = mk(), mk(), mk(), mk()
+        _, lse = mb.mb_alibi_attn_fwd(t["q"], t["k"], t["v"], cu, L, slopes, c["scale"], out=o)
+        mb.mb_alibi_attn_bwd(t["do"], t["q"], t["k"], t["v"], o, lse, cu, L, slopes, c["scale"], dq=dq, dk=dk, dv=dv)
+        torch.cuda.synchronize()
+        mb.mb_device_status()
+        res[kind] = {"o": o.contiguous(), "dq": dq.contiguous(), "dk": dk.contiguous(), "dv": dv.contiguous(), "lse": lse}
+        del t, o, dq, dk, dv
+        torch.cuda.empty_cache()
+    for key in ("o", "dq", "dk", "dv", "lse"):
+        assert torch.equal(res["dense"][key], res["wide"][key]), key
+    for key in ("o", "dq", "dk", "dv"):
+        ma, rf = err_stats(res["dense"][key].float().cpu().numpy().astype(np.float64), ref[key][mask])
+        assert ma <= BF16_TOL[0] and (rf <= BF16_TOL[1] or ma <= 1e-7), "%s: %.3e %.3e" % (key, ma, rf)
+
+
 def test_unpad_pad_buffers_beyond_four_gigabytes(mb):
     """Gather and scatter on a padded batch of 13.8 GB (3 million rows of 4608 bytes): bit-exact against
     torch's index_select / index_copy, which also checks the index maps of a 3000 x 1000 mask."""
