@@ -27,14 +27,14 @@ MEASURED_COPY_GBS = 6000.0    # what a plain row copy of 1 GiB each way reaches 
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this
 # file (KiB per dispatch), each scaled by what the same counter reads for a plain row copy of known size
-# (--copy-calibration: FETCH_SIZE reads 66060.5 KiB for 131072 KiB copied -> factor 1.984; WRITE_SIZE reads
+# (--copy-calibration: FETCH_SIZE reads 66060.8 KiB for 131072 KiB copied -> factor 1.984; WRITE_SIZE reads
 # 131072.0 KiB -> factor 1.0).  Summaries: profiles/bert_base_attn_hbm_traffic.md.
-COPY_FACTOR_FETCH = 131072.0 / 66060.5
+COPY_FACTOR_FETCH = 131072.0 / 66060.8
 COPY_FACTOR_WRITE = 1.0
 # The counted dispatches are the token_rows variants of the two kernels (same bytes per token, and the only ones that run
 # on exactly this batch's tokens in that command; the packed variants' averages mix in the padded comparison).
 MEASURED_TRAFFIC_KIB = {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE) KiB per dispatch
-    "bert_base": {"attn_bwd_fused128_kernel": (102236.1, 121336.0), "attn_fwd_short_kernel": (60900.0, 41788.2)},
+    "bert_base": {"attn_bwd_fused128_kernel": (102245.6, 121334.1), "attn_fwd_short_kernel": (60901.2, 41788.2)},
 }
 TRAFFIC_SOURCE = ("profiles/bert_base_attn_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
                   "not measured in the run that prints this line")
