@@ -545,7 +545,7 @@ constexpr int kDsPitch = 136;   // LDS row pitch of dS in bf16 (272 B)
 // the step from one group of rows to the next is added (the whole offset must be the vector operand: the scalar
 // offset of a buffer instruction takes no part in its range check).  Rows past the unit's end then read as zeros and
 // are dropped on a store without a compare, and forming an address is one 32-bit add.  (With per-lane 64-bit
-// addresses every row access costs a 64-bit multiply, three quarter-rate vector instructions: a tenth of all vector
+// addresses every row access costs a 64-bit multiply, three quarter-rate vector instructions: a fifth of all vector
 // instructions of this kernel were address arithmetic.)
 // kUnits: (sequence, head) units per workgroup, 1 or 2.
 template <int kMode, int kUnits>
