@@ -252,10 +252,9 @@ __global__ __launch_bounds__(64 * kColsumSlices) void add_layernorm_colsum_kerne
   }
 }
 
-// bf16 rows that split evenly over the 64 lanes in 8-byte pieces (at most 4 each) but not in 16-byte pieces
-bool use_half_pieces(mb_dtype dt, int W) {
-  return dt == MB_BF16 && W % 4 == 0 && (W / 4) % 64 == 0 && W / 4 <= 256 && (W % 8 != 0 || (W / 8) % 64 != 0);
-}
+// bf16 rows that split evenly over the 64 lanes in 8-byte pieces but not in 16-byte pieces: 256 or 768 columns
+// (one or three pieces per lane)
+bool use_half_pieces(mb_dtype dt, int W) { return dt == MB_BF16 && (W == 256 || W == 768); }
 
 int bwd_blocks(int T_cap) { return max(1, min((T_cap + kLnWaves - 1) / kLnWaves, kLayerNormMaxParts)); }
 
@@ -276,10 +275,8 @@ mb_status launch_add_layernorm_fwd(mb_dtype dt, const void* x, const void* r, co
   hipLaunchKernelGGL((add_layernorm_fwd_kernel<uint16_t, P, HalfPiece>), dim3(blocks), dim3(kLnThreads), 0, stream, \
                      (const uint16_t*)x, (const uint16_t*)r, (const uint16_t*)gamma, (const uint16_t*)beta, T_cap, \
                      meta, W, eps, (uint16_t*)y, (uint16_t*)s, mean, rstd, y_rows)
-    if (per_lane == 1) MB_LN_FWD_H(1);
-    else if (per_lane == 2) MB_LN_FWD_H(2);
-    else if (per_lane == 3) MB_LN_FWD_H(3);
-    else MB_LN_FWD_H(4);
+    if (per_lane == 1) MB_LN_FWD_H(1);   // (an even count per lane would also split evenly in 16-byte pieces)
+    else MB_LN_FWD_H(3);
 #undef MB_LN_FWD_H
   } else if (dt == MB_BF16) { if (small) MB_LN_FWD(uint16_t, 2); else MB_LN_FWD(uint16_t, 4); }
   else { if (small) MB_LN_FWD(float, 2); else MB_LN_FWD(float, 4); }

@@ -39,7 +39,7 @@ def dev(a, bf16):
 
 
 @pytest.mark.parametrize("T,W,residual", [(1000, 768, True), (1, 1024, True), (4097, 64, True), (333, 2048, True),
-                                          (517, 768, False), (26963, 768, True)])
+                                          (517, 768, False), (26963, 768, True), (300, 256, True)])
 def test_layernorm_bf16_parity(mb, T, W, residual):
     print("layernorm bf16 T=%d W=%d residual=%s" % (T, W, residual), flush=True)
     x, r, gamma, beta, dy = make(7, T, W)
