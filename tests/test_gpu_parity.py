@@ -526,6 +526,56 @@ def test_plan_built_once_gives_the_same_bits_as_plans_built_per_call(mb, limit_k
     assert torch.equal(o1, o2) and torch.equal(lse1, lse2) and torch.equal(g1, g2)
 
 
+@pytest.mark.parametrize("lengths,L,H,limit_keys", [([300, 0, 129, 128, 513, 64, 1], 513, 3, False),
+                                                     ([700, 20, 256, 255, 257], 700, 12, True),
+                                                     (list(range(1, 41)) * 15, 200, 2, False)])
+def test_work_plan_lists_every_tile_exactly_once(mb, lengths, L, H, limit_keys):
+    """The work plan of the any-length kernels is scheduling, not arithmetic, so what can be checked is that it is
+    VALID: read back, its 8 lists (8 int32 counts, then 8 x cap items of 4 int32: first packed token, length,
+    tile | head << 16, keys) together name every (sequence, head, tile of 128 tokens) that has work exactly once,
+    with the sequence's own start, length and key count; sequences without tokens or without keys are absent;
+    and, for up to 512 sequences (more are taken in the order given), pair p = rank * H + head, ranks longest first,
+    sits in list p % 16 or 15 - p % 16 and inside a list lengths never increase."""
+    B = len(lengths)
+    print("plan B=%d L=%d H=%d limit_keys=%s" % (B, L, H, limit_keys), flush=True)
+    lens = np.asarray(lengths, dtype=np.int64)
+    cu = torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int32, device="cuda")
+    klens_np = np.maximum(lens - np.arange(B) % 3 * 40, 0) if limit_keys else lens
+    klens = torch.tensor(klens_np, dtype=torch.int32, device="cuda") if limit_keys else None
+    plan = mb.mb_attn_plan(cu, L, H, key_lens=klens)
+    torch.cuda.synchronize()
+    mb.mb_device_status()
+    words = plan.view(torch.int32).cpu().numpy()
+    cap = 2 * ((B * H + 15) // 16) * ((L + 127) // 128)   # items a list can hold: the pairs it can get x the most tiles
+    assert 32 + 8 * cap * 16 <= mb.mb_attn_plan_bytes(B, L, H)
+    counts = words[:8]
+    assert np.all(counts >= 0) and np.all(counts <= cap)
+    starts = np.concatenate([[0], np.cumsum(lens)])[:B]
+    expected = {}
+    for b in range(B):
+        if lens[b] > 0 and klens_np[b] > 0:
+            for h in range(H):
+                for t in range((lens[b] + 127) // 128):
+                    expected[(int(starts[b]), h, t)] = (int(lens[b]), int(min(klens_np[b], lens[b])))
+    order = sorted(range(B), key=lambda b: (-lens[b], b))   # longest first, ties by index
+    rank = {b: r for r, b in enumerate(order)}
+    seq_of_start = {int(starts[b]): b for b in range(B) if lens[b] > 0}
+    seen = set()
+    for c in range(8):
+        items = words[8 + c * cap * 4: 8 + (c * cap + int(counts[c])) * 4].reshape(-1, 4)
+        if B <= 512:
+            assert np.all(np.diff(items[:, 1]) <= 0), "list %d is not longest first" % c
+        for start, n, th, nk in items.tolist():
+            key = (start, th >> 16, th & 0xffff)
+            assert key in expected and key not in seen, "list %d: item %s" % (c, key)
+            assert expected[key] == (n, nk)
+            seen.add(key)
+            if B <= 512:
+                pair = rank[seq_of_start[start]] * H + (th >> 16)
+                assert c in (pair % 16, 15 - pair % 16)
+    assert len(seen) == len(expected)
+
+
 def test_bf16_tile_boundary_lengths(mb):
     """Lengths on both sides of every tile boundary of the any-length kernels (32, 64, 128) in one batch."""
     lengths = [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 2, 0]
