@@ -137,7 +137,8 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
                                                                 const int32_t* __restrict__ indices, int T_cap,
                                                                 const int32_t* __restrict__ meta, int rows_padded,
                                                                 int units, uint4* __restrict__ padded) {
-  __shared__ int s_t0;
+  __shared__ int s_t0, s_off;
+  __shared__ int s_v[128];
   const int T = meta ? min(meta[0], T_cap) : T_cap;
   const int p0 = blockIdx.x * kRowsPerBlock;
   if (threadIdx.x < 64) {
@@ -153,9 +154,14 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
       lo = (int)nlo;
       hi = (int)(nhi < hi ? nhi : hi);
     }
-    const bool less = (lo + lane < hi) && (indices[lo + lane] < p0);
-    const int t0 = lo + __popcll(__ballot(less));
-    if (lane == 0) s_t0 = t0;
+    // last probe: two entries per lane (the end of the list counts as +infinity), so that the entries from t0 on,
+    // which say where the block's rows come from, are already here and cost no further round trip
+    const int v0 = lo + lane < T ? indices[lo + lane] : 0x7fffffff;
+    const int v1 = lo + 64 + lane < T ? indices[lo + 64 + lane] : 0x7fffffff;
+    const int t0 = lo + __popcll(__ballot(v0 < p0));   // entries at and beyond hi are >= p0: t0 <= hi <= lo + 64
+    s_v[lane] = v0;
+    s_v[64 + lane] = v1;
+    if (lane == 0) { s_t0 = t0; s_off = t0 - lo; }
   }
   __syncthreads();
   const int t0 = s_t0;
@@ -163,8 +169,12 @@ __global__ __launch_bounds__(kThreads) void scatter_rows_kernel(const uint4* __r
   const int p = p0 + r;
   if (p >= rows_padded) return;
   int c = 0;  // kept rows of this block before row p
-  for (int x = 0; x < kRowsPerBlock; ++x) c += (t0 + x < T && indices[t0 + x] < p) ? 1 : 0;
-  const bool kept = (t0 + c < T) && (indices[t0 + c] == p);
+  bool kept = false;
+  for (int x = 0; x < kRowsPerBlock; ++x) {
+    const int v = s_v[s_off + x];   // indices[t0 + x], +infinity past the end (s_off + x <= 71)
+    c += v < p ? 1 : 0;
+    kept = kept || v == p;
+  }
   uint4* dst = padded + (size_t)p * units;
   const int lane = threadIdx.x % kLanesPerRow;
   if (kept) {
