@@ -520,8 +520,8 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(
 // Whole backward of one (sequence, head) with at most 128 tokens in one workgroup: every input is read
 // from HBM once and every output written once, always as full 128-byte rows shared by 8 lanes; the
 // fragment layouts of the matrix cores are produced by passing through LDS.
-//   phase 0  K, V rows -> LDS -> each wave keeps K^T, V^T fragments of its own 32 keys in registers;
-//            then Q, dO rows -> the same LDS; Delta = rowsum(dO * O) and -lse -> LDS.
+//   phase 0  K, V, Q, dO rows -> LDS (K and V into the dS buffer, which is idle until phase 1), Delta = rowsum(dO * O)
+//            and -lse -> LDS; one barrier; each wave takes the K^T, V^T fragments of its own 32 keys into registers.
 //   phase 1  wave w owns keys 32w..: for every block of 32 queries, S = Q K^T, dP = dO V^T, P, dS in
 //            registers; dV^T += dO^T P, dK^T += Q^T dS; dS (bf16) is also written to LDS as [key][query].
 //   phase 2  dK, dV leave through the (now free) dO tile; the K registers go back to LDS over the Q
@@ -558,9 +558,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
     int32_t* __restrict__ misuse, const int32_t* __restrict__ key_lens, int H, int n_units) {
   constexpr bool kRows = kMode != kRowsIdentity;   // token t may sit at another row than t
   if (kMode == kRowsIdentity) rows = nullptr;
-  __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // K, then Q, then K again
-  __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // V, then dO, then output rows
-  __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // dS as [key][query]
+  __shared__ __attribute__((aligned(16))) uint16_t sA[kTile * kPitch];      // Q, then K
+  __shared__ __attribute__((aligned(16))) uint16_t sB[kTile * kPitch];      // dO, then output rows
+  __shared__ __attribute__((aligned(16))) uint16_t sDs[kTile * kDsPitch];   // K and V rows on their way in, then dS as [key][query]
   __shared__ __attribute__((aligned(16))) float sLse[kTile];                // -lse, base-2 units
   __shared__ __attribute__((aligned(16))) float sDelta[kTile];              // -Delta
 
@@ -705,24 +705,18 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
       // ---- phase 0
       // stored negated: -lse in base-2 units (-inf past the end, which makes P = 0 there)
       if (tid < kTile) sLse[tid] = tid < n ? -lse[(int64_t)h * T + U.start + tid] * kLog2e : -INFINITY;
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        if (it < nblk) {   // rows n..32*nblk-1 are zeros; rows >= 32*nblk are never read
-          *reinterpret_cast<u32x4*>(&sA[(32 * it + st_row) * kPitch + st_col]) = tk[it];
-          *reinterpret_cast<u32x4*>(&sB[(32 * it + st_row) * kPitch + st_col]) = tv[it];
-        }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        bk[s] = lds_read8(&sA[kj * kPitch + 16 * s + 8 * g]);
-        bv[s] = lds_read8(&sB[kj * kPitch + 16 * s + 8 * g]);
-      }
-      __syncthreads();   // K, V have been read by everyone
+      // K and V rows are staged in the dS buffer, which is free until phase 1: the 32 rows of K and of V that wave
+      // `it` will own go into the very part of it that this wave later fills with dS (rows of 128 bytes, the 16-byte
+      // pieces of a row rotated by the row number so that a wave's fragment reads spread over the banks).  A wave thus
+      // overwrites only K/V rows it has already taken into registers, and one barrier serves all four tiles.
 #pragma unroll
       for (int it = 0; it < 4; ++it) {
         const int row = 32 * it + st_row;
-        if (it < nblk) {
+        if (it < nblk) {   // rows n..32*nblk-1 are zeros; rows >= 32*nblk are never read
+          uint16_t* part = &sDs[it * 32 * kDsPitch];
+          const int piece = ((st_col >> 3) ^ (st_row & 7)) * 8;
+          *reinterpret_cast<u32x4*>(&part[st_row * 64 + piece]) = tk[it];
+          *reinterpret_cast<u32x4*>(&part[2048 + st_row * 64 + piece]) = tv[it];
           *reinterpret_cast<u32x4*>(&sA[row * kPitch + st_col]) = tq[it];
           *reinterpret_cast<u32x4*>(&sB[row * kPitch + st_col]) = tg[it];
         }
@@ -738,6 +732,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_fused128_kernel(
         if ((tid & 7) == 0) sDelta[row] = -acc;
       }
       __syncthreads();
+      {
+        const uint16_t* part = &sDs[wave * 32 * kDsPitch];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int piece = ((2 * s + g) ^ (c & 7)) * 8;
+          bk[s] = lds_read8(&part[c * 64 + piece]);
+          bv[s] = lds_read8(&part[2048 + c * 64 + piece]);
+        }
+      }
     }
     if (n <= 0) {
       if (more) {
